@@ -1,0 +1,186 @@
+/*
+ * alcop.h - C ABI of the MI355X (gfx950) load-compute-pipelined tensor kernels.
+ *
+ * The library implements the tiled main loop that the ALCOP paper (arXiv 2210.16691)
+ * pipelines, for the three operators the paper names as pipelinable (Sec. 6.2: MatMul,
+ * batched MatMul, Conv2D; half-precision inputs on the matrix cores, Sec. 6.1):
+ *
+ *   - tiles of A and B travel HBM -> LDS through an S-slot circular buffer filled by
+ *     asynchronous direct-to-LDS loads (Sec. 4.2, transformation steps 1-5: buffer
+ *     expansion, index shift by S-1, slot = iteration mod S, prologue of S-1 loads,
+ *     producer/consumer synchronisation);
+ *   - fragments travel LDS -> registers through an R-slot register buffer (multi-level
+ *     pipelining, Fig. 3(c));
+ *   - with fuse_inner the register pipeline is one pipeline over all (ko, ki) steps: the
+ *     first fragment of tile ko+1 is fetched during the last step of tile ko (inner-pipeline
+ *     fusion, Fig. 3(d) and Sec. 4.1 step 5);
+ *   - a static latency model ranks schedules without running them and a tuner times only the
+ *     best-ranked ones (Sec. 5, Table 1 and Sec. 5.3).
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never
+ *     allocates, frees or copies device memory.  Host pointers are marked "host".
+ *   - Calls enqueue work on the given HIP stream (a hipStream_t passed as void*; NULL is the
+ *     default stream) and return without synchronising.  alcop_tune is the one exception:
+ *     it synchronises the stream in order to time its trials.
+ *   - Return value: ALCOP_OK (0) or a negative alcop_status.  Nothing is launched when an
+ *     error is returned.  No entry point throws or aborts.
+ *   - Element types: inputs are IEEE binary16 (ALCOP_F16) or bfloat16 (ALCOP_BF16); products
+ *     are accumulated in fp32 on the matrix cores in a fixed order (ko ascending, ki
+ *     ascending), so for a fixed tile shape the result does not depend on stages,
+ *     reg_stages or fuse_inner.  The output is the fp32 accumulator converted with
+ *     round-to-nearest-even to ALCOP_F16 / ALCOP_BF16, or stored as is (ALCOP_F32).
+ *   - Alignment: every tensor base pointer is 16-byte aligned; leading dimensions and batch
+ *     strides are multiples of 8 elements.
+ *   - Shapes: K must be a multiple of the schedule's bk; N a multiple of 8; M is free
+ *     (edge tiles in M and N are loaded with zero fill and stored under a mask).  Each
+ *     operand of one GEMM (one batch entry) must span less than 2 GiB.
+ */
+#ifndef ALCOP_H
+#define ALCOP_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { ALCOP_F16 = 0, ALCOP_BF16 = 1, ALCOP_F32 = 2 /* output only */ } alcop_dtype;
+
+typedef enum {
+  ALCOP_OK = 0,
+  ALCOP_ERR_NULL = -1,        /* a required pointer is NULL                                  */
+  ALCOP_ERR_DTYPE = -2,       /* unsupported input / output element type                     */
+  ALCOP_ERR_ALIGN = -3,       /* pointer, leading dimension or stride not aligned as stated  */
+  ALCOP_ERR_SHAPE = -4,       /* non-positive size, K not a multiple of bk, N not of 8, ...  */
+  ALCOP_ERR_SCHED = -5,       /* schedule infeasible: no such kernel, LDS or wait-counter    */
+                              /* limit exceeded, fuse_inner without reg_stages=2/stages>=2   */
+  ALCOP_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch                          */
+  ALCOP_ERR_UNSUPPORTED = -7, /* valid request outside what is built (e.g. transA)           */
+  ALCOP_ERR_SIZE = -8         /* an operand spans 2 GiB or more                              */
+} alcop_status;
+
+/*
+ * Schedule parameters: the knobs the paper's tuner searches (tile sizes and per-buffer
+ * stage counts, Sec. 4.1 step 1 and Sec. 6.1).  A NULL schedule pointer, or bm == 0, asks
+ * the library to pick: the entry with the lowest predicted latency under the static model
+ * among the feasible built kernels.
+ */
+typedef struct {
+  int bm, bn, bk;     /* block tile of C (bm x bn) and reduction step bk                    */
+  int wm, wn;         /* per-wavefront tile; the block runs (bm/wm)*(bn/wn) wavefronts      */
+  int stages;         /* S: LDS ring depth, 1..4; 1 = load and use strictly alternate       */
+  int reg_stages;     /* R: 1 = fragment loaded then used; 2 = next fragment prefetched     */
+  int fuse_inner;     /* 1 = register pipeline runs across ko (needs R=2 and S>=2)          */
+  int raster;         /* block -> tile order: 0 row-major, 1 XCD-grouped panels             */
+} alcop_sched;
+
+/* Problem description used by the model / tuner / feasibility entry points. */
+typedef enum { ALCOP_OP_GEMM = 0, ALCOP_OP_BMM = 1, ALCOP_OP_CONV2D = 2 } alcop_op;
+typedef struct {
+  alcop_op op;
+  int batch;          /* 1 for GEMM and conv                                                */
+  int M, N, K;        /* GEMM view; for conv M = N_img*P*Q, N = K_out, K = R*S*C           */
+  int transB;         /* 1: B stored N x K (K contiguous)                                   */
+  alcop_dtype in, out;
+  int conv_C;         /* conv only: input channels (bk must divide it)                      */
+} alcop_problem;
+
+/*
+ * C[M,N] = A[M,K] . B[K,N]        (paper Sec. 6.1 "MatMul")
+ *   A: row-major M x K, leading dimension lda (elements).  transA must be 0.
+ *   B: transB == 0: row-major K x N, ldb >= N;  transB == 1: stored N x K, ldb >= K.
+ *   C: row-major M x N, ldc >= N, element type `out`.
+ */
+int alcop_gemm(const void* A, const void* B, void* C, int M, int N, int K,
+               long lda, long ldb, long ldc, int transA, int transB,
+               alcop_dtype in, alcop_dtype out, const alcop_sched* sched /* host */,
+               void* hip_stream);
+
+/*
+ * Batched matmul (paper Sec. 6.1 "BMM"; attention Q.K^T uses transB = 1, P.V transB = 0).
+ * Batch entry b uses A + b*strideA, B + b*strideB, C + b*strideC (strides in elements).
+ */
+int alcop_bmm(const void* A, const void* B, void* C, int batch, int M, int N, int K,
+              long lda, long ldb, long ldc, long strideA, long strideB, long strideC,
+              int transA, int transB, alcop_dtype in, alcop_dtype out,
+              const alcop_sched* sched /* host */, void* hip_stream);
+
+/*
+ * 2-D convolution as an implicit GEMM (paper Sec. 6.2 "Conv2D": its reduction loop over
+ * (r, s, c) is a sequential load-and-use loop in the sense of Sec. 3.1, rule 2).
+ *   x: NHWC  [N][H][W][C];  w: RSCK [R][S][C][K];  y: NPQK [N][P][Q][K],
+ *   P = (H + 2*pad_h - R)/stride_h + 1, Q likewise.  Cross-correlation, zero padding,
+ *   dilation 1, one group.  GEMM view: M = N*P*Q, N = K, reduction = R*S*C in (r,s,c) order.
+ *   C must be a multiple of the schedule's bk; K a multiple of 8; x must span < 2 GiB.
+ */
+int alcop_conv2d_igemm(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                       int K, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
+                       alcop_dtype in, alcop_dtype out, const alcop_sched* sched /* host */,
+                       void* hip_stream);
+
+/*
+ * Feasibility of a schedule for a problem, without launching (the checks the paper's
+ * schedule rules and "compile fail" marks stand for, Sec. 3.1 and Fig. 9): a kernel with
+ * these parameters is built; the LDS ring fits 160 KB; the outstanding-load count
+ * (S-2)*loads_per_stage fits the 6-bit vector-memory counter; fuse_inner implies R=2, S>=2;
+ * bk divides K (and C for conv).  Returns ALCOP_OK or the error a launch would return.
+ */
+int alcop_sched_supported(const alcop_problem* prob /* host */, const alcop_sched* sched /* host */);
+
+/*
+ * The schedule space: every kernel built into the library that matches the problem's
+ * dtype / layout / operator, whether or not it is feasible for the shape.
+ * Writes at most `cap` entries to out (host) and returns the total count.
+ */
+int alcop_sched_space(const alcop_problem* prob /* host */, alcop_sched* out /* host */, int cap);
+
+/*
+ * Static latency model (paper Sec. 5, Table 1): predicted kernel time in microseconds and,
+ * optionally, its terms.  terms (host, may be NULL) receives 8 doubles:
+ *   [0] T_kernel  [1] T_threadblk  [2] T_init  [3] T_main_loop  [4] T_epilogue
+ *   [5] T_smem_load  [6] T_smem_use  [7] N_threadblk_batch
+ * model: 0 = the paper's pipeline-aware model; 1 = the bottleneck-only model it is compared
+ * against in Sec. 6.4 (max of compute, LDS traffic and DRAM traffic at full rate).
+ */
+int alcop_model_predict(const alcop_problem* prob /* host */, const alcop_sched* sched /* host */,
+                        int model, double* predicted_us /* host */, double* terms /* host */);
+
+/*
+ * Model-ranked tuning (paper Sec. 5.3 "Analytical-only": rank all schedules by predicted
+ * latency and measure the best-ranked ones).  Runs on the caller's buffers (contents of C
+ * are overwritten), synchronises the stream, times each trial with HIP events.
+ *   top_k > 0: time the top_k feasible schedules by predicted latency; top_k == 0: time all
+ *   feasible schedules (exhaustive / grid search, the 100 % reference of Sec. 6.4).
+ *   model: as in alcop_model_predict.
+ *   For conv problems pass x as A, w as B, y as C and the geometry in `conv` (host; 11 ints:
+ *   N,H,W,C,K,R,S,stride_h,stride_w,pad_h,pad_w), else conv = NULL and lda/ldb/ldc/strides
+ *   as for alcop_bmm (batch 1 for GEMM).
+ *   Outputs (host): best schedule and its time; number of timed trials; size of the feasible
+ *   space; optional log arrays (may be NULL) of capacity log_cap receiving, in rank order,
+ *   each timed schedule, its predicted and measured microseconds.
+ */
+int alcop_tune(const alcop_problem* prob /* host */, const void* A, const void* B, void* C,
+               long lda, long ldb, long ldc, long strideA, long strideB, long strideC,
+               const int* conv /* host */, int top_k, int model, int iters,
+               alcop_sched* best /* host */, double* best_us /* host */,
+               int* trials_run /* host */, int* space_size /* host */,
+               alcop_sched* log_sched /* host */, double* log_pred_us /* host */,
+               double* log_meas_us /* host */, int log_cap, void* hip_stream);
+
+/* Times `iters` back-to-back launches of one schedule with HIP events on the given stream
+ * (after `warmup` untimed ones); writes the mean microseconds per launch.  Same operand
+ * conventions as alcop_tune.  Synchronises the stream. */
+int alcop_time(const alcop_problem* prob /* host */, const void* A, const void* B, void* C,
+               long lda, long ldb, long ldc, long strideA, long strideB, long strideC,
+               const int* conv /* host */, const alcop_sched* sched /* host */,
+               int warmup, int iters, double* mean_us /* host */, void* hip_stream);
+
+/* Static string for a status code. */
+const char* alcop_strerror(int code);
+
+/* Library version, and the GPU architecture string it was compiled for ("gfx950"). */
+const char* alcop_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALCOP_H */

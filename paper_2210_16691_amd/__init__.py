@@ -1,0 +1,231 @@
+"""MI355X-native load-compute-pipelined GEMM / BMM / implicit-GEMM conv2d (ALCOP, arXiv 2210.16691).
+
+Thin ctypes binding over ``libalcop.so`` (C ABI declared in ``include/alcop.h``).  Argument
+marshalling only: every step of the hot path runs in the HIP kernels.  PyTorch is used for device
+memory and streams.  There is no CPU fallback: if the shared library is missing, importing the
+binding's functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libalcop.so")
+
+F16, BF16, F32 = 0, 1, 2
+OP_GEMM, OP_BMM, OP_CONV2D = 0, 1, 2
+
+OK = 0
+ERR_NULL, ERR_DTYPE, ERR_ALIGN, ERR_SHAPE, ERR_SCHED, ERR_LAUNCH, ERR_UNSUPPORTED, ERR_SIZE = (
+    -1, -2, -3, -4, -5, -6, -7, -8)
+
+EXPORTS = [
+    "alcop_gemm", "alcop_bmm", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
+    "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
+]
+
+
+class AlcopError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__("%s failed: %s (%d)" % (what, strerror(code), code))
+        self.code = code
+
+
+class Sched(ctypes.Structure):
+    """Mirror of ``alcop_sched``."""
+    _fields_ = [(n, ctypes.c_int) for n in
+                ("bm", "bn", "bk", "wm", "wn", "stages", "reg_stages", "fuse_inner", "raster")]
+
+    def key(self):
+        return tuple(getattr(self, n) for n, _ in self._fields_)
+
+    def __repr__(self):
+        return "Sched(%dx%dx%d w%dx%d S%d R%d F%d r%d)" % self.key()
+
+
+def sched(bm, bn, bk, wm, wn, stages=1, reg_stages=1, fuse_inner=0, raster=1) -> Sched:
+    return Sched(bm, bn, bk, wm, wn, stages, reg_stages, fuse_inner, raster)
+
+
+class Problem(ctypes.Structure):
+    """Mirror of ``alcop_problem``."""
+    _fields_ = [("op", ctypes.c_int), ("batch", ctypes.c_int), ("M", ctypes.c_int),
+                ("N", ctypes.c_int), ("K", ctypes.c_int), ("transB", ctypes.c_int),
+                ("in_", ctypes.c_int), ("out", ctypes.c_int), ("conv_C", ctypes.c_int)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libalcop.so (built by ``python -m paper_2210_16691_amd.build``); fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libalcop.so is not built: run `python -m paper_2210_16691_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, l = ctypes.c_void_p, ctypes.c_int, ctypes.c_long
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int)
+        sp = ctypes.POINTER(Sched)
+        pp = ctypes.POINTER(Problem)
+        L.alcop_gemm.restype = i
+        L.alcop_gemm.argtypes = [vp, vp, vp, i, i, i, l, l, l, i, i, i, i, sp, vp]
+        L.alcop_bmm.restype = i
+        L.alcop_bmm.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, sp, vp]
+        L.alcop_conv2d_igemm.restype = i
+        L.alcop_conv2d_igemm.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, vp]
+        L.alcop_sched_supported.restype = i
+        L.alcop_sched_supported.argtypes = [pp, sp]
+        L.alcop_sched_space.restype = i
+        L.alcop_sched_space.argtypes = [pp, sp, i]
+        L.alcop_model_predict.restype = i
+        L.alcop_model_predict.argtypes = [pp, sp, i, dp, dp]
+        L.alcop_tune.restype = i
+        L.alcop_tune.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, i, i, i, sp, dp, ip, ip,
+                                 sp, dp, dp, i, vp]
+        L.alcop_time.restype = i
+        L.alcop_time.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, sp, i, i, dp, vp]
+        L.alcop_strerror.restype = ctypes.c_char_p
+        L.alcop_strerror.argtypes = [i]
+        L.alcop_version.restype = ctypes.c_char_p
+        L.alcop_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().alcop_strerror(int(code)).decode()
+
+
+def version() -> str:
+    return lib().alcop_version().decode()
+
+
+# ---- marshalling helpers ---------------------------------------------------------------------
+def _dtype_code(t) -> int:
+    import torch
+    return {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}[t.dtype]
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _sp(s):
+    return ctypes.byref(s) if s is not None else None
+
+
+def _check(rc, what):
+    if rc != OK:
+        raise AlcopError(rc, what)
+
+
+# ---- the entry points (same names as the C ABI) ----------------------------------------------
+def alcop_gemm(A, B, C, sched=None, transB=False, stream=None):
+    """C[M,N] = A[M,K] . B  (B is [K,N], or [N,K] if transB).  Tensors are 2-D CUDA tensors whose
+    last dimension is contiguous; C's dtype selects the output type."""
+    M, K = A.shape
+    N = B.shape[0] if transB else B.shape[1]
+    rc = lib().alcop_gemm(_ptr(A), _ptr(B), _ptr(C), M, N, K, A.stride(0), B.stride(0), C.stride(0),
+                          0, int(transB), _dtype_code(A), _dtype_code(C), _sp(sched), _stream(stream))
+    _check(rc, "alcop_gemm")
+    return C
+
+
+def alcop_bmm(A, B, C, sched=None, transB=False, stream=None):
+    """Batched: A [b,M,K], B [b,K,N] (or [b,N,K] if transB), C [b,M,N]."""
+    b, M, K = A.shape
+    N = B.shape[1] if transB else B.shape[2]
+    rc = lib().alcop_bmm(_ptr(A), _ptr(B), _ptr(C), b, M, N, K, A.stride(1), B.stride(1), C.stride(1),
+                         A.stride(0), B.stride(0), C.stride(0), 0, int(transB),
+                         _dtype_code(A), _dtype_code(C), _sp(sched), _stream(stream))
+    _check(rc, "alcop_bmm")
+    return C
+
+
+def alcop_conv2d_igemm(x, w, y, stride=(1, 1), pad=(0, 0), sched=None, stream=None):
+    """x NHWC [N,H,W,C], w RSCK [R,S,C,K], y NPQK [N,P,Q,K]; all contiguous."""
+    N, H, W, Cc = x.shape
+    R, S, _, K = w.shape
+    rc = lib().alcop_conv2d_igemm(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cc, K, R, S,
+                                  stride[0], stride[1], pad[0], pad[1],
+                                  _dtype_code(x), _dtype_code(y), _sp(sched), _stream(stream))
+    _check(rc, "alcop_conv2d_igemm")
+    return y
+
+
+def problem(op, M, N, K, in_dtype, out_dtype, batch=1, transB=False, conv_C=0) -> Problem:
+    return Problem(op, batch, M, N, K, int(transB), in_dtype, out_dtype, conv_C)
+
+
+def alcop_sched_supported(prob: Problem, s: Sched) -> int:
+    return lib().alcop_sched_supported(ctypes.byref(prob), ctypes.byref(s))
+
+
+def alcop_sched_space(prob: Problem):
+    n = lib().alcop_sched_space(ctypes.byref(prob), None, 0)
+    arr = (Sched * max(n, 1))()
+    lib().alcop_sched_space(ctypes.byref(prob), arr, n)
+    return [Sched(*arr[i].key()) for i in range(n)]
+
+
+def alcop_model_predict(prob: Problem, s: Sched, model: int = 0):
+    """Returns (predicted_us, terms[8])."""
+    us = ctypes.c_double()
+    terms = (ctypes.c_double * 8)()
+    rc = lib().alcop_model_predict(ctypes.byref(prob), ctypes.byref(s), model, ctypes.byref(us), terms)
+    _check(rc, "alcop_model_predict")
+    return us.value, list(terms)
+
+
+@dataclass
+class TuneResult:
+    best: Sched
+    best_us: float
+    trials: int
+    space: int
+    log: list   # [(Sched, predicted_us, measured_us)] in rank order
+
+
+def _operands(prob, A, B, C, conv):
+    if prob.op == OP_CONV2D:
+        cv = (ctypes.c_int * 11)(*conv)
+        return cv, (0, 0, 0, 0, 0, 0)
+    if prob.op == OP_BMM:
+        return None, (A.stride(1), B.stride(1), C.stride(1), A.stride(0), B.stride(0), C.stride(0))
+    return None, (A.stride(0), B.stride(0), C.stride(0), 0, 0, 0)
+
+
+def alcop_tune(prob: Problem, A, B, C, top_k=10, model=0, iters=20, conv=None, stream=None) -> TuneResult:
+    """Model-ranked tuning on the caller's tensors (C is overwritten). top_k=0: exhaustive."""
+    cv, ld = _operands(prob, A, B, C, conv)
+    cap = max(1, lib().alcop_sched_space(ctypes.byref(prob), None, 0))
+    best, best_us = Sched(), ctypes.c_double()
+    trials, space = ctypes.c_int(), ctypes.c_int()
+    ls, lp, lm = (Sched * cap)(), (ctypes.c_double * cap)(), (ctypes.c_double * cap)()
+    rc = lib().alcop_tune(ctypes.byref(prob), _ptr(A), _ptr(B), _ptr(C), *ld, cv, top_k, model, iters,
+                          ctypes.byref(best), ctypes.byref(best_us), ctypes.byref(trials),
+                          ctypes.byref(space), ls, lp, lm, cap, _stream(stream))
+    _check(rc, "alcop_tune")
+    log = [(Sched(*ls[i].key()), lp[i], lm[i]) for i in range(trials.value)]
+    return TuneResult(Sched(*best.key()), best_us.value, trials.value, space.value, log)
+
+
+def alcop_time(prob: Problem, A, B, C, s: Sched, warmup=3, iters=20, conv=None, stream=None) -> float:
+    """Mean microseconds per launch of one schedule, timed with HIP events on the stream."""
+    cv, ld = _operands(prob, A, B, C, conv)
+    us = ctypes.c_double()
+    rc = lib().alcop_time(ctypes.byref(prob), _ptr(A), _ptr(B), _ptr(C), *ld, cv, ctypes.byref(s),
+                          warmup, iters, ctypes.byref(us), _stream(stream))
+    _check(rc, "alcop_time")
+    return us.value

@@ -1,0 +1,530 @@
+// C ABI of the library: argument validation, schedule lookup, launch, timing and the
+// model-ranked tuner.  Declarations and argument contracts are in include/alcop.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <tuple>
+#include <vector>
+
+#include "../../include/alcop.h"
+#include "alcop_model.h"
+#include "alcop_registry.h"
+
+namespace alcop {
+
+const std::vector<KernelEntry>& registry()
+{
+  static const std::vector<KernelEntry> table = [] {
+    std::vector<KernelEntry> t;
+    register_f16_kn_big(t);
+    register_f16_kn_mid(t);
+    register_f16_kn_small(t);
+    register_bf16_kn(t);
+    register_nk(t);
+    register_conv(t);
+    return t;
+  }();
+  return table;
+}
+
+namespace {
+
+struct Call {
+  alcop_op op;
+  const void *A, *B;
+  void* C;
+  int batch, M, N, K;
+  long lda, ldb, ldc, strideA, strideB, strideC;
+  int transB;
+  alcop_dtype in, out;
+  // conv geometry
+  int cN, cH, cW, cC, cK, cR, cS, csh, csw, cph, cpw, cP, cQ;
+};
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+alcop_problem problem_of(const Call& c)
+{
+  alcop_problem p;
+  p.op = c.op;
+  p.batch = c.batch;
+  p.M = c.M;
+  p.N = c.N;
+  p.K = c.K;
+  p.transB = c.transB;
+  p.in = c.in;
+  p.out = c.out;
+  p.conv_C = c.op == ALCOP_OP_CONV2D ? c.cC : 0;
+  return p;
+}
+
+const KernelEntry* find_entry(const alcop_problem& p, const alcop_sched& s)
+{
+  const int am = p.op == ALCOP_OP_CONV2D ? 1 : 0;
+  for (const KernelEntry& e : registry())
+    if (e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.am == am && e.bm == s.bm &&
+        e.bn == s.bn && e.bk == s.bk && e.wm == s.wm && e.wn == s.wn && e.stages == s.stages &&
+        e.reg_stages == s.reg_stages && e.fuse == (s.fuse_inner ? 1 : 0))
+      return &e;
+  return nullptr;
+}
+
+int check_problem(const alcop_problem& p)
+{
+  if (p.in != ALCOP_F16 && p.in != ALCOP_BF16) return ALCOP_ERR_DTYPE;
+  if (p.out != ALCOP_F16 && p.out != ALCOP_BF16 && p.out != ALCOP_F32) return ALCOP_ERR_DTYPE;
+  if (p.op != ALCOP_OP_GEMM && p.op != ALCOP_OP_BMM && p.op != ALCOP_OP_CONV2D)
+    return ALCOP_ERR_UNSUPPORTED;
+  if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.batch <= 0 || p.batch > 65535) return ALCOP_ERR_SHAPE;
+  if (p.N % 8 != 0 || p.K % 8 != 0) return ALCOP_ERR_SHAPE;
+  if (p.op == ALCOP_OP_CONV2D && (p.transB || p.conv_C <= 0 || p.K % p.conv_C != 0))
+    return ALCOP_ERR_SHAPE;
+  return ALCOP_OK;
+}
+
+// Feasibility of a schedule for a problem (no pointers involved).
+int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry** out)
+{
+  int rc = check_problem(p);
+  if (rc) return rc;
+  if (s.stages < 1 || s.stages > 4 || s.reg_stages < 1 || s.reg_stages > 2) return ALCOP_ERR_SCHED;
+  if (s.fuse_inner && (s.reg_stages != 2 || s.stages < 2)) return ALCOP_ERR_SCHED;
+  if (s.raster != 0 && s.raster != 1) return ALCOP_ERR_SCHED;
+  const KernelEntry* e = find_entry(p, s);
+  if (!e) return ALCOP_ERR_SCHED;
+  if (e->lds_bytes > 160 * 1024) return ALCOP_ERR_SCHED;
+  if (e->stages >= 2 && (e->stages - 2) * e->loads_per_stage > 63) return ALCOP_ERR_SCHED;
+  if (p.K % s.bk != 0) return ALCOP_ERR_SHAPE;
+  if (p.op == ALCOP_OP_CONV2D && p.conv_C % s.bk != 0) return ALCOP_ERR_SHAPE;
+  const long ntm = (p.M + s.bm - 1) / s.bm, ntn = (p.N + s.bn - 1) / s.bn;
+  if (ntm * ntn > 0x7fffffffL) return ALCOP_ERR_SHAPE;
+  if (out) *out = e;
+  return ALCOP_OK;
+}
+
+std::vector<alcop_sched> space_of(const alcop_problem& p)
+{
+  std::vector<alcop_sched> v;
+  const int am = p.op == ALCOP_OP_CONV2D ? 1 : 0;
+  for (const KernelEntry& e : registry())
+    if (e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.am == am)
+      v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1});
+  return v;
+}
+
+using CacheKey = std::tuple<int, int, int, int, int, int, int, int, int>;
+std::mutex g_cache_mu;
+std::map<CacheKey, alcop_sched> g_cache;   // problem -> chosen schedule (tuned or model top-1)
+
+CacheKey key_of(const alcop_problem& p)
+{
+  return CacheKey{(int)p.op, p.batch, p.M, p.N, p.K, p.transB, (int)p.in, (int)p.out, p.conv_C};
+}
+
+// Model's top-1 among the feasible schedules (used when the caller passes no schedule).
+int auto_sched(const alcop_problem& p, alcop_sched* out)
+{
+  {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    auto it = g_cache.find(key_of(p));
+    if (it != g_cache.end()) {
+      *out = it->second;
+      return ALCOP_OK;
+    }
+  }
+  const Device dev;
+  double best = 0;
+  bool have = false;
+  for (const alcop_sched& s : space_of(p)) {
+    if (check_sched(p, s, nullptr) != ALCOP_OK) continue;
+    const double t = predict(p, s, 0, dev, nullptr);
+    if (!have || t < best) {
+      best = t;
+      *out = s;
+      have = true;
+    }
+  }
+  if (!have) return ALCOP_ERR_SCHED;
+  std::lock_guard<std::mutex> lk(g_cache_mu);
+  g_cache[key_of(p)] = *out;
+  return ALCOP_OK;
+}
+
+int check_call(const Call& c)
+{
+  if (!c.A || !c.B || !c.C) return ALCOP_ERR_NULL;
+  int rc = check_problem(problem_of(c));
+  if (rc) return rc;
+  if (!aligned16(c.A) || !aligned16(c.B) || !aligned16(c.C)) return ALCOP_ERR_ALIGN;
+  if (c.op == ALCOP_OP_CONV2D) {
+    if (c.cR <= 0 || c.cS <= 0 || c.csh <= 0 || c.csw <= 0 || c.cph < 0 || c.cpw < 0 ||
+        c.cP <= 0 || c.cQ <= 0 || c.cC % 8 != 0)
+      return ALCOP_ERR_SHAPE;
+    const double xbytes = 2.0 * c.cN * c.cH * c.cW * c.cC;
+    if (xbytes >= 2147483648.0) return ALCOP_ERR_SIZE;
+    return ALCOP_OK;
+  }
+  if ((c.lda | c.ldb | c.ldc) & 7) return ALCOP_ERR_ALIGN;
+  if (c.batch > 1 && ((c.strideA | c.strideB | c.strideC) & 7)) return ALCOP_ERR_ALIGN;
+  if (c.lda < c.K || c.ldb < (c.transB ? c.K : c.N) || c.ldc < c.N) return ALCOP_ERR_SHAPE;
+  if (c.lda >= (1L << 30) || c.ldb >= (1L << 30) || c.ldc >= (1L << 30)) return ALCOP_ERR_SIZE;
+  return ALCOP_OK;
+}
+
+int span_check(const Call& c, const alcop_sched& s)
+{
+  if (c.op == ALCOP_OP_CONV2D) {
+    if (2.0 * ((double)(c.K - 1) * c.N + c.N) >= 2147483648.0) return ALCOP_ERR_SIZE;
+    return ALCOP_OK;
+  }
+  const double rows = std::min(s.bm, c.M), cols = std::min(s.bn, c.N);
+  const double a = 2.0 * ((rows - 1) * c.lda + c.K);
+  const double b = c.transB ? 2.0 * ((cols - 1) * c.ldb + c.K) : 2.0 * ((double)(c.K - 1) * c.ldb + cols);
+  if (a >= 2147483648.0 || b >= 2147483648.0) return ALCOP_ERR_SIZE;
+  return ALCOP_OK;
+}
+
+int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipStream_t st)
+{
+  Params p;
+  std::memset(&p, 0, sizeof(p));
+  p.A = c.A;
+  p.B = c.B;
+  p.C = c.C;
+  p.M = c.M;
+  p.N = c.N;
+  p.K = c.K;
+  p.lda = (int)c.lda;
+  p.ldb = (int)c.ldb;
+  p.ldc = (int)c.ldc;
+  p.strideA = c.strideA;
+  p.strideB = c.strideB;
+  p.strideC = c.strideC;
+  p.out_dtype = (int)c.out;
+  p.ntm = (c.M + s.bm - 1) / s.bm;
+  p.ntn = (c.N + s.bn - 1) / s.bn;
+  p.raster = s.raster;
+  p.group_m = std::min(8, p.ntm);
+  if (c.op == ALCOP_OP_CONV2D) {
+    p.cH = c.cH;
+    p.cW = c.cW;
+    p.cC = c.cC;
+    p.cP = c.cP;
+    p.cQ = c.cQ;
+    p.cS = c.cS;
+    p.csh = c.csh;
+    p.csw = c.csw;
+    p.cph = c.cph;
+    p.cpw = c.cpw;
+    p.a_span = (unsigned)(2L * c.cN * c.cH * c.cW * c.cC);
+  }
+  dim3 grid((unsigned)(p.ntm * p.ntn), (unsigned)c.batch, 1);
+  hipError_t err = e->launch(p, grid, st);
+  return err == hipSuccess ? ALCOP_OK : ALCOP_ERR_LAUNCH;
+}
+
+int run(const Call& c, const alcop_sched* sched, void* stream)
+{
+  int rc = check_call(c);
+  if (rc) return rc;
+  const alcop_problem prob = problem_of(c);
+  alcop_sched s;
+  if (!sched || sched->bm == 0) {
+    rc = auto_sched(prob, &s);
+    if (rc) return rc;
+  } else {
+    s = *sched;
+  }
+  const KernelEntry* e = nullptr;
+  rc = check_sched(prob, s, &e);
+  if (rc) return rc;
+  rc = span_check(c, s);
+  if (rc) return rc;
+  return launch_call(c, s, e, (hipStream_t)stream);
+}
+
+Call gemm_call(alcop_op op, const void* A, const void* B, void* C, int batch, int M, int N, int K,
+               long lda, long ldb, long ldc, long sA, long sB, long sC, int transB,
+               alcop_dtype in, alcop_dtype out)
+{
+  Call c;
+  std::memset(&c, 0, sizeof(c));
+  c.op = op;
+  c.A = A;
+  c.B = B;
+  c.C = C;
+  c.batch = batch;
+  c.M = M;
+  c.N = N;
+  c.K = K;
+  c.lda = lda;
+  c.ldb = ldb;
+  c.ldc = ldc;
+  c.strideA = sA;
+  c.strideB = sB;
+  c.strideC = sC;
+  c.transB = transB ? 1 : 0;
+  c.in = in;
+  c.out = out;
+  return c;
+}
+
+int conv_call(Call* c, const void* x, const void* w, void* y, int N, int H, int W, int Cc, int K,
+              int R, int S, int sh, int sw, int ph, int pw, alcop_dtype in, alcop_dtype out)
+{
+  std::memset(c, 0, sizeof(*c));
+  if (N <= 0 || H <= 0 || W <= 0 || Cc <= 0 || K <= 0 || R <= 0 || S <= 0 || sh <= 0 || sw <= 0 ||
+      ph < 0 || pw < 0)
+    return ALCOP_ERR_SHAPE;
+  if (H + 2 * ph < R || W + 2 * pw < S) return ALCOP_ERR_SHAPE;
+  const long P = (H + 2 * ph - R) / sh + 1, Q = (W + 2 * pw - S) / sw + 1;
+  const long Mg = (long)N * P * Q, Kg = (long)R * S * Cc;
+  if (Mg > 0x7fffffffL || Kg > 0x7fffffffL) return ALCOP_ERR_SHAPE;
+  c->op = ALCOP_OP_CONV2D;
+  c->A = x;
+  c->B = w;
+  c->C = y;
+  c->batch = 1;
+  c->M = (int)Mg;
+  c->N = K;
+  c->K = (int)Kg;
+  c->lda = Kg;
+  c->ldb = K;
+  c->ldc = K;
+  c->transB = 0;
+  c->in = in;
+  c->out = out;
+  c->cN = N;
+  c->cH = H;
+  c->cW = W;
+  c->cC = Cc;
+  c->cK = K;
+  c->cR = R;
+  c->cS = S;
+  c->csh = sh;
+  c->csw = sw;
+  c->cph = ph;
+  c->cpw = pw;
+  c->cP = (int)P;
+  c->cQ = (int)Q;
+  return ALCOP_OK;
+}
+
+// Builds the Call of a model/tuner-style request (problem + operand pointers).
+int call_of_problem(const alcop_problem* prob, const void* A, const void* B, void* C, long lda,
+                    long ldb, long ldc, long sA, long sB, long sC, const int* conv, Call* out)
+{
+  if (!prob) return ALCOP_ERR_NULL;
+  if (prob->op == ALCOP_OP_CONV2D) {
+    if (!conv) return ALCOP_ERR_NULL;
+    int rc = conv_call(out, A, B, C, conv[0], conv[1], conv[2], conv[3], conv[4], conv[5], conv[6],
+                       conv[7], conv[8], conv[9], conv[10], prob->in, prob->out);
+    if (rc) return rc;
+    if (out->M != prob->M || out->N != prob->N || out->K != prob->K) return ALCOP_ERR_SHAPE;
+    return ALCOP_OK;
+  }
+  *out = gemm_call(prob->op, A, B, C, prob->batch, prob->M, prob->N, prob->K, lda, ldb, ldc, sA,
+                   sB, sC, prob->transB, prob->in, prob->out);
+  return ALCOP_OK;
+}
+
+// Mean microseconds per launch over `iters` back-to-back launches (HIP events on `st`).
+int time_sched(const Call& c, const alcop_sched& s, const KernelEntry* e, int warmup, int iters,
+               hipStream_t st, double* us)
+{
+  for (int i = 0; i < warmup; i++) {
+    int rc = launch_call(c, s, e, st);
+    if (rc) return rc;
+  }
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return ALCOP_ERR_LAUNCH;
+  if (hipEventCreate(&e1) != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    return ALCOP_ERR_LAUNCH;
+  }
+  int rc = ALCOP_OK;
+  (void)hipEventRecord(e0, st);
+  for (int i = 0; i < iters && rc == ALCOP_OK; i++) rc = launch_call(c, s, e, st);
+  (void)hipEventRecord(e1, st);
+  if (hipEventSynchronize(e1) != hipSuccess) rc = ALCOP_ERR_LAUNCH;
+  float ms = 0.f;
+  if (rc == ALCOP_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = ALCOP_ERR_LAUNCH;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc == ALCOP_OK) *us = (double)ms * 1000.0 / iters;
+  return rc;
+}
+
+}  // namespace
+}  // namespace alcop
+
+using namespace alcop;
+
+extern "C" {
+
+int alcop_gemm(const void* A, const void* B, void* C, int M, int N, int K, long lda, long ldb,
+               long ldc, int transA, int transB, alcop_dtype in, alcop_dtype out,
+               const alcop_sched* sched, void* hip_stream)
+{
+  if (transA) return ALCOP_ERR_UNSUPPORTED;
+  Call c = gemm_call(ALCOP_OP_GEMM, A, B, C, 1, M, N, K, lda, ldb, ldc, 0, 0, 0, transB, in, out);
+  return run(c, sched, hip_stream);
+}
+
+int alcop_bmm(const void* A, const void* B, void* C, int batch, int M, int N, int K, long lda,
+              long ldb, long ldc, long strideA, long strideB, long strideC, int transA, int transB,
+              alcop_dtype in, alcop_dtype out, const alcop_sched* sched, void* hip_stream)
+{
+  if (transA) return ALCOP_ERR_UNSUPPORTED;
+  Call c = gemm_call(ALCOP_OP_BMM, A, B, C, batch, M, N, K, lda, ldb, ldc, strideA, strideB,
+                     strideC, transB, in, out);
+  return run(c, sched, hip_stream);
+}
+
+int alcop_conv2d_igemm(const void* x, const void* w, void* y, int N, int H, int W, int C, int K,
+                       int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
+                       alcop_dtype in, alcop_dtype out, const alcop_sched* sched, void* hip_stream)
+{
+  Call c;
+  int rc = conv_call(&c, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, in, out);
+  if (rc) return rc;
+  return run(c, sched, hip_stream);
+}
+
+int alcop_sched_supported(const alcop_problem* prob, const alcop_sched* sched)
+{
+  if (!prob || !sched) return ALCOP_ERR_NULL;
+  return check_sched(*prob, *sched, nullptr);
+}
+
+int alcop_sched_space(const alcop_problem* prob, alcop_sched* out, int cap)
+{
+  if (!prob) return ALCOP_ERR_NULL;
+  const std::vector<alcop_sched> v = space_of(*prob);
+  if (out)
+    for (int i = 0; i < (int)v.size() && i < cap; i++) out[i] = v[i];
+  return (int)v.size();
+}
+
+int alcop_model_predict(const alcop_problem* prob, const alcop_sched* sched, int model,
+                        double* predicted_us, double* terms)
+{
+  if (!prob || !sched || !predicted_us) return ALCOP_ERR_NULL;
+  if (model != 0 && model != 1) return ALCOP_ERR_UNSUPPORTED;
+  int rc = check_problem(*prob);
+  if (rc) return rc;
+  if (sched->bm <= 0 || sched->bn <= 0 || sched->bk <= 0 || sched->wm <= 0 || sched->wn <= 0 ||
+      sched->stages < 1 || sched->reg_stages < 1)
+    return ALCOP_ERR_SCHED;
+  ModelTerms t;
+  *predicted_us = predict(*prob, *sched, model, Device(), &t);
+  if (terms) {
+    terms[0] = t.t_kernel;
+    terms[1] = t.t_threadblk;
+    terms[2] = t.t_init;
+    terms[3] = t.t_main_loop;
+    terms[4] = t.t_epilogue;
+    terms[5] = t.t_smem_load;
+    terms[6] = t.t_smem_use;
+    terms[7] = t.n_threadblk_batch;
+  }
+  return ALCOP_OK;
+}
+
+int alcop_time(const alcop_problem* prob, const void* A, const void* B, void* C, long lda, long ldb,
+               long ldc, long strideA, long strideB, long strideC, const int* conv,
+               const alcop_sched* sched, int warmup, int iters, double* mean_us, void* hip_stream)
+{
+  if (!sched || !mean_us) return ALCOP_ERR_NULL;
+  if (iters <= 0 || warmup < 0) return ALCOP_ERR_SHAPE;
+  Call c;
+  int rc = call_of_problem(prob, A, B, C, lda, ldb, ldc, strideA, strideB, strideC, conv, &c);
+  if (rc) return rc;
+  rc = check_call(c);
+  if (rc) return rc;
+  const KernelEntry* e = nullptr;
+  rc = check_sched(problem_of(c), *sched, &e);
+  if (rc) return rc;
+  rc = span_check(c, *sched);
+  if (rc) return rc;
+  return time_sched(c, *sched, e, warmup, iters, (hipStream_t)hip_stream, mean_us);
+}
+
+int alcop_tune(const alcop_problem* prob, const void* A, const void* B, void* C, long lda, long ldb,
+               long ldc, long strideA, long strideB, long strideC, const int* conv, int top_k,
+               int model, int iters, alcop_sched* best, double* best_us, int* trials_run,
+               int* space_size, alcop_sched* log_sched, double* log_pred_us, double* log_meas_us,
+               int log_cap, void* hip_stream)
+{
+  if (!best || !best_us) return ALCOP_ERR_NULL;
+  if (top_k < 0 || iters <= 0 || (model != 0 && model != 1)) return ALCOP_ERR_SHAPE;
+  Call c;
+  int rc = call_of_problem(prob, A, B, C, lda, ldb, ldc, strideA, strideB, strideC, conv, &c);
+  if (rc) return rc;
+  rc = check_call(c);
+  if (rc) return rc;
+  const alcop_problem p = problem_of(c);
+  struct Cand {
+    alcop_sched s;
+    const KernelEntry* e;
+    double pred;
+  };
+  std::vector<Cand> cands;
+  const Device dev;
+  for (const alcop_sched& s : space_of(p)) {
+    const KernelEntry* e = nullptr;
+    if (check_sched(p, s, &e) != ALCOP_OK || span_check(c, s) != ALCOP_OK) continue;   // pruned
+    cands.push_back(Cand{s, e, predict(p, s, model, dev, nullptr)});
+  }
+  if (space_size) *space_size = (int)cands.size();
+  if (cands.empty()) return ALCOP_ERR_SCHED;
+  std::stable_sort(cands.begin(), cands.end(),
+                   [](const Cand& a, const Cand& b) { return a.pred < b.pred; });
+  const int n = top_k == 0 ? (int)cands.size() : std::min(top_k, (int)cands.size());
+  bool have = false;
+  int done = 0;
+  for (int i = 0; i < n; i++) {
+    double us = 0;
+    rc = time_sched(c, cands[i].s, cands[i].e, 3, iters, (hipStream_t)hip_stream, &us);
+    if (rc) return rc;
+    if (i < log_cap) {
+      if (log_sched) log_sched[i] = cands[i].s;
+      if (log_pred_us) log_pred_us[i] = cands[i].pred;
+      if (log_meas_us) log_meas_us[i] = us;
+    }
+    if (!have || us < *best_us) {
+      *best_us = us;
+      *best = cands[i].s;
+      have = true;
+    }
+    done++;
+  }
+  if (trials_run) *trials_run = done;
+  std::lock_guard<std::mutex> lk(g_cache_mu);
+  g_cache[key_of(p)] = *best;
+  return ALCOP_OK;
+}
+
+const char* alcop_strerror(int code)
+{
+  switch (code) {
+    case ALCOP_OK: return "ok";
+    case ALCOP_ERR_NULL: return "null pointer";
+    case ALCOP_ERR_DTYPE: return "unsupported element type";
+    case ALCOP_ERR_ALIGN: return "pointer, leading dimension or stride not aligned";
+    case ALCOP_ERR_SHAPE: return "bad shape (size <= 0, K not a multiple of bk, N not a multiple of 8, ...)";
+    case ALCOP_ERR_SCHED: return "schedule not built or infeasible";
+    case ALCOP_ERR_LAUNCH: return "HIP launch failed";
+    case ALCOP_ERR_UNSUPPORTED: return "not supported";
+    case ALCOP_ERR_SIZE: return "operand spans 2 GiB or more";
+    default: return "unknown status";
+  }
+}
+
+const char* alcop_version(void) { return "alcop-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,72 @@
+// Helpers used by the instance shards: launcher template and cartesian-product macros.
+#pragma once
+#include "alcop_registry.h"
+
+namespace alcop {
+
+template <class C>
+hipError_t launch_instance(const Params& p, dim3 grid, hipStream_t st)
+{
+  static bool attr_set = false;
+  if (!attr_set) {
+    // LDS rings above the default 64 KB per-block limit need an explicit opt-in.
+    hipError_t e = hipFuncSetAttribute((const void*)alcop_mainloop<C>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  alcop_mainloop<C><<<grid, dim3(C::NT), C::LDS_BYTES, st>>>(p);
+  return hipGetLastError();
+}
+
+constexpr bool instance_feasible(int bm, int bn, int bk, int wm, int wn, int s, int r, int f)
+{
+  const int nt = (bm / wm) * (bn / wn) * 64;
+  const int a = bm * bk * 2, b = bn * bk * 2;
+  if (a % (nt * 16) || b % (nt * 16)) return false;
+  if (s * (a + b) > 160 * 1024) return false;
+  if (f && (r != 2 || s < 2)) return false;
+  const int l = (a + b) / (nt * 16);
+  if (s >= 2 && (s - 2) * l > 63) return false;
+  return true;
+}
+
+template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int R, int F, int BL, int AM>
+void add_instance(std::vector<KernelEntry>& t)
+{
+  if constexpr (instance_feasible(BM, BN, BK, WM, WN, S, R, F)) {
+    using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM>;
+    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, C::LDS_BYTES, C::NT, C::L,
+                            &launch_instance<C>});
+  }
+}
+
+}  // namespace alcop
+
+// Every pipelining variant of one tile: S in 1..4 single-level (R=1), multi-level unfused
+// (R=2), multi-level fused (R=2, F=1).  Infeasible combinations are skipped at compile time.
+#define ALCOP_ALL_PIPES(T, DT, BM, BN, BK, WM, WN, BL, AM)      \
+  add_instance<DT, BM, BN, BK, WM, WN, 1, 1, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 2, 1, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 3, 1, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 4, 1, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 1, 2, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 2, 2, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 3, 2, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 4, 2, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 2, 2, 1, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 3, 2, 1, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 4, 2, 1, BL, AM>(T);
+
+// A reduced set: the unpipelined baseline, double buffering, and the fused multi-level ones.
+#define ALCOP_KEY_PIPES(T, DT, BM, BN, BK, WM, WN, BL, AM)      \
+  add_instance<DT, BM, BN, BK, WM, WN, 1, 1, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 2, 1, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 3, 1, 0, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 2, 2, 1, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 3, 2, 1, BL, AM>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 4, 2, 1, BL, AM>(T);
+
+#define ALCOP_BOTH_BK(MACRO, T, DT, BM, BN, WM, WN, BL, AM) \
+  MACRO(T, DT, BM, BN, 32, WM, WN, BL, AM)                  \
+  MACRO(T, DT, BM, BN, 64, WM, WN, BL, AM)

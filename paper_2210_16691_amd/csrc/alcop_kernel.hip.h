@@ -1,0 +1,427 @@
+// Pipelined tiled main loop for gfx950 (MI355X): GEMM / batched matmul / implicit-GEMM conv.
+//
+// One template, one kernel.  The loop structure is the paper's transformed load-and-use loop
+// (arXiv 2210.16691, Sec. 4.2 steps 1-5) written by hand for CDNA4:
+//   step 1  buffer x S      -> LDS ring of S stages, each [A tile | B tile]; R register slots
+//   step 2  index shift     -> iteration ko issues the loads of k-tile ko+S-1
+//   step 3  roll and wrap   -> slot = k-tile mod S; k-tiles past the end are issued as
+//                              out-of-range buffer loads (they fetch nothing and zero-fill a
+//                              free slot), which keeps the number of loads in flight constant
+//   step 4  prologue        -> S-1 k-tiles issued before the loop (and, with fusion, the first
+//                              fragment read before the loop: Sec. 4.1 step 5)
+//   step 5  synchronisation -> producer_commit is implicit (the vector-memory counter counts
+//                              loads in issue order); consumer_wait = s_waitcnt vmcnt((S-2)*L)
+//                              + s_barrier; consumer_release / producer_acquire = s_waitcnt
+//                              lgkmcnt(0) + the same s_barrier of the following iteration.
+// Rule 1 of Sec. 3.1 (the buffer must be produced by an asynchronous copy) is met by
+// buffer_load_dwordx4 ... lds: data goes HBM/L2 -> LDS without passing through registers.
+//
+// Data layout in LDS.  A direct-to-LDS load writes lane l's 16 bytes at M0 + 16*l, so the
+// LDS image of a tile is linear in (load, wave, lane); the bank-conflict-free swizzle is
+// applied on the source side by choosing which 16-byte chunk of the global tile each lane
+// fetches (the paper applies shared-memory swizzling to all its kernels, Sec. 6.1).
+//   K-contiguous tile (A, or B stored N x K): rows of BK halves, CPR = BK/8 chunks per row,
+//     physical chunk = logical chunk XOR ((row/2) mod CPR); read with ds_read_b128.
+//   N-contiguous tile (B stored K x N): rows of BN halves (one row per k), physical chunk =
+//     logical chunk XOR (((k/RPB) mod min(4,BN/32)) << 2); read with ds_read_b64_tr_b16,
+//     which hands each lane 4 consecutive k of one column.
+//
+// Matrix-core mapping.  v_mfma_f32_32x32x16_{f16,bf16} computes D[i][j] += sum_k X[i][k] Y[k][j]
+// with X lane l = row l%32, k = 8*(l/32)..+7, Y lane l = column l%32, same k, and D lane l =
+// column l%32, rows 8*(v/4) + 4*(l/32) + v%4 for v = 0..15.  We feed X from B (i = n) and Y
+// from A (j = m), so a lane owns 4 consecutive n of one output row m: a vector store.
+
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace alcop {
+
+struct Params {
+  const void* A;
+  const void* B;
+  void* C;
+  int M, N, K;                 // GEMM view
+  int lda, ldb, ldc;           // elements (host guarantees the byte spans fit 31 bits)
+  long strideA, strideB, strideC;
+  int out_dtype;               // 0 f16, 1 bf16, 2 f32
+  int ntm, ntn;                // tile counts
+  int raster, group_m;         // block -> tile order
+  // convolution geometry (AM == 1): x is NHWC, A rows are (img, p, q)
+  int cH, cW, cC, cP, cQ, cS, csh, csw, cph, cpw;
+  unsigned a_span, b_span;     // conv: bytes of x; unused otherwise
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define ALCOP_LDS __attribute__((address_space(3)))
+
+template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int S_, int R_, int FUSE_,
+          int BL_, int AM_>
+struct KCfg {
+  static constexpr int DT = DT_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
+  static constexpr int S = S_, R = R_, FUSE = FUSE_, BL = BL_, AM = AM_;
+  static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, NWAVES = WAVES_M * WAVES_N;
+  static constexpr int NT = NWAVES * 64;
+  static constexpr int TM = WM / 32, TN = WN / 32, NKI = BK / 16;
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = S * STAGE_BYTES;
+  static constexpr int NLA = A_BYTES / (NT * 16), NLB = B_BYTES / (NT * 16), L = NLA + NLB;
+  static constexpr int CPR_A = BK / 8;                       // 16-byte chunks per A-tile row
+  static constexpr int RSTEP_A = NT / CPR_A;                 // tile rows covered by one load
+  static constexpr int CPR_B = BL ? BK / 8 : BN / 8;
+  static constexpr int RSTEP_B = NT / CPR_B;
+  // swizzle of the N-contiguous B tile
+  static constexpr int UPR = BN / 32;                        // 64-byte units per row
+  static constexpr int RPB = (4 / UPR) > 1 ? (4 / UPR) : 1;  // rows per 256-byte bank line
+  static constexpr int GM = UPR < 4 ? UPR : 4;
+  static constexpr int WAIT = (S >= 2 ? (S - 2) * L : 0);    // loads allowed in flight at a wait
+  static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "wave tile");
+  static_assert(BK == 32 || BK == 64, "bk");
+  static_assert(A_BYTES % (NT * 16) == 0 && B_BYTES % (NT * 16) == 0, "loads per thread");
+  static_assert(RSTEP_A % 2 == 0 && (RSTEP_A / 2) % CPR_A == 0, "A swizzle period");
+  static_assert(BL ? (RSTEP_B % 2 == 0 && (RSTEP_B / 2) % CPR_B == 0)
+                   : (RSTEP_B % (4 * RPB) == 0), "B swizzle period");
+  static_assert(S >= 1 && S <= 4 && (R == 1 || R == 2), "stages");
+  static_assert(!FUSE || (R == 2 && S >= 2), "fusion needs a register double buffer and S>=2");
+  static_assert(WAIT <= 63, "vmcnt is a 6-bit counter");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
+};
+
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, uint32_t lds_dst)
+{
+  // M0 holds the wave-uniform LDS destination; lane l lands at M0 + 16*l.
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :
+               : "s"(lds_dst), "v"(voff), "s"(rsrc)
+               : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm()
+{
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lds()
+{
+  asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
+}
+__device__ __forceinline__ void block_barrier()
+{
+  __builtin_amdgcn_s_barrier();
+}
+
+template <int DT>
+__device__ __forceinline__ f32x16 mma(u32x4 x, u32x4 y, f32x16 acc)
+{
+  if constexpr (DT == 0)
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, x),
+                                                  __builtin_bit_cast(f16x8, y), acc, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x),
+                                                   __builtin_bit_cast(bf16x8, y), acc, 0, 0, 0);
+}
+
+__device__ __forceinline__ u32x4 lds_read16(uint32_t addr)
+{
+  return *(const ALCOP_LDS u32x4*)(uintptr_t)addr;
+}
+__device__ __forceinline__ u32x2 lds_read_tr8(uint32_t addr)
+{
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ALCOP_LDS s16x4*)(uintptr_t)addr);
+  return __builtin_bit_cast(u32x2, v);
+}
+
+template <class C>
+__global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
+{
+  constexpr int BM = C::BM, BN = C::BN, BK = C::BK, WM = C::WM, WN = C::WN, S = C::S;
+  constexpr int TM = C::TM, TN = C::TN, NKI = C::NKI, NLA = C::NLA, NLB = C::NLB;
+  constexpr int NWAVES = C::NWAVES, STAGE_BYTES = C::STAGE_BYTES, A_BYTES = C::A_BYTES;
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(ALCOP_LDS unsigned char*)smem;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int wm = wave % C::WAVES_M, wn = wave / C::WAVES_M;
+  const int batch = blockIdx.y;
+
+  // ---- block -> tile (paper Sec. 1: inter-tile parallelism; the order only affects L2 reuse)
+  int lid = blockIdx.x;
+  const int nblk = p.ntm * p.ntn;
+  int tm, tn;
+  if (p.raster == 1) {
+    if ((nblk & 7) == 0) lid = (lid & 7) * (nblk >> 3) + (lid >> 3);   // blocks of one XCD adjacent
+    const int width = p.group_m * p.ntn;
+    const int g = lid / width;
+    const int first = g * p.group_m;
+    const int gsz = (p.ntm - first) < p.group_m ? (p.ntm - first) : p.group_m;
+    const int rem = lid - g * width;
+    tm = first + rem % gsz;
+    tn = rem / gsz;
+  } else {
+    tm = lid / p.ntn;
+    tn = lid - tm * p.ntn;
+  }
+  const int nko = p.K / BK;
+
+  // ---- global -> LDS producers -----------------------------------------------------------
+  const int q0 = wave * 64 + lane;            // 16-byte slot of this lane in load 0
+  __amdgpu_buffer_rsrc_t rsrcA, rsrcB;
+  uint32_t voffA, stepA = 0;
+  // conv state: per-load row geometry
+  int ih0[NLA], iw0[NLA];
+  uint32_t coff[NLA];
+  int cr = 0, cs = 0, cc0 = 0;                // (r, s, c0) of the next k-tile to issue
+  {
+    const int r = q0 / C::CPR_A, ph = q0 % C::CPR_A;
+    const int c = ph ^ ((r >> 1) % C::CPR_A);
+    if constexpr (C::AM == 0) {
+      const int rows = (p.M - tm * BM) < BM ? (p.M - tm * BM) : BM;
+      const char* base = (const char*)p.A + ((long)batch * p.strideA + (long)tm * BM * p.lda) * 2;
+      rsrcA = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0,
+                                                ((rows - 1) * p.lda + p.K) * 2, 0x00020000);
+      voffA = (uint32_t)(r * p.lda * 2 + c * 16);
+      stepA = (uint32_t)(C::RSTEP_A * p.lda * 2);
+    } else {
+      rsrcA = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, (int)p.a_span, 0x00020000);
+      voffA = 0;
+#pragma unroll
+      for (int i = 0; i < NLA; i++) {
+        const int m = tm * BM + r + i * C::RSTEP_A;
+        const int img = m / (p.cP * p.cQ);
+        const int pq = m - img * (p.cP * p.cQ);
+        const int pp = pq / p.cQ, qq = pq - pp * p.cQ;
+        ih0[i] = (m < p.M) ? pp * p.csh - p.cph : -0x40000000;
+        iw0[i] = qq * p.csw - p.cpw;
+        coff[i] = (uint32_t)((((img * p.cH + (pp * p.csh - p.cph)) * p.cW) + iw0[i]) * p.cC * 2 +
+                             c * 16);
+      }
+    }
+  }
+  uint32_t voffB, stepB, kstepB;
+  {
+    const int r = q0 / C::CPR_B, ph = q0 % C::CPR_B;
+    if constexpr (C::BL == 1) {                // B stored N x K: same shape of loader as A
+      const int c = ph ^ ((r >> 1) % C::CPR_B);
+      const int cols = (p.N - tn * BN) < BN ? (p.N - tn * BN) : BN;
+      const char* base = (const char*)p.B + ((long)batch * p.strideB + (long)tn * BN * p.ldb) * 2;
+      rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0,
+                                                ((cols - 1) * p.ldb + p.K) * 2, 0x00020000);
+      voffB = (uint32_t)(r * p.ldb * 2 + c * 16);
+      stepB = (uint32_t)(C::RSTEP_B * p.ldb * 2);
+      kstepB = BK * 2;
+    } else {                                   // B stored K x N: tile rows are k
+      const int c = ph ^ (((r / C::RPB) % C::GM) << 2);
+      const int cols = (p.N - tn * BN) < BN ? (p.N - tn * BN) : BN;
+      const char* base = (const char*)p.B + ((long)batch * p.strideB + (long)tn * BN) * 2;
+      rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0,
+                                                ((p.K - 1) * p.ldb + cols) * 2, 0x00020000);
+      voffB = (uint32_t)(r * p.ldb * 2 + c * 16);
+      stepB = (uint32_t)(C::RSTEP_B * p.ldb * 2);
+      kstepB = (uint32_t)(BK * p.ldb * 2);
+    }
+  }
+
+  // Issue the loads of k-tile `kt` into ring slot `slot`.  Always exactly L loads per wave.
+  auto issue = [&](int kt, int slot) {
+    const bool live = kt < nko;
+    const uint32_t dst = lds0 + (uint32_t)slot * STAGE_BYTES + (uint32_t)wave * 1024u;
+    if constexpr (C::AM == 0) {
+      const uint32_t ka = live ? (uint32_t)kt * (BK * 2) : 0x80000000u;
+#pragma unroll
+      for (int i = 0; i < NLA; i++)
+        dma16(rsrcA, voffA + ka + (uint32_t)i * stepA, dst + i * (NWAVES * 1024));
+    } else {
+      const uint32_t tap = (uint32_t)(((cr * p.cW + cs) * p.cC + cc0) * 2);
+#pragma unroll
+      for (int i = 0; i < NLA; i++) {
+        const bool ok = live && (unsigned)(ih0[i] + cr) < (unsigned)p.cH &&
+                        (unsigned)(iw0[i] + cs) < (unsigned)p.cW;
+        dma16(rsrcA, ok ? coff[i] + tap : 0x80000000u, dst + i * (NWAVES * 1024));
+      }
+      cc0 += BK;
+      if (cc0 == p.cC) { cc0 = 0; cs++; if (cs == p.cS) { cs = 0; cr++; } }
+    }
+    const uint32_t kb = live ? (uint32_t)kt * kstepB : 0x80000000u;
+#pragma unroll
+    for (int i = 0; i < NLB; i++)
+      dma16(rsrcB, voffB + kb + (uint32_t)i * stepB, dst + A_BYTES + i * (NWAVES * 1024));
+  };
+
+  // ---- LDS -> register consumers ---------------------------------------------------------
+  // Y operand (from A): lane reads row wm*WM + t*32 + lane%32, logical chunk 2*ki + lane/32.
+  uint32_t rdA[NKI];
+  {
+    const int row = wm * WM + (lane & 31);
+#pragma unroll
+    for (int ki = 0; ki < NKI; ki++)
+      rdA[ki] = (uint32_t)(row * (BK * 2) + (((2 * ki + (lane >> 5)) ^ ((row >> 1) % C::CPR_A)) * 16));
+  }
+  // X operand (from B)
+  uint32_t rdB[C::BL ? NKI : TN];
+  if constexpr (C::BL == 1) {
+    const int row = wn * WN + (lane & 31);
+#pragma unroll
+    for (int ki = 0; ki < NKI; ki++)
+      rdB[ki] = (uint32_t)(A_BYTES + row * (BK * 2) +
+                           (((2 * ki + (lane >> 5)) ^ ((row >> 1) % C::CPR_B)) * 16));
+  } else {
+    // transposing read: 16-lane group G reads 4 k-rows x 16 columns; lane s of the group
+    // supplies row s/4, columns 4*(s%4)..+3 and receives column s, rows 0..3.
+    const int G = lane >> 4, s = lane & 15;
+    const int k = 8 * (G >> 1) + (s >> 2);
+#pragma unroll
+    for (int t = 0; t < TN; t++) {
+      const int n = wn * WN + t * 32 + 16 * (G & 1) + 4 * (s & 3);
+      const int c = (n >> 3) ^ (((k / C::RPB) % C::GM) << 2);
+      rdB[t] = (uint32_t)(A_BYTES + k * (BN * 2) + c * 16 + (n & 7) * 2);
+    }
+  }
+
+  auto load_frags = [&](uint32_t sbase, int ki, u32x4(&fa)[TM], u32x4(&fb)[TN]) {
+#pragma unroll
+    for (int t = 0; t < TM; t++) fa[t] = lds_read16(sbase + rdA[ki] + t * (32 * BK * 2));
+    if constexpr (C::BL == 1) {
+#pragma unroll
+      for (int t = 0; t < TN; t++) fb[t] = lds_read16(sbase + rdB[ki] + t * (32 * BK * 2));
+    } else {
+#pragma unroll
+      for (int t = 0; t < TN; t++) {
+        const uint32_t a = sbase + rdB[t] + ki * (16 * BN * 2);
+        const u32x2 lo = lds_read_tr8(a);
+        const u32x2 hi = lds_read_tr8(a + 4 * BN * 2);
+        fb[t] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+      }
+    }
+  };
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; i++)
+#pragma unroll
+    for (int j = 0; j < TM; j++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
+
+  auto mma_all = [&](u32x4(&fa)[TM], u32x4(&fb)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TN; i++)
+#pragma unroll
+      for (int j = 0; j < TM; j++) acc[i][j] = mma<C::DT>(fb[i], fa[j], acc[i][j]);
+  };
+
+  u32x4 fa[C::R][TM], fb[C::R][TN];
+
+  // ---- the pipelined main loop -----------------------------------------------------------
+  if constexpr (C::FUSE) {
+    // Holistic pipeline over (ko, ki): Fig. 3(d).
+#pragma unroll
+    for (int s = 0; s < S - 1; s++) issue(s, s);
+    wait_vm<C::WAIT>();
+    block_barrier();
+    load_frags(lds0, 0, fa[0], fb[0]);
+    int rslot = 0, wslot = S - 1;
+    for (int ko = 0; ko < nko; ko++) {
+      issue(ko + S - 1, wslot);
+      wslot = (wslot + 1 == S) ? 0 : wslot + 1;
+#pragma unroll
+      for (int ki = 0; ki < NKI; ki++) {
+        if (ki == NKI - 1) {
+          wait_vm<C::WAIT>();            // consumer_wait: k-tile ko+1 has landed (this wave)
+          wait_lds();                    // consumer_release: my reads of slot ko are done
+          block_barrier();               // ... for every wave
+          rslot = (rslot + 1 == S) ? 0 : rslot + 1;
+          load_frags(lds0 + rslot * STAGE_BYTES, 0, fa[(ki + 1) & 1], fb[(ki + 1) & 1]);
+        } else {
+          load_frags(lds0 + rslot * STAGE_BYTES, ki + 1, fa[(ki + 1) & 1], fb[(ki + 1) & 1]);
+        }
+        mma_all(fa[ki & 1], fb[ki & 1]);
+      }
+    }
+  } else {
+    if constexpr (S >= 2) {
+#pragma unroll
+      for (int s = 0; s < S - 1; s++) issue(s, s);
+    }
+    int rslot = 0, wslot = (S >= 2) ? S - 1 : 0;
+    for (int ko = 0; ko < nko; ko++) {
+      if constexpr (S >= 2) {
+        wait_vm<C::WAIT>();              // consumer_wait for k-tile ko
+        wait_lds();
+        block_barrier();                 // also releases slot (ko-1) mod S
+        issue(ko + S - 1, wslot);
+      } else {
+        wait_lds();
+        block_barrier();                 // producer_acquire: slot 0 is free
+        issue(ko, 0);
+        wait_vm<0>();                    // consumer_wait
+        block_barrier();
+      }
+      wslot = (wslot + 1 == S) ? 0 : wslot + 1;
+      const uint32_t sbase = lds0 + rslot * STAGE_BYTES;
+      rslot = (rslot + 1 == S) ? 0 : rslot + 1;
+      if constexpr (C::R == 2) {
+        // register-level pipeline restarted in every ko: Fig. 3(c)
+        load_frags(sbase, 0, fa[0], fb[0]);
+#pragma unroll
+        for (int ki = 0; ki < NKI; ki++) {
+          if (ki + 1 < NKI) load_frags(sbase, ki + 1, fa[(ki + 1) & 1], fb[(ki + 1) & 1]);
+          mma_all(fa[ki & 1], fb[ki & 1]);
+        }
+      } else {
+        // single-level: load a fragment, use it (Fig. 3(b))
+#pragma unroll
+        for (int ki = 0; ki < NKI; ki++) {
+          load_frags(sbase, ki, fa[0], fb[0]);
+          mma_all(fa[0], fb[0]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+  }
+  wait_vm<0>();   // drain the zero-fill loads of the ring's tail before the wave may retire
+
+  // ---- epilogue: convert and store (Table 1, epilogue term) --------------------------------
+  const int m_base = tm * BM + wm * WM + (lane & 31);
+  const int n_base = tn * BN + wn * WN + 4 * (lane >> 5);
+  char* Cb = (char*)p.C;
+  const long cbatch = (long)batch * p.strideC;
+#pragma unroll
+  for (int j = 0; j < TM; j++) {
+    const int m = m_base + j * 32;
+    if (m >= p.M) continue;
+    const long rowoff = cbatch + (long)m * p.ldc;
+#pragma unroll
+    for (int i = 0; i < TN; i++) {
+#pragma unroll
+      for (int vq = 0; vq < 4; vq++) {
+        const int n = n_base + i * 32 + 8 * vq;
+        if (n >= p.N) continue;
+        const float v0 = acc[i][j][4 * vq + 0], v1 = acc[i][j][4 * vq + 1];
+        const float v2 = acc[i][j][4 * vq + 2], v3 = acc[i][j][4 * vq + 3];
+        if (p.out_dtype == 2) {
+          *(f32x4*)(Cb + (rowoff + n) * 4) = f32x4{v0, v1, v2, v3};
+        } else if (p.out_dtype == 0) {
+          f16x4 h = {(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};
+          *(f16x4*)(Cb + (rowoff + n) * 2) = h;
+        } else {
+          bf16x4 h = {(__bf16)v0, (__bf16)v1, (__bf16)v2, (__bf16)v3};
+          *(bf16x4*)(Cb + (rowoff + n) * 2) = h;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace alcop

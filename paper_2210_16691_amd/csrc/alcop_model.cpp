@@ -1,0 +1,101 @@
+// Static latency model (paper Sec. 5).  Symbols follow Table 1; where the paper leaves a term
+// open the reading taken is stated next to it.
+#include "alcop_model.h"
+
+#include <algorithm>
+#include <cmath>
+
+namespace alcop {
+
+// Table 1, "Pipeline Latency Model".  A load is hidden when the work that can overlap it
+// (the other N_pipe-1 stages of this worker plus N_mplx-1 other workers) lasts at least as
+// long; otherwise every N_pipe iterations cost one exposed load plus one use.
+double pipeline_latency(double t_load, double t_use, double n_loop, double n_pipe, double n_mplx)
+{
+  if (t_load <= (n_pipe * n_mplx - 1.0) * t_use) return t_use * n_loop;
+  return (t_load + t_use) * n_loop / n_pipe;
+}
+
+static double ceil_div(double a, double b) { return std::ceil(a / b); }
+
+double predict(const alcop_problem& prob, const alcop_sched& s, int model, const Device& dev,
+               ModelTerms* terms)
+{
+  const double bm = s.bm, bn = s.bn, bk = s.bk, wm = s.wm, wn = s.wn;
+  const double S = s.stages, R = s.reg_stages;
+  const double out_bytes = prob.out == ALCOP_F32 ? 4.0 : 2.0;
+  const double batch = prob.batch > 0 ? prob.batch : 1;
+  const double ntm = ceil_div(prob.M, bm), ntn = ceil_div(prob.N, bn);
+  const double tiles = ntm * ntn;
+  const double n_blocks = tiles * batch;
+  const double n_warp = (bm / wm) * (bn / wn);              // N_warp_per_threadblk
+  const double n_smem_loop = std::floor(prob.K / bk);       // N_smem_loop
+  const double n_reg_loop = bk / 16.0;                       // N_reg_loop (MFMA k = 16)
+  const double stage_bytes = (bm + bn) * bk * 2.0;          // Bytes_one_smem_loop
+  const double frag_bytes = n_warp * (wm + wn) * 16.0 * 2.0; // Bytes_one_reg_loop (LDS reads)
+  const double flops_reg_loop = 2.0 * bm * bn * 16.0;        // FLOPs_one_reg_loop
+
+  if (model == 1) {
+    // Bottleneck-only model (Sec. 6.4): full utilisation of every resource, no latency terms.
+    const double t_cmp = n_blocks * n_smem_loop * n_reg_loop * flops_reg_loop /
+                         (dev.num_cu * dev.flop_per_us_cu);
+    const double t_lds = n_blocks * n_smem_loop * n_reg_loop * frag_bytes /
+                         (dev.num_cu * dev.bw_lds_cu);
+    const double t_mem = (n_blocks * n_smem_loop * stage_bytes + n_blocks * bm * bn * out_bytes) /
+                         dev.bw_dram;
+    const double t = std::max(t_cmp, std::max(t_lds, t_mem));
+    if (terms) *terms = ModelTerms{t, t, 0, t, 0, t_mem, t_cmp, 1};
+    return t;
+  }
+
+  // --- simulated block scheduler (Sec. 5.1: blocks per SM limited by shared memory and
+  // registers).  Reading: registers per lane = accumulators + R fragment sets + 48.
+  const double regs = wm * wn / 64.0 + R * (wm / 32.0 + wn / 32.0) * 4.0 + 48.0;
+  const double waves_per_simd = std::max(1.0, std::min(8.0, std::floor(dev.regs_per_lane / regs)));
+  double blk_per_cu = std::min(std::floor(dev.lds_bytes / (S * stage_bytes)),
+                               std::floor(waves_per_simd * dev.simd_per_cu / n_warp));
+  blk_per_cu = std::max(1.0, blk_per_cu);
+  blk_per_cu = std::min(blk_per_cu, ceil_div(n_blocks, dev.num_cu));   // no more than exist
+  const double slots = dev.num_cu * blk_per_cu;
+  const double n_batch = ceil_div(n_blocks, slots);           // N_threadblk_batch
+  const double n_in_batch = std::min(n_blocks, slots);        // N_threadblk_per_threadblk_batch
+
+  // --- computation latency.  Reading of Util(N_warp, N_blk): the share of one CU's matrix
+  // throughput that ONE block obtains: all pipes busy once N_warp*N_blk >= 4, split evenly
+  // among the co-resident blocks.
+  const double util = std::min(1.0, n_warp * blk_per_cu / dev.simd_per_cu) / blk_per_cu;
+  const double t_compute = flops_reg_loop / (dev.flop_per_us_cu * util);
+
+  // --- register-level loop.  T_reg_load is not printed in the paper; reading: same form as the
+  // LLC term, latency + bytes / bandwidth, the LDS port shared by the co-resident blocks.
+  const double t_reg_load = dev.lat_lds + frag_bytes * blk_per_cu / dev.bw_lds_cu;
+  // Workers that can be multiplexed onto one matrix pipe = wavefronts per SIMD.
+  const double mplx_inner = std::max(1.0, n_warp * blk_per_cu / dev.simd_per_cu);
+  double t_smem_use = pipeline_latency(t_reg_load, t_compute, n_reg_loop, R, mplx_inner);
+  // The paper's T_smem_use is the fused steady state.  Without fusion the register pipeline is
+  // refilled in every outer iteration: one exposed fragment load per ko.
+  if (!s.fuse_inner && s.reg_stages >= 2) t_smem_use += t_reg_load;
+
+  // --- memory latency
+  const double t_llc = dev.lat_llc + stage_bytes * n_in_batch / dev.bw_llc;
+  // DRAM working set of a block batch: the co-resident blocks of one matrix form a near-square
+  // patch of tiles; distinct row panels and column panels are fetched once.
+  const double per_mat = std::min(tiles, n_in_batch);
+  const double mats = ceil_div(n_in_batch, tiles);
+  const double rows_u = std::min(ntm, std::ceil(std::sqrt(per_mat)));
+  const double cols_u = std::min(ntn, ceil_div(per_mat, rows_u));
+  const double workset = (rows_u * bm + cols_u * bn) * bk * 2.0 * mats;
+  const double t_dram = dev.lat_dram + workset / dev.bw_dram;
+  const double t_smem_load = std::max(t_llc, t_dram);
+
+  const double t_init = t_smem_load + t_reg_load;
+  const double t_main = pipeline_latency(t_smem_load, t_smem_use, n_smem_loop, S, blk_per_cu);
+  const double t_epi = dev.lat_dram_write + bm * bn * out_bytes * n_in_batch / dev.bw_dram_write;
+  const double t_blk = t_init + t_main + t_epi;
+  const double t_kernel = t_blk * n_batch;
+  if (terms)
+    *terms = ModelTerms{t_kernel, t_blk, t_init, t_main, t_epi, t_smem_load, t_smem_use, n_batch};
+  return t_kernel;
+}
+
+}  // namespace alcop

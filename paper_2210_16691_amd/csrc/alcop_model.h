@@ -1,0 +1,35 @@
+// Static latency model of a schedule (paper Sec. 5, Table 1), host code, fp64.
+#pragma once
+#include "../../include/alcop.h"
+
+namespace alcop {
+
+// Machine constants of the model (the LAT_* / BW_* / Throughput symbols of Table 1).
+// Times in microseconds, sizes in bytes, rates per microsecond.
+struct Device {
+  int num_cu = 256;                 // compute units ("SMs")
+  int simd_per_cu = 4;              // matrix pipes per CU
+  double lds_bytes = 163840.0;      // LDS per CU
+  double regs_per_lane = 512.0;     // VGPR + AGPR budget per SIMD lane
+  double flop_per_us_cu = 4096.0 * 2400.0;   // dense fp16/bf16 MFMA: 4096 flop/clk/CU at 2.4 GHz
+  double lat_lds = 128.0 / 2400.0;
+  double bw_lds_cu = 128.0 * 2400.0;          // LDS read bytes/us per CU
+  double lat_llc = 0.6, bw_llc = 16.0e6;      // L2 / Infinity Cache -> CU, aggregate
+  double lat_dram = 1.2, bw_dram = 8.0e6;     // HBM3E read
+  double lat_dram_write = 1.0, bw_dram_write = 8.0e6;
+};
+
+struct ModelTerms {
+  double t_kernel, t_threadblk, t_init, t_main_loop, t_epilogue, t_smem_load, t_smem_use,
+      n_threadblk_batch;
+};
+
+// The pipeline latency model of Table 1, second row.
+double pipeline_latency(double t_load, double t_use, double n_loop, double n_pipe, double n_mplx);
+
+// model 0: pipeline-aware model of Table 1; model 1: bottleneck-only comparison model (Sec. 6.4).
+// Returns predicted microseconds; fills terms if not null.
+double predict(const alcop_problem& prob, const alcop_sched& s, int model, const Device& dev,
+               ModelTerms* terms);
+
+}  // namespace alcop
