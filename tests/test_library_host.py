@@ -1,0 +1,106 @@
+"""Host-side checks that need no GPU: the shared library loads and exports every symbol that
+include/alcop.h declares; argument validation returns error codes before any launch; the
+schedule space and feasibility rules."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2210_16691_amd as al
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "alcop.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(alcop_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert set(names) == set(al.EXPORTS)
+    L = al.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_strerror():
+    assert "gfx950" in al.version()
+    assert al.strerror(0) == "ok"
+    for code in range(-8, 0):
+        assert al.strerror(code) != "unknown status"
+    assert al.strerror(-99) == "unknown status"
+
+
+def test_null_and_bad_arguments_are_rejected_without_a_launch():
+    L = al.lib()
+    s = al.sched(128, 128, 64, 64, 64, 1, 1, 0)
+    fake = ctypes.c_void_p(0x10000)           # never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x10008)
+    g = lambda A, B, C, M, N, K, lda, ldb, ldc, tA, tB, i, o: L.alcop_gemm(
+        A, B, C, M, N, K, lda, ldb, ldc, tA, tB, i, o, ctypes.byref(s), None)
+    assert g(None, fake, fake, 128, 128, 64, 64, 128, 128, 0, 0, 0, 0) == al.ERR_NULL
+    assert g(fake, fake, None, 128, 128, 64, 64, 128, 128, 0, 0, 0, 0) == al.ERR_NULL
+    assert g(fake, fake, fake, 128, 128, 64, 64, 128, 128, 1, 0, 0, 0) == al.ERR_UNSUPPORTED
+    assert g(fake, fake, fake, 128, 128, 64, 64, 128, 128, 0, 0, 2, 0) == al.ERR_DTYPE
+    assert g(fake, fake, fake, 128, 128, 64, 64, 128, 128, 0, 0, 0, 7) == al.ERR_DTYPE
+    assert g(fake, fake, fake, 0, 128, 64, 64, 128, 128, 0, 0, 0, 0) == al.ERR_SHAPE
+    assert g(fake, fake, fake, 128, 100, 64, 64, 104, 104, 0, 0, 0, 0) == al.ERR_SHAPE   # N % 8
+    assert g(odd, fake, fake, 128, 128, 64, 64, 128, 128, 0, 0, 0, 0) == al.ERR_ALIGN
+    assert g(fake, fake, fake, 128, 128, 64, 68, 128, 128, 0, 0, 0, 0) == al.ERR_ALIGN   # lda % 8
+    assert g(fake, fake, fake, 128, 128, 64, 56, 128, 128, 0, 0, 0, 0) == al.ERR_SHAPE   # lda < K
+    assert g(fake, fake, fake, 128, 128, 96, 96, 128, 128, 0, 0, 0, 0) == al.ERR_SHAPE   # K % bk
+    bad = al.sched(128, 128, 64, 64, 64, 1, 2, 1)      # fusion needs S >= 2
+    assert L.alcop_gemm(fake, fake, fake, 128, 128, 64, 64, 128, 128, 0, 0, 0, 0,
+                        ctypes.byref(bad), None) == al.ERR_SCHED
+    assert L.alcop_conv2d_igemm(fake, fake, fake, 1, 8, 8, 64, 64, 3, 3, 0, 1, 1, 1, 0, 0,
+                                None, None) == al.ERR_SHAPE       # stride 0
+    assert L.alcop_conv2d_igemm(fake, fake, fake, 1, 2, 2, 64, 64, 5, 5, 1, 1, 0, 0, 0, 0,
+                                None, None) == al.ERR_SHAPE       # filter larger than image
+
+
+def test_feasibility_rules():
+    p = al.problem(al.OP_GEMM, 2048, 2048, 2048, al.F16, al.F16)
+    ok = al.sched(128, 128, 64, 64, 64, 3, 2, 1)
+    assert al.alcop_sched_supported(p, ok) == al.OK
+    # 256x256x64 needs 64 KB per stage: three stages exceed the 160 KB LDS -> not built, infeasible
+    assert al.alcop_sched_supported(p, al.sched(256, 256, 64, 128, 128, 3, 2, 1)) == al.ERR_SCHED
+    assert al.alcop_sched_supported(p, al.sched(256, 256, 64, 128, 128, 2, 2, 1)) == al.OK
+    assert al.alcop_sched_supported(p, al.sched(128, 128, 64, 64, 64, 2, 1, 1)) == al.ERR_SCHED
+    assert al.alcop_sched_supported(p, al.sched(128, 128, 48, 64, 64, 2, 1, 0)) == al.ERR_SCHED
+    p2 = al.problem(al.OP_GEMM, 2048, 2048, 2080, al.F16, al.F16)       # K % 64 != 0, % 32 == 0
+    assert al.alcop_sched_supported(p2, ok) == al.ERR_SHAPE
+    assert al.alcop_sched_supported(p2, al.sched(128, 128, 32, 64, 64, 3, 2, 1)) == al.OK
+    pc = al.problem(al.OP_CONV2D, 32 * 56 * 56, 64, 576, al.F16, al.F16, conv_C=64)
+    assert al.alcop_sched_supported(pc, al.sched(128, 64, 64, 64, 32, 3, 2, 1)) == al.OK
+    pc32 = al.problem(al.OP_CONV2D, 1024, 64, 9 * 32, al.F16, al.F16, conv_C=32)
+    assert al.alcop_sched_supported(pc32, al.sched(128, 64, 64, 64, 32, 3, 2, 1)) == al.ERR_SHAPE
+    assert al.alcop_sched_supported(pc32, al.sched(128, 64, 32, 64, 32, 3, 2, 1)) == al.OK
+
+
+def test_sweep_of_the_motivating_example_is_built():
+    # tile {64,128,256}^2 x k-tile {32,64} x stages {1..4}: 24 points, two exceed the LDS
+    p = al.problem(al.OP_GEMM, 2048, 2048, 2048, al.F16, al.F16)
+    space = {s.key()[:8] for s in al.alcop_sched_space(p)}
+    waves = {64: 32, 128: 64, 256: 128}
+    feasible = 0
+    for b in (64, 128, 256):
+        for bk in (32, 64):
+            for S in (1, 2, 3, 4):
+                lds = S * 2 * b * bk * 2
+                has = any((b, b, bk, waves[b], waves[b], S, r, f) in space for r in (1, 2) for f in (0, 1))
+                assert has == (lds <= 160 * 1024), (b, bk, S)
+                feasible += has
+    assert feasible == 22
+
+
+def test_space_is_not_empty_for_every_operator():
+    for p in [al.problem(al.OP_GEMM, 512, 512, 512, al.BF16, al.BF16),
+              al.problem(al.OP_BMM, 512, 512, 64, al.F16, al.F16, batch=96, transB=True),
+              al.problem(al.OP_BMM, 512, 64, 512, al.F16, al.F16, batch=96),
+              al.problem(al.OP_CONV2D, 6272, 256, 2304, al.F16, al.F16, conv_C=256)]:
+        sp = al.alcop_sched_space(p)
+        assert len(sp) >= 6
+        assert any(al.alcop_sched_supported(p, s) == al.OK for s in sp)
