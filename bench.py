@@ -27,6 +27,10 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--quick", action="store_true", help="skip the other shapes and the CPU baseline")
+    ap.add_argument("--workload", default="gemm2048", choices=["gemm2048", "gemm8192", "ffn1", "ffn2"],
+                    help="GEMM configuration to time (the headline is gemm2048)")
+    ap.add_argument("--sched", default=None,
+                    help="bm,bn,bk,wm,wn,S,R,F[,raster]: time this schedule only, no tuning (for profiling)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the path is a single-kernel, single-GPU "
@@ -42,12 +46,31 @@ def main():
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
 
-    cfg, A, B = wl.make_inputs("gemm2048")
+    cfg, A, B = wl.make_inputs(a.workload)
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
     Ad, Bd = A.to(dev), B.to(dev)
-    Cd = torch.empty(M, N, dtype=torch.float16, device=dev)
-    prob = al.problem(al.OP_GEMM, M, N, K, al.F16, al.F16)
+    it = al.F16 if cfg["dtype"] == "f16" else al.BF16
+    Cd = torch.empty(M, N, dtype=torch.float16 if cfg["out"] == "f16" else torch.bfloat16, device=dev)
+    prob = al.problem(al.OP_GEMM, M, N, K, it, it)
     flops = 2.0 * M * N * K
+
+    if a.sched:
+        # profiling mode: one fixed schedule, no tuning, a minimal JSON line
+        s = al.sched(*[int(v) for v in a.sched.split(",")])
+        for _ in range(a.warmup):
+            al.alcop_gemm(Ad, Bd, Cd, s)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(a.steps):
+            al.alcop_gemm(Ad, Bd, Cd, s, stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / a.steps
+        print(json.dumps({"workload": a.workload, "schedule": repr(s), "kernel_us": round(us, 3),
+                          "tflops": round(flops / us / 1e6, 1), "steps": a.steps}))
+        return
 
     # ---- tuning: exhaustive (the 100 % reference) and model-ranked top-k ------------------------
     ex = al.alcop_tune(prob, Ad, Bd, Cd, top_k=0, model=0, iters=30)
@@ -94,8 +117,8 @@ def main():
         "metric": "TFLOP/s and % of fp16 MFMA peak per shape; speedup vs 1-stage schedule",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": round(ms_per_step, 6), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "gemm2048: C=A.B, M=N=K=2048, fp16 in, fp32 accumulate, fp16 out",
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": "%s: C=A.B, M=%d N=%d K=%d, %s in, fp32 accumulate, %s out" % (a.workload, M, N, K, cfg["dtype"], cfg["out"]),
                    "schedule": repr(best), "global_batch": 1},
         "pct_of_peak": round(100.0 * value / PEAK_TFLOPS, 2),
         "speedup_vs_1stage_equal_tile": round(us_base / us_best, 3),

@@ -71,6 +71,8 @@ typedef struct {
   int reg_stages;     /* R: 1 = fragment loaded then used; 2 = next fragment prefetched     */
   int fuse_inner;     /* 1 = register pipeline runs across ko (needs R=2 and S>=2)          */
   int raster;         /* block -> tile order: 0 row-major, 1 XCD-grouped panels             */
+  int l2_prefetch;    /* third buffer level (HBM -> L2): lines of k-tile kt+l2_prefetch are  */
+                      /* touched when k-tile kt is issued; 0 = off; needs raster = 1         */
 } alcop_sched;
 
 /* Problem description used by the model / tuner / feasibility entry points. */

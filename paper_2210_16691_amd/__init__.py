@@ -36,17 +36,18 @@ class AlcopError(RuntimeError):
 class Sched(ctypes.Structure):
     """Mirror of ``alcop_sched``."""
     _fields_ = [(n, ctypes.c_int) for n in
-                ("bm", "bn", "bk", "wm", "wn", "stages", "reg_stages", "fuse_inner", "raster")]
+                ("bm", "bn", "bk", "wm", "wn", "stages", "reg_stages", "fuse_inner", "raster",
+                 "l2_prefetch")]
 
     def key(self):
         return tuple(getattr(self, n) for n, _ in self._fields_)
 
     def __repr__(self):
-        return "Sched(%dx%dx%d w%dx%d S%d R%d F%d r%d)" % self.key()
+        return "Sched(%dx%dx%d w%dx%d S%d R%d F%d r%d pf%d)" % self.key()
 
 
-def sched(bm, bn, bk, wm, wn, stages=1, reg_stages=1, fuse_inner=0, raster=1) -> Sched:
-    return Sched(bm, bn, bk, wm, wn, stages, reg_stages, fuse_inner, raster)
+def sched(bm, bn, bk, wm, wn, stages=1, reg_stages=1, fuse_inner=0, raster=1, l2_prefetch=0) -> Sched:
+    return Sched(bm, bn, bk, wm, wn, stages, reg_stages, fuse_inner, raster, l2_prefetch)
 
 
 class Problem(ctypes.Structure):

@@ -94,6 +94,8 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
   if (s.stages < 1 || s.stages > 4 || s.reg_stages < 1 || s.reg_stages > 2) return ALCOP_ERR_SCHED;
   if (s.fuse_inner && (s.reg_stages != 2 || s.stages < 2)) return ALCOP_ERR_SCHED;
   if (s.raster != 0 && s.raster != 1) return ALCOP_ERR_SCHED;
+  if (s.l2_prefetch < 0 || s.l2_prefetch > 64 || (s.l2_prefetch > 0 && s.raster != 1))
+    return ALCOP_ERR_SCHED;
   const KernelEntry* e = find_entry(p, s);
   if (!e) return ALCOP_ERR_SCHED;
   if (e->lds_bytes > 160 * 1024) return ALCOP_ERR_SCHED;
@@ -106,13 +108,23 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
   return ALCOP_OK;
 }
 
+// Depth of the HBM -> L2 level when it is on: look ahead 256 elements of k (a few L2 miss
+// latencies of matrix work at any tile size).
+int default_l2_prefetch(int bk) { return 256 / bk; }
+
 std::vector<alcop_sched> space_of(const alcop_problem& p)
 {
   std::vector<alcop_sched> v;
   const int am = p.op == ALCOP_OP_CONV2D ? 1 : 0;
   for (const KernelEntry& e : registry())
     if (e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.am == am)
-      v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1});
+    {
+      v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1, 0});
+      // the fused multi-level kernels are also offered with the third (HBM -> L2) level on
+      if (e.fuse && e.am == 0)
+        v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1,
+                                default_l2_prefetch(e.bk)});
+    }
   return v;
 }
 
@@ -209,6 +221,12 @@ int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipSt
   p.ntn = (c.N + s.bn - 1) / s.bn;
   p.raster = s.raster;
   p.group_m = std::min(8, p.ntm);
+  // sharers of a panel among the blocks one XCD runs side by side (32 CUs, blocks per CU by LDS)
+  const int per_cu = std::max(1, std::min(2, (160 * 1024) / e->lds_bytes));
+  p.pf_dist = s.l2_prefetch;
+  p.pf_pb = std::max(1, p.group_m);
+  p.pf_pa = std::max(1, std::min(p.ntn, 32 * per_cu / p.pf_pb));
+  while (p.pf_pa > 1 && s.bm / p.pf_pa < 1) p.pf_pa--;
   if (c.op == ALCOP_OP_CONV2D) {
     p.cH = c.cH;
     p.cW = c.cW;

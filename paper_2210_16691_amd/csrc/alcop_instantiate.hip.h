@@ -24,9 +24,9 @@ constexpr bool instance_feasible(int bm, int bn, int bk, int wm, int wn, int s, 
   const int nt = (bm / wm) * (bn / wn) * 64;
   const int a = bm * bk * 2, b = bn * bk * 2;
   if (a % (nt * 16) || b % (nt * 16)) return false;
-  if (s * (a + b) > 160 * 1024) return false;
+  if (s * (a + b) + (nt / 64) * 256 > 160 * 1024) return false;
   if (f && (r != 2 || s < 2)) return false;
-  const int l = (a + b) / (nt * 16);
+  const int l = (a + b) / (nt * 16) + 1;
   if (s >= 2 && (s - 2) * l > 63) return false;
   return true;
 }

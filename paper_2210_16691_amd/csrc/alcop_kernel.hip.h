@@ -50,6 +50,9 @@ struct Params {
   // convolution geometry (AM == 1): x is NHWC, A rows are (img, p, q)
   int cH, cW, cC, cP, cQ, cS, csh, csw, cph, cpw;
   unsigned a_span, b_span;     // conv: bytes of x; unused otherwise
+  // third pipeline level (HBM -> L2): every wave touches lines of k-tile kt + pf_dist when it
+  // issues k-tile kt; the lines of a panel are split among the pf_pa (pf_pb) blocks that share it
+  int pf_dist, pf_pa, pf_pb;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -74,8 +77,10 @@ struct KCfg {
   static constexpr int TM = WM / 32, TN = WN / 32, NKI = BK / 16;
   static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-  static constexpr int LDS_BYTES = S * STAGE_BYTES;
-  static constexpr int NLA = A_BYTES / (NT * 16), NLB = B_BYTES / (NT * 16), L = NLA + NLB;
+  static constexpr int RING_BYTES = S * STAGE_BYTES;
+  static constexpr int LDS_BYTES = RING_BYTES + NWAVES * 256;   // + landing pad of the L2 touches
+  static constexpr int NLA = A_BYTES / (NT * 16), NLB = B_BYTES / (NT * 16);
+  static constexpr int L = NLA + NLB + 1;   // per wave and k-tile: tile loads + one L2 touch
   static constexpr int CPR_A = BK / 8;                       // 16-byte chunks per A-tile row
   static constexpr int RSTEP_A = NT / CPR_A;                 // tile rows covered by one load
   static constexpr int CPR_B = BL ? BK / 8 : BN / 8;
@@ -103,6 +108,16 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :
                : "s"(lds_dst), "v"(voff), "s"(rsrc)
+               : "memory");
+}
+
+__device__ __forceinline__ void touch4(const char* gptr, uint32_t lds_dst)
+{
+  // 4-byte direct-to-LDS load per lane into a landing pad nobody reads: its only purpose is to
+  // bring the 128-byte line it touches into L2 ahead of the tile loads.
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+               :
+               : "s"(lds_dst), "v"(gptr)
                : "memory");
 }
 
@@ -233,30 +248,97 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     }
   }
 
-  // Issue the loads of k-tile `kt` into ring slot `slot`.  Always exactly L loads per wave.
-  auto issue = [&](int kt, int slot) {
-    const bool live = kt < nko;
-    const uint32_t dst = lds0 + (uint32_t)slot * STAGE_BYTES + (uint32_t)wave * 1024u;
-    if constexpr (C::AM == 0) {
-      const uint32_t ka = live ? (uint32_t)kt * (BK * 2) : 0x80000000u;
-#pragma unroll
-      for (int i = 0; i < NLA; i++)
-        dma16(rsrcA, voffA + ka + (uint32_t)i * stepA, dst + i * (NWAVES * 1024));
-    } else {
-      const uint32_t tap = (uint32_t)(((cr * p.cW + cs) * p.cC + cc0) * 2);
-#pragma unroll
-      for (int i = 0; i < NLA; i++) {
-        const bool ok = live && (unsigned)(ih0[i] + cr) < (unsigned)p.cH &&
-                        (unsigned)(iw0[i] + cs) < (unsigned)p.cW;
-        dma16(rsrcA, ok ? coff[i] + tap : 0x80000000u, dst + i * (NWAVES * 1024));
+  // ---- HBM -> L2 touches (third pipeline level) --------------------------------------------
+  // The blocks of one XCD that run side by side load the same A row-panel (those with equal tm)
+  // or B column-panel (equal tn) at about the same time, so each line misses L2 once and all
+  // sharers wait for that miss.  Touching the line pf_dist k-tiles earlier, once, by one of the
+  // sharers, turns the tile loads into L2 hits.  Lane x of the block owns one line per k-tile.
+  const char* pf_ptr;
+  uint32_t pf_step = 0;
+  const int pf_d = p.pf_dist < nko - 1 ? p.pf_dist : nko - 1;   // never past the last k-tile
+  {
+    const int x = wave * 64 + lane;
+    const char* abase = (const char*)p.A + ((long)batch * p.strideA + (long)tm * BM * p.lda) * 2;
+    pf_ptr = (C::AM == 0) ? abase : (const char*)p.B;     // a valid address for idle lanes
+    if (pf_d > 0) {
+      const int na = (C::AM == 0) ? BM / p.pf_pa : 0;
+      if (x < na) {
+        int row = x * p.pf_pa + tn % p.pf_pa;
+        if (tm * BM + row >= p.M) row = 0;
+        pf_ptr = abase + (long)row * p.lda * 2;
+        pf_step = BK * 2;
+      } else {
+        const int j = x - na;
+        if constexpr (C::BL == 1) {
+          if (j < BN / p.pf_pb) {
+            int row = j * p.pf_pb + tm % p.pf_pb;
+            if (tn * BN + row >= p.N) row = 0;
+            pf_ptr = (const char*)p.B +
+                     ((long)batch * p.strideB + ((long)tn * BN + row) * p.ldb) * 2;
+            pf_step = BK * 2;
+          }
+        } else {
+          constexpr int LPR = (BN * 2) / 128;               // 128-byte lines per k-row of the tile
+          if (j < BK * LPR / p.pf_pb) {
+            const int line = j * p.pf_pb + tm % p.pf_pb;
+            const int row = line / LPR;
+            int seg = line % LPR;
+            if (tn * BN + seg * 64 >= p.N) seg = 0;
+            pf_ptr = (const char*)p.B +
+                     ((long)batch * p.strideB + (long)row * p.ldb + (long)tn * BN + seg * 64) * 2;
+            pf_step = (uint32_t)(BK * p.ldb * 2);
+          }
+        }
       }
+      pf_ptr += (long)pf_step * pf_d;
+    }
+  }
+  const uint32_t pf_dst = lds0 + C::RING_BYTES + (uint32_t)wave * 256u;
+
+  // Loads of one k-tile: stage_begin fixes the wave-uniform offsets of k-tile `kt` and ring slot
+  // `slot`; issue_one(i) emits load i of the L loads a wave owns (A loads first, then B);
+  // stage_end advances the convolution tap.  Always exactly L loads per wave and stage.
+  uint32_t st_ka = 0, st_kb = 0, st_dst = 0, st_tap = 0;
+  bool st_live = false, st_pf_live = false;
+  auto stage_begin = [&](int kt, int slot) {
+    st_live = kt < nko;
+    st_pf_live = kt + pf_d + 1 < nko;
+    st_dst = lds0 + (uint32_t)slot * STAGE_BYTES + (uint32_t)wave * 1024u;
+    if constexpr (C::AM == 0)
+      st_ka = st_live ? (uint32_t)kt * (BK * 2) : 0x80000000u;
+    else
+      st_tap = (uint32_t)(((cr * p.cW + cs) * p.cC + cc0) * 2);
+    st_kb = st_live ? (uint32_t)kt * kstepB : 0x80000000u;
+  };
+  auto issue_one = [&](int idx) {
+    if (idx < NLA) {
+      const int i = idx;
+      if constexpr (C::AM == 0) {
+        dma16(rsrcA, voffA + st_ka + (uint32_t)i * stepA, st_dst + i * (NWAVES * 1024));
+      } else {
+        const bool ok = st_live && (unsigned)(ih0[i] + cr) < (unsigned)p.cH &&
+                        (unsigned)(iw0[i] + cs) < (unsigned)p.cW;
+        dma16(rsrcA, ok ? coff[i] + st_tap : 0x80000000u, st_dst + i * (NWAVES * 1024));
+      }
+    } else if (idx < NLA + NLB) {
+      const int i = idx - NLA;
+      dma16(rsrcB, voffB + st_kb + (uint32_t)i * stepB, st_dst + A_BYTES + i * (NWAVES * 1024));
+    } else {
+      touch4(pf_ptr, pf_dst);
+      if (st_pf_live) pf_ptr += pf_step;      // stop at the last k-tile: never run past the operand
+    }
+  };
+  auto stage_end = [&]() {
+    if constexpr (C::AM == 1) {
       cc0 += BK;
       if (cc0 == p.cC) { cc0 = 0; cs++; if (cs == p.cS) { cs = 0; cr++; } }
     }
-    const uint32_t kb = live ? (uint32_t)kt * kstepB : 0x80000000u;
+  };
+  auto issue = [&](int kt, int slot) {
+    stage_begin(kt, slot);
 #pragma unroll
-    for (int i = 0; i < NLB; i++)
-      dma16(rsrcB, voffB + kb + (uint32_t)i * stepB, dst + A_BYTES + i * (NWAVES * 1024));
+    for (int i = 0; i < C::L; i++) issue_one(i);
+    stage_end();
   };
 
   // ---- LDS -> register consumers ---------------------------------------------------------
@@ -289,21 +371,34 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     }
   }
 
-  auto load_frags = [&](uint32_t sbase, int ki, u32x4(&fa)[TM], u32x4(&fb)[TN]) {
+  // One LDS read instruction of fragment `ki`: r < TM reads A sub-tile r; the rest read B
+  // (one ds_read_b128 per sub-tile when K-contiguous, two transposing 8-byte reads otherwise).
+  // Read addresses of the slot being consumed (lane base + slot base), refreshed once per k-tile
+  // so that every read is "register + immediate".
+  constexpr int NRB = C::BL ? NKI : TN;
+  uint32_t curA[NKI], curB[NRB];
+  auto set_read_slot = [&](uint32_t sbase) {
 #pragma unroll
-    for (int t = 0; t < TM; t++) fa[t] = lds_read16(sbase + rdA[ki] + t * (32 * BK * 2));
-    if constexpr (C::BL == 1) {
+    for (int i = 0; i < NKI; i++) curA[i] = sbase + rdA[i];
 #pragma unroll
-      for (int t = 0; t < TN; t++) fb[t] = lds_read16(sbase + rdB[ki] + t * (32 * BK * 2));
+    for (int i = 0; i < NRB; i++) curB[i] = sbase + rdB[i];
+  };
+  constexpr int NRI = TM + TN * (C::BL ? 1 : 2);
+  auto read_one = [&](int ki, int r, u32x4(&fa)[TM], u32x4(&fb)[TN]) {
+    if (r < TM) {
+      fa[r] = lds_read16(curA[ki] + r * (32 * BK * 2));
+    } else if constexpr (C::BL == 1) {
+      fb[r - TM] = lds_read16(curB[ki] + (r - TM) * (32 * BK * 2));
     } else {
-#pragma unroll
-      for (int t = 0; t < TN; t++) {
-        const uint32_t a = sbase + rdB[t] + ki * (16 * BN * 2);
-        const u32x2 lo = lds_read_tr8(a);
-        const u32x2 hi = lds_read_tr8(a + 4 * BN * 2);
-        fb[t] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-      }
+      const int t = (r - TM) >> 1, h = (r - TM) & 1;
+      const u32x2 v = lds_read_tr8(curB[t] + ki * (16 * BN * 2) + h * (4 * BN * 2));
+      fb[t][2 * h] = v[0];
+      fb[t][2 * h + 1] = v[1];
     }
+  };
+  auto load_frags = [&](int ki, u32x4(&fa)[TM], u32x4(&fb)[TN]) {
+#pragma unroll
+    for (int r = 0; r < NRI; r++) read_one(ki, r, fa, fb);
   };
 
   f32x16 acc[TN][TM];
@@ -314,40 +409,69 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
-  auto mma_all = [&](u32x4(&fa)[TM], u32x4(&fb)[TN]) {
+  // One register-level step: the TN*TM matrix instructions on fragment (ua, ub); the LDS reads
+  // of the next fragment (if nread) are issued two per matrix instruction starting right after
+  // instruction `first`, so that they have returned long before the step ends; the
+  // direct-to-LDS loads [d0, d1) of the k-tile being fetched are spread evenly.  `first` > 0
+  // leaves room for the block-wide synchronisation that `sync` performs after instruction
+  // first-1.  The compiler must keep exactly this order (sched_barrier).
+  constexpr int NMM = TM * TN;
+  auto step = [&](u32x4(&ua)[TM], u32x4(&ub)[TN], bool nread, int nki, u32x4(&na)[TM],
+                  u32x4(&nb)[TN], int d0, int d1, int first, auto&& sync) {
+    const int gaps = NMM - first > 0 ? NMM - first : 1;
+    const int rpg = (NRI + gaps - 1) / gaps > 2 ? (NRI + gaps - 1) / gaps : 2;   // reads per gap
 #pragma unroll
-    for (int i = 0; i < TN; i++)
+    for (int m = 0; m < NMM; m++) {
+      const int i = m / TM, j = m % TM;
+      acc[i][j] = mma<C::DT>(ub[i], ua[j], acc[i][j]);
+      if (m + 1 == first || (first >= NMM && m == NMM - 1)) sync();
+      if (nread && (m >= first || m == NMM - 1)) {
+        const int g = m >= first ? m - first : 0;
 #pragma unroll
-      for (int j = 0; j < TM; j++) acc[i][j] = mma<C::DT>(fb[i], fa[j], acc[i][j]);
+        for (int r = g * rpg; r < (g + 1) * rpg && r < NRI; r++) read_one(nki, r, na, nb);
+      }
+#pragma unroll
+      for (int d = d0 + m * (d1 - d0) / NMM; d < d0 + (m + 1) * (d1 - d0) / NMM; d++) issue_one(d);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
+  auto no_sync = [] {};
 
   u32x4 fa[C::R][TM], fb[C::R][TN];
 
   // ---- the pipelined main loop -----------------------------------------------------------
   if constexpr (C::FUSE) {
-    // Holistic pipeline over (ko, ki): Fig. 3(d).
+    // Holistic pipeline over (ko, ki): Fig. 3(d).  The loads of k-tile ko+S-1 are issued during
+    // steps 0..NKI-2; the wait for k-tile ko+1 and the barrier open step NKI-1, whose reads
+    // already fetch the first fragment of k-tile ko+1.
 #pragma unroll
     for (int s = 0; s < S - 1; s++) issue(s, s);
     wait_vm<C::WAIT>();
     block_barrier();
-    load_frags(lds0, 0, fa[0], fb[0]);
+    set_read_slot(lds0);
+    load_frags(0, fa[0], fb[0]);
     int rslot = 0, wslot = S - 1;
     for (int ko = 0; ko < nko; ko++) {
-      issue(ko + S - 1, wslot);
+      stage_begin(ko + S - 1, wslot);
       wslot = (wslot + 1 == S) ? 0 : wslot + 1;
 #pragma unroll
       for (int ki = 0; ki < NKI; ki++) {
         if (ki == NKI - 1) {
-          wait_vm<C::WAIT>();            // consumer_wait: k-tile ko+1 has landed (this wave)
-          wait_lds();                    // consumer_release: my reads of slot ko are done
-          block_barrier();               // ... for every wave
-          rslot = (rslot + 1 == S) ? 0 : rslot + 1;
-          load_frags(lds0 + rslot * STAGE_BYTES, 0, fa[(ki + 1) & 1], fb[(ki + 1) & 1]);
+          // the synchronisation sits after the first quarter of this step's matrix instructions
+          constexpr int FIRST = NMM >= 8 ? NMM / 4 : 1;
+          step(fa[ki & 1], fb[ki & 1], true, 0, fa[(ki + 1) & 1], fb[(ki + 1) & 1], 0, 0, FIRST, [&] {
+            wait_vm<C::WAIT>();          // consumer_wait: k-tile ko+1 has landed (this wave)
+            wait_lds();                  // consumer_release: my reads of slot ko are done
+            block_barrier();             // ... for every wave
+            rslot = (rslot + 1 == S) ? 0 : rslot + 1;
+            set_read_slot(lds0 + rslot * STAGE_BYTES);
+          });
         } else {
-          load_frags(lds0 + rslot * STAGE_BYTES, ki + 1, fa[(ki + 1) & 1], fb[(ki + 1) & 1]);
+          step(fa[ki & 1], fb[ki & 1], true, ki + 1, fa[(ki + 1) & 1], fb[(ki + 1) & 1],
+               ki * C::L / (NKI - 1), (ki + 1) * C::L / (NKI - 1), 0, no_sync);
         }
-        mma_all(fa[ki & 1], fb[ki & 1]);
       }
+      stage_end();
     }
   } else {
     if constexpr (S >= 2) {
@@ -360,7 +484,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
         wait_vm<C::WAIT>();              // consumer_wait for k-tile ko
         wait_lds();
         block_barrier();                 // also releases slot (ko-1) mod S
-        issue(ko + S - 1, wslot);
+        stage_begin(ko + S - 1, wslot);  // its loads are spread over the steps below
       } else {
         wait_lds();
         block_barrier();                 // producer_acquire: slot 0 is free
@@ -369,25 +493,27 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
         block_barrier();
       }
       wslot = (wslot + 1 == S) ? 0 : wslot + 1;
-      const uint32_t sbase = lds0 + rslot * STAGE_BYTES;
+      set_read_slot(lds0 + rslot * STAGE_BYTES);
       rslot = (rslot + 1 == S) ? 0 : rslot + 1;
+      constexpr int DL = (S >= 2) ? C::L : 0;   // loads to interleave (none when S = 1)
       if constexpr (C::R == 2) {
         // register-level pipeline restarted in every ko: Fig. 3(c)
-        load_frags(sbase, 0, fa[0], fb[0]);
+        load_frags(0, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ki = 0; ki < NKI; ki++) {
-          if (ki + 1 < NKI) load_frags(sbase, ki + 1, fa[(ki + 1) & 1], fb[(ki + 1) & 1]);
-          mma_all(fa[ki & 1], fb[ki & 1]);
-        }
+        for (int ki = 0; ki < NKI; ki++)
+          step(fa[ki & 1], fb[ki & 1], ki + 1 < NKI, (ki + 1) % NKI, fa[(ki + 1) & 1],
+               fb[(ki + 1) & 1], ki * DL / NKI, (ki + 1) * DL / NKI, 0, no_sync);
       } else {
-        // single-level: load a fragment, use it (Fig. 3(b))
+        // single-level: load a fragment, then use it (Fig. 3(b))
 #pragma unroll
         for (int ki = 0; ki < NKI; ki++) {
-          load_frags(sbase, ki, fa[0], fb[0]);
-          mma_all(fa[0], fb[0]);
+          load_frags(ki, fa[0], fb[0]);
           __builtin_amdgcn_sched_barrier(0);
+          step(fa[0], fb[0], false, 0, fa[0], fb[0], ki * DL / NKI, (ki + 1) * DL / NKI, 0, no_sync);
         }
       }
+      if constexpr (S >= 2) stage_end();
     }
   }
   wait_vm<0>();   // drain the zero-fill loads of the ring's tail before the wave may retire
