@@ -78,7 +78,10 @@ struct KCfg {
   static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int RING_BYTES = S * STAGE_BYTES;
-  static constexpr int LDS_BYTES = RING_BYTES + NWAVES * 256;   // + landing pad of the L2 touches
+  static constexpr int EPI_WAVE_BYTES = 32 * (WN * 4 + 16);     // epilogue band, fp32 worst case
+  static constexpr int MAIN_BYTES = RING_BYTES + NWAVES * 256;  // + landing pad of the L2 touches
+  static constexpr int LDS_BYTES =
+      MAIN_BYTES > NWAVES * EPI_WAVE_BYTES ? MAIN_BYTES : NWAVES * EPI_WAVE_BYTES;
   static constexpr int NLA = A_BYTES / (NT * 16), NLB = B_BYTES / (NT * 16);
   static constexpr int L = NLA + NLB + 1;   // per wave and k-tile: tile loads + one L2 touch
   static constexpr int CPR_A = BK / 8;                       // 16-byte chunks per A-tile row
@@ -516,38 +519,51 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       if constexpr (S >= 2) stage_end();
     }
   }
-  wait_vm<0>();   // drain the zero-fill loads of the ring's tail before the wave may retire
+  wait_vm<0>();   // drain the zero-fill loads of the ring's tail before the ring is reused
+  wait_lds();
+  block_barrier();   // every wave has finished reading the ring
 
-  // ---- epilogue: convert and store (Table 1, epilogue term) --------------------------------
-  const int m_base = tm * BM + wm * WM + (lane & 31);
-  const int n_base = tn * BN + wn * WN + 4 * (lane >> 5);
-  char* Cb = (char*)p.C;
-  const long cbatch = (long)batch * p.strideC;
+  // ---- epilogue: convert, transpose through LDS, store rows (Table 1, epilogue term) --------
+  // A lane holds 4 consecutive n of one row m (16 such groups per 32x32 sub-tile); stored as is,
+  // a wave instruction would scatter 8-byte pieces over 32 rows.  Each wave instead parks one
+  // 32-row band of its tile in its own LDS region (row stride padded by 16 B) and reads it back
+  // with 16 bytes per lane along the row, so every global store covers whole 128-byte lines.
+  auto epilogue = [&](auto zero) {
+    using OT = decltype(zero);
+    constexpr int OB = sizeof(OT);
+    constexpr int RS = WN * OB + 16;                 // LDS row stride of the band
+    constexpr int LPR = WN * OB / 16;                // lanes per row when reading back
+    constexpr int RPI = 64 / LPR;                    // rows per read instruction
+    typedef OT ot4 __attribute__((ext_vector_type(4)));
+    const uint32_t ebase = lds0 + (uint32_t)wave * C::EPI_WAVE_BYTES;
+    const int m0 = tm * BM + wm * WM, n0 = tn * BN + wn * WN;
+    char* Cb = (char*)p.C + (long)batch * p.strideC * OB;
 #pragma unroll
-  for (int j = 0; j < TM; j++) {
-    const int m = m_base + j * 32;
-    if (m >= p.M) continue;
-    const long rowoff = cbatch + (long)m * p.ldc;
+    for (int j = 0; j < TM; j++) {
 #pragma unroll
-    for (int i = 0; i < TN; i++) {
+      for (int i = 0; i < TN; i++)
 #pragma unroll
-      for (int vq = 0; vq < 4; vq++) {
-        const int n = n_base + i * 32 + 8 * vq;
-        if (n >= p.N) continue;
-        const float v0 = acc[i][j][4 * vq + 0], v1 = acc[i][j][4 * vq + 1];
-        const float v2 = acc[i][j][4 * vq + 2], v3 = acc[i][j][4 * vq + 3];
-        if (p.out_dtype == 2) {
-          *(f32x4*)(Cb + (rowoff + n) * 4) = f32x4{v0, v1, v2, v3};
-        } else if (p.out_dtype == 0) {
-          f16x4 h = {(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};
-          *(f16x4*)(Cb + (rowoff + n) * 2) = h;
-        } else {
-          bf16x4 h = {(__bf16)v0, (__bf16)v1, (__bf16)v2, (__bf16)v3};
-          *(bf16x4*)(Cb + (rowoff + n) * 2) = h;
+        for (int vq = 0; vq < 4; vq++) {
+          ot4 h = {(OT)acc[i][j][4 * vq + 0], (OT)acc[i][j][4 * vq + 1],
+                   (OT)acc[i][j][4 * vq + 2], (OT)acc[i][j][4 * vq + 3]};
+          *(ALCOP_LDS ot4*)(uintptr_t)(ebase + (lane & 31) * RS +
+                                       (i * 32 + 8 * vq + 4 * (lane >> 5)) * OB) = h;
         }
+#pragma unroll
+      for (int t = 0; t < 32 / RPI; t++) {
+        const int r = t * RPI + lane / LPR, c16 = lane % LPR;
+        const u32x4 v = *(const ALCOP_LDS u32x4*)(uintptr_t)(ebase + r * RS + c16 * 16);
+        const int m = m0 + j * 32 + r, n = n0 + c16 * (16 / OB);
+        if (m < p.M && n < p.N) *(u32x4*)(Cb + ((long)m * p.ldc + n) * OB) = v;
       }
     }
-  }
+  };
+  if (p.out_dtype == 2)
+    epilogue(0.0f);
+  else if (p.out_dtype == 0)
+    epilogue((_Float16)0);
+  else
+    epilogue((__bf16)0);
 }
 
 }  // namespace alcop
