@@ -29,6 +29,9 @@ def main():
     ap.add_argument("--quick", action="store_true", help="skip the other shapes and the CPU baseline")
     ap.add_argument("--workload", default="gemm2048", choices=["gemm2048", "gemm8192", "ffn1", "ffn2"],
                     help="GEMM configuration to time (the headline is gemm2048)")
+    ap.add_argument("--tune-report", action="store_true",
+                    help="exhaustive search on every configuration and the best-in-top-k curves of the "
+                         "two static models (the paper's Sec. 6.4 experiment); prints one JSON object")
     ap.add_argument("--sched", default=None,
                     help="bm,bn,bk,wm,wn,S,R,F[,raster]: time this schedule only, no tuning (for profiling)")
     a = ap.parse_args()
@@ -45,6 +48,10 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
+
+    if a.tune_report:
+        print(json.dumps(tune_report(al, wl, torch, dev)))
+        return
 
     cfg, A, B = wl.make_inputs(a.workload)
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
@@ -140,6 +147,58 @@ def main():
         out["other_shapes"] = other_shapes(al, wl, torch, dev)
         out["cpu_baseline"] = cpu_baseline(wl, A, B, flops)
     print(json.dumps(out))
+
+
+def _setup(al, wl, torch, dev, name):
+    """Device tensors, problem descriptor and flop / byte counts of a named configuration."""
+    cfg, A, B = wl.make_inputs(name)
+    Ad, Bd = A.to(dev), B.to(dev)
+    it = al.F16 if cfg["dtype"] == "f16" else al.BF16
+    tdt = torch.float16 if cfg["out"] == "f16" else torch.bfloat16
+    conv = None
+    if cfg["kind"] == "gemm":
+        M, N, K, b = cfg["M"], cfg["N"], cfg["K"], 1
+        prob = al.problem(al.OP_GEMM, M, N, K, it, it)
+        Cd = torch.empty(M, N, dtype=tdt, device=dev)
+    elif cfg["kind"] == "bmm":
+        M, N, K, b = cfg["M"], cfg["N"], cfg["K"], cfg["batch"]
+        prob = al.problem(al.OP_BMM, M, N, K, it, it, batch=b, transB=cfg["transB"])
+        Cd = torch.empty(b, M, N, dtype=tdt, device=dev)
+    else:
+        n, H, W, C, Ko, R, S = (cfg[k] for k in ("N", "H", "W", "C", "K", "R", "S"))
+        M, N, K, b = n * H * W, Ko, R * S * C, 1
+        prob = al.problem(al.OP_CONV2D, M, N, K, it, it, conv_C=C)
+        Cd = torch.empty(n, H, W, Ko, dtype=tdt, device=dev)
+        conv = (n, H, W, C, Ko, R, S, 1, 1, 1, 1)
+    flops = 2.0 * M * N * K * b
+    byts = 2.0 * (A.numel() + B.numel() + Cd.numel())
+    return prob, Ad, Bd, Cd, conv, flops, byts
+
+
+def tune_report(al, wl, torch, dev):
+    """Exhaustive search per configuration; best-in-top-k of the pipeline-aware model and of the
+    bottleneck-only model, normalised to the exhaustive best (paper Sec. 6.4 / 6.5 metrics)."""
+    rep = {}
+    for name in ("gemm2048", "ffn1", "ffn2", "gemm8192", "bmm_qk", "bmm_pv", "conv56", "conv14"):
+        prob, Ad, Bd, Cd, conv, flops, byts = _setup(al, wl, torch, dev, name)
+        iters = 5 if name == "gemm8192" else 30
+        ex = al.alcop_tune(prob, Ad, Bd, Cd, top_k=0, model=0, iters=iters, conv=conv)
+        meas = [(s, us) for s, _, us in ex.log]
+        best = min(us for _, us in meas)
+        curves = {}
+        for model in (0, 1):
+            order = sorted(range(len(meas)),
+                           key=lambda i: (al.alcop_model_predict(prob, meas[i][0], model)[0], i))
+            curves["model%d" % model] = {
+                str(k): round(100.0 * best / min(meas[i][1] for i in order[:k]), 1)
+                for k in (1, 5, 10, 20, 50) if k <= len(meas)}
+        top = sorted(meas, key=lambda t: t[1])[:5]
+        rep[name] = {"space": ex.space, "exhaustive_best_us": round(best, 2),
+                     "tflops": round(flops / best / 1e6, 1), "gbs": round(byts / best / 1e3, 1),
+                     "best_in_top_k_pct": curves,
+                     "top5": [[repr(s), round(us, 2)] for s, us in top],
+                     "all": [[list(s.key()), round(us, 3)] for s, us in meas]}
+    return rep
 
 
 def other_shapes(al, wl, torch, dev):

@@ -16,6 +16,11 @@ follows (the same readings are listed in the design doc):
     patch; every distinct row panel and column panel is fetched once per outer iteration.
   * Without inner-pipeline fusion (not modelled by the paper, which assumes the fused steady
     state) one fragment load per outer iteration is exposed when R = 2.
+  * LDS port occupancy (an addition to Table 1 for this machine): T_smem_use is at least the time
+    the single LDS port needs to move the fragment reads of every wave (K-contiguous operand at
+    128 B/clk, N-contiguous operand through the transposing read at ~240 B/clk) plus the
+    direct-to-LDS writes of one k-tile.
+  * Clock: rates are taken at the ~1.8 GHz a GEMM sustains under the power cap.
 
 Pins (tests/test_model.py): the pipeline latency model against hand-computed values and the
 equivalence of its two printed forms (Table 1 and the captions of Fig. 7); every other row of
@@ -33,9 +38,10 @@ class Device:
     simd_per_cu: int = 4
     lds_bytes: float = 163840.0
     regs_per_lane: float = 512.0
-    flop_per_us_cu: float = 4096.0 * 2400.0
-    lat_lds: float = 128.0 / 2400.0
-    bw_lds_cu: float = 128.0 * 2400.0
+    flop_per_us_cu: float = 4096.0 * 1800.0      # sustained clock under the power cap ~1.8 GHz
+    lat_lds: float = 128.0 / 1800.0
+    bw_lds_cu: float = 128.0 * 1800.0            # ds_read_b128 and DMA writes
+    bw_lds_tr_cu: float = 240.0 * 1800.0         # transposing 8-byte read
     lat_llc: float = 0.6
     bw_llc: float = 16.0e6
     lat_dram: float = 1.2
@@ -58,7 +64,8 @@ def pipeline_latency_caption_form(t_load, t_use, n_loop, n_pipe, n_mplx):
     return (t_load + t_use) * n_loop / n_pipe
 
 
-def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Device = Device()):
+def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Device = Device(),
+            transB: bool = False):
     """Returns a dict of the Table 1 quantities (microseconds)."""
     ntm, ntn = math.ceil(M / bm), math.ceil(N / bn)
     tiles = ntm * ntn
@@ -90,6 +97,12 @@ def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Devi
     t_smem_use = pipeline_latency(t_reg_load, t_compute, n_reg_loop, R, n_mplx_inner)
     if not fuse and R >= 2:
         t_smem_use += t_reg_load
+    # LDS port occupancy: fragment reads of all waves + DMA writes of the next k-tile share one port
+    a_read = bm * bk * 2 * (bn // wn)
+    b_read = bn * bk * 2 * (bm // wm)
+    t_port = (a_read / dev.bw_lds_cu + b_read / (dev.bw_lds_cu if transB else dev.bw_lds_tr_cu)
+              + bytes_one_smem_loop / dev.bw_lds_cu) * n_blk_per_cu
+    t_smem_use = max(t_smem_use, t_port)
 
     # Memory Latency Model
     t_llc_load = dev.lat_llc + bytes_one_smem_loop * n_blk_per_batch / dev.bw_llc

@@ -554,7 +554,8 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
         const int r = t * RPI + lane / LPR, c16 = lane % LPR;
         const u32x4 v = *(const ALCOP_LDS u32x4*)(uintptr_t)(ebase + r * RS + c16 * 16);
         const int m = m0 + j * 32 + r, n = n0 + c16 * (16 / OB);
-        if (m < p.M && n < p.N) *(u32x4*)(Cb + ((long)m * p.ldc + n) * OB) = v;
+        if (m < p.M && n < p.N)
+          __builtin_nontemporal_store(v, (u32x4*)(Cb + ((long)m * p.ldc + n) * OB));
       }
     }
   };

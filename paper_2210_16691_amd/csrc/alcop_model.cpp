@@ -75,6 +75,18 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   // The paper's T_smem_use is the fused steady state.  Without fusion the register pipeline is
   // refilled in every outer iteration: one exposed fragment load per ko.
   if (!s.fuse_inner && s.reg_stages >= 2) t_smem_use += t_reg_load;
+  // LDS port occupancy (not in Table 1): the LDS serves the fragment reads of every wave and
+  // the direct-to-LDS writes of the incoming k-tile through one port.  The K-contiguous operand
+  // is read at bw_lds, the N-contiguous one through the faster transposing read.  However well
+  // latencies are hidden, a k-tile cannot be consumed faster than the port moves its bytes.
+  {
+    const double a_read = bm * bk * 2.0 * (bn / wn);   // every A row is read by the waves along n
+    const double b_read = bn * bk * 2.0 * (bm / wm);
+    const double t_port = (a_read / dev.bw_lds_cu +
+                           b_read / (prob.transB ? dev.bw_lds_cu : dev.bw_lds_tr_cu) +
+                           stage_bytes / dev.bw_lds_cu) * blk_per_cu;
+    t_smem_use = std::max(t_smem_use, t_port);
+  }
 
   // --- memory latency
   const double t_llc = dev.lat_llc + stage_bytes * n_in_batch / dev.bw_llc;

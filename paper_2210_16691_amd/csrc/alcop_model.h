@@ -11,9 +11,13 @@ struct Device {
   int simd_per_cu = 4;              // matrix pipes per CU
   double lds_bytes = 163840.0;      // LDS per CU
   double regs_per_lane = 512.0;     // VGPR + AGPR budget per SIMD lane
-  double flop_per_us_cu = 4096.0 * 2400.0;   // dense fp16/bf16 MFMA: 4096 flop/clk/CU at 2.4 GHz
-  double lat_lds = 128.0 / 2400.0;
-  double bw_lds_cu = 128.0 * 2400.0;          // LDS read bytes/us per CU
+  // dense fp16/bf16 MFMA: 4096 flop/clk/CU; the clock a GEMM sustains under the power cap is
+  // about 1.8 GHz (measured inside the kernel), not the 2.4 GHz peak
+  double clk_per_us = 1800.0;
+  double flop_per_us_cu = 4096.0 * 1800.0;
+  double lat_lds = 128.0 / 1800.0;
+  double bw_lds_cu = 128.0 * 1800.0;          // ds_read_b128 / DMA write: 128 B/clk per CU
+  double bw_lds_tr_cu = 240.0 * 1800.0;       // ds_read_b64_tr_b16: ~240 B/clk per CU (measured)
   double lat_llc = 0.6, bw_llc = 16.0e6;      // L2 / Infinity Cache -> CU, aggregate
   double lat_dram = 1.2, bw_dram = 8.0e6;     // HBM3E read
   double lat_dram_write = 1.0, bw_dram_write = 8.0e6;

@@ -38,14 +38,18 @@ def test_table_rows_by_hand():
     r = pm.predict(2048, 2048, 2048, 1, 2, 128, 128, 64, 64, 64, 3, 2, True, d)
     # scheduler: 256 blocks on 256 CUs -> one block per CU, one batch
     assert r["n_blk_per_cu"] == 1 and r["n_threadblk_batch"] == 1
-    # compute: 2*128*128*16 flop on 4096 flop/clk * 2400 clk/us, 4 waves fill the 4 pipes
+    # compute: 2*128*128*16 flop on 4096 flop/clk * 1800 clk/us, 4 waves fill the 4 pipes
     assert r["util"] == 1.0
-    assert r["t_compute"] == pytest.approx(524288 / 9830400.0)
+    assert r["t_compute"] == pytest.approx(524288 / (4096 * 1800.0))
     # register load: 128 clk latency + 4 waves * (64+64)*16*2 B at 128 B/clk
-    assert r["t_reg_load"] == pytest.approx((128 + 16384 / 128) / 2400.0)
+    assert r["t_reg_load"] == pytest.approx((128 + 16384 / 128) / 1800.0)
     # inner pipeline, R=2, one wave per pipe: hidden iff t_reg_load <= t_compute
     assert r["t_reg_load"] > r["t_compute"]
-    assert r["t_smem_use"] == pytest.approx((r["t_reg_load"] + r["t_compute"]) * 4 / 2)
+    t_pipe = (r["t_reg_load"] + r["t_compute"]) * 4 / 2
+    # LDS port: A 128x64x2 B read by 2 waves along n at 128 B/clk, B likewise at 240 B/clk,
+    # plus the 32 KiB k-tile written at 128 B/clk
+    t_port = (32768 / 128 + 32768 / 240 + 32768 / 128) / 1800.0
+    assert r["t_smem_use"] == pytest.approx(max(t_pipe, t_port))
     # memory: LLC term 0.6 + 256 blocks * 32 KiB / 16e6 ; DRAM term 1.2 + (16+16 panels)*128*64*2/8e6
     t_llc = 0.6 + 256 * 32768 / 16.0e6
     t_dram = 1.2 + 32 * 128 * 64 * 2 / 8.0e6
@@ -95,7 +99,7 @@ def test_library_model_matches_oracle(P):
     for s in space:
         us, terms = al.alcop_model_predict(prob, s, 0)
         r = pm.predict(P["M"], P["N"], P["K"], P["batch"], ob, s.bm, s.bn, s.bk, s.wm, s.wn,
-                       s.stages, s.reg_stages, bool(s.fuse_inner))
+                       s.stages, s.reg_stages, bool(s.fuse_inner), transB=P["tb"])
         want = [r[k] for k in ("t_kernel", "t_threadblk", "t_init", "t_main_loop", "t_epilogue",
                                "t_smem_load", "t_smem_use", "n_threadblk_batch")]
         assert us == pytest.approx(r["t_kernel"], rel=1e-12)
