@@ -32,6 +32,9 @@ def main():
     ap.add_argument("--tune-report", action="store_true",
                     help="exhaustive search on every configuration and the best-in-top-k curves of the "
                          "two static models (the paper's Sec. 6.4 experiment); prints one JSON object")
+    ap.add_argument("--copy-calib", type=int, default=0, metavar="MiB",
+                    help="run a plain device-to-device copy of this many MiB --steps times and exit "
+                         "(calibrates the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     ap.add_argument("--sched", default=None,
                     help="bm,bn,bk,wm,wn,S,R,F[,raster]: time this schedule only, no tuning (for profiling)")
     a = ap.parse_args()
@@ -48,6 +51,16 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
+
+    if a.copy_calib:
+        n = a.copy_calib << 20
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(a.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": n, "steps": a.steps}))
+        return
 
     if a.tune_report:
         print(json.dumps(tune_report(al, wl, torch, dev)))
@@ -120,6 +133,14 @@ def main():
     value = flops / (ms_per_step * 1e-3) / 1e12
     achieved = flops / (kernel_us * 1e-6) / 1e12
 
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tf):
+        # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
+        rec = json.load(open(tf)).get(a.workload)
+        if rec and rec.get("schedule") == repr(best):
+            traffic = rec["fetch_bytes"] + rec["write_bytes"]
+
     out = {
         "metric": "TFLOP/s and % of fp16 MFMA peak per shape; speedup vs 1-stage schedule",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps,
@@ -137,7 +158,8 @@ def main():
                   "best_in_top5_pct": round(100 * best_in_top(5, 0), 1),
                   "exhaustive_best": repr(ex.best), "exhaustive_best_us": round(ex.best_us, 2)},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS, 4), "traffic": traffic,
+                     "algorithmic_bytes": 2 * (M * K + K * N) + 2 * M * N,
                      "kernel_us": round(kernel_us, 3)},
         "paper_context": "A100/TVM: 1.23x mean (0.95-1.73x) single-operator speedup from pipelining; "
                          "another machine, context only",
