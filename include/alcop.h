@@ -152,7 +152,11 @@ int alcop_model_predict(const alcop_problem* prob /* host */, const alcop_sched*
  * are overwritten), synchronises the stream, times each trial with HIP events.
  *   top_k > 0: time the top_k feasible schedules by predicted latency; top_k == 0: time all
  *   feasible schedules (exhaustive / grid search, the 100 % reference of Sec. 6.4).
- *   model: as in alcop_model_predict.
+ *   model: 0 / 1 as in alcop_model_predict (fixed ranking by that model);
+ *          2 = measurement-corrected model (Sec. 5.3 "Analytical + ML"): a regression whose prior
+ *              is model 0 and which is refitted after every timed trial; the next trial is the
+ *              untried schedule with the lowest corrected prediction;
+ *          3 = no model: schedules in table order (the paper's grid search baseline).
  *   For conv problems pass x as A, w as B, y as C and the geometry in `conv` (host; 11 ints:
  *   N,H,W,C,K,R,S,stride_h,stride_w,pad_h,pad_w), else conv = NULL and lda/ldb/ldc/strides
  *   as for alcop_bmm (batch 1 for GEMM).

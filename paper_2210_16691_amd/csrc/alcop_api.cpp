@@ -479,7 +479,7 @@ int alcop_tune(const alcop_problem* prob, const void* A, const void* B, void* C,
                int log_cap, void* hip_stream)
 {
   if (!best || !best_us) return ALCOP_ERR_NULL;
-  if (top_k < 0 || iters <= 0 || (model != 0 && model != 1)) return ALCOP_ERR_SHAPE;
+  if (top_k < 0 || iters <= 0 || model < 0 || model > 3) return ALCOP_ERR_SHAPE;
   Call c;
   int rc = call_of_problem(prob, A, B, C, lda, ldb, ldc, strideA, strideB, strideC, conv, &c);
   if (rc) return rc;
@@ -490,33 +490,63 @@ int alcop_tune(const alcop_problem* prob, const void* A, const void* B, void* C,
     alcop_sched s;
     const KernelEntry* e;
     double pred;
+    double x[Corrector::D];
+    bool tried;
   };
   std::vector<Cand> cands;
   const Device dev;
   for (const alcop_sched& s : space_of(p)) {
     const KernelEntry* e = nullptr;
     if (check_sched(p, s, &e) != ALCOP_OK || span_check(c, s) != ALCOP_OK) continue;   // pruned
-    cands.push_back(Cand{s, e, predict(p, s, model, dev, nullptr)});
+    Cand cd;
+    cd.s = s;
+    cd.e = e;
+    cd.pred = model == 3 ? (double)cands.size() : predict(p, s, model == 2 ? 0 : model, dev, nullptr);
+    cd.tried = false;
+    Corrector::features(p, s, dev, cd.x);
+    cands.push_back(cd);
   }
   if (space_size) *space_size = (int)cands.size();
   if (cands.empty()) return ALCOP_ERR_SCHED;
   std::stable_sort(cands.begin(), cands.end(),
                    [](const Cand& a, const Cand& b) { return a.pred < b.pred; });
   const int n = top_k == 0 ? (int)cands.size() : std::min(top_k, (int)cands.size());
+  Corrector corr;
   bool have = false;
   int done = 0;
-  for (int i = 0; i < n; i++) {
+  for (int t = 0; t < n; t++) {
+    // next trial: models 0, 1, 3 walk their fixed ranking; model 2 takes the untried schedule
+    // with the lowest corrected prediction (equal to the analytical ranking until data arrives)
+    int pick = -1;
+    if (model == 2) {
+      double bestp = 0;
+      for (int i = 0; i < (int)cands.size(); i++) {
+        if (cands[i].tried) continue;
+        const double pl = corr.predict_log(cands[i].x);
+        if (pick < 0 || pl < bestp) {
+          pick = i;
+          bestp = pl;
+        }
+      }
+    } else {
+      pick = t;
+    }
     double us = 0;
-    rc = time_sched(c, cands[i].s, cands[i].e, 3, iters, (hipStream_t)hip_stream, &us);
+    rc = time_sched(c, cands[pick].s, cands[pick].e, 3, iters, (hipStream_t)hip_stream, &us);
     if (rc) return rc;
-    if (i < log_cap) {
-      if (log_sched) log_sched[i] = cands[i].s;
-      if (log_pred_us) log_pred_us[i] = cands[i].pred;
-      if (log_meas_us) log_meas_us[i] = us;
+    cands[pick].tried = true;
+    if (model == 2) {
+      corr.add(cands[pick].x, us);
+      if (t >= 2) corr.fit();
+    }
+    if (t < log_cap) {
+      if (log_sched) log_sched[t] = cands[pick].s;
+      if (log_pred_us) log_pred_us[t] = cands[pick].pred;
+      if (log_meas_us) log_meas_us[t] = us;
     }
     if (!have || us < *best_us) {
       *best_us = us;
-      *best = cands[i].s;
+      *best = cands[pick].s;
       have = true;
     }
     done++;

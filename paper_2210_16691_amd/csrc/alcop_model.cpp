@@ -110,4 +110,74 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   return t_kernel;
 }
 
+// ---- measurement-corrected model ------------------------------------------------------------
+Corrector::Corrector() : n_(0)
+{
+  for (int i = 0; i < D; i++) {
+    xty_[i] = 0;
+    prior_[i] = 0;
+    for (int j = 0; j < D; j++) xtx_[i][j] = 0;
+  }
+  prior_[1] = 1.0;   // log t = 1 * log(analytical prediction)
+  for (int i = 0; i < D; i++) w_[i] = prior_[i];
+}
+
+void Corrector::features(const alcop_problem& prob, const alcop_sched& s, const Device& dev,
+                         double* x)
+{
+  const double waves = (double)(s.bm / s.wm) * (s.bn / s.wn);
+  x[0] = 1.0;
+  x[1] = std::log(predict(prob, s, 0, dev, nullptr));
+  x[2] = std::log(predict(prob, s, 1, dev, nullptr));
+  x[3] = std::log2((double)s.bm * s.bn) - 14.0;     // tile area relative to 128 x 128
+  x[4] = std::log2((double)s.bk) - 6.0;
+  x[5] = s.stages - 2.0;
+  x[6] = s.reg_stages - 1.0;
+  x[7] = s.fuse_inner ? 1.0 : 0.0;
+  x[8] = std::log2(waves) - 2.0;
+  x[9] = s.l2_prefetch > 0 ? 1.0 : 0.0;
+}
+
+void Corrector::add(const double* x, double measured_us)
+{
+  const double y = std::log(measured_us);
+  for (int i = 0; i < D; i++) {
+    xty_[i] += x[i] * y;
+    for (int j = 0; j < D; j++) xtx_[i][j] += x[i] * x[j];
+  }
+  n_++;
+}
+
+void Corrector::fit()
+{
+  // minimise sum (y - w.x)^2 + lambda |w - prior|^2 : (XtX + lambda I) w = Xty + lambda prior
+  const double lambda = 0.3;
+  double a[D][D + 1];
+  for (int i = 0; i < D; i++) {
+    for (int j = 0; j < D; j++) a[i][j] = xtx_[i][j] + (i == j ? lambda : 0.0);
+    a[i][D] = xty_[i] + lambda * prior_[i];
+  }
+  for (int c = 0; c < D; c++) {            // Gaussian elimination with partial pivoting
+    int piv = c;
+    for (int r = c + 1; r < D; r++)
+      if (std::fabs(a[r][c]) > std::fabs(a[piv][c])) piv = r;
+    if (std::fabs(a[piv][c]) < 1e-12) return;   // singular: keep the previous weights
+    if (piv != c)
+      for (int j = 0; j <= D; j++) std::swap(a[c][j], a[piv][j]);
+    for (int r = 0; r < D; r++) {
+      if (r == c) continue;
+      const double f = a[r][c] / a[c][c];
+      for (int j = c; j <= D; j++) a[r][j] -= f * a[c][j];
+    }
+  }
+  for (int i = 0; i < D; i++) w_[i] = a[i][D] / a[i][i];
+}
+
+double Corrector::predict_log(const double* x) const
+{
+  double y = 0;
+  for (int i = 0; i < D; i++) y += w_[i] * x[i];
+  return y;
+}
+
 }  // namespace alcop

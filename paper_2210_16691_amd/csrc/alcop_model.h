@@ -36,4 +36,25 @@ double pipeline_latency(double t_load, double t_use, double n_loop, double n_pip
 double predict(const alcop_problem& prob, const alcop_sched& s, int model, const Device& dev,
                ModelTerms* terms);
 
+// Measurement-corrected cost model (paper Sec. 5.3, "Analytical + ML": a learned cost model that
+// starts from the analytical predictions and is updated with profiled trials).  The learner is
+// a ridge regression on log-time whose prior is the analytical model itself: with no
+// measurements it ranks exactly like model 0; every timed trial pulls the weights of a few
+// schedule features (tile area, k-tile, stages, waves, fusion, L2 touches) towards what was
+// measured on this machine and shape.
+class Corrector {
+ public:
+  static constexpr int D = 10;
+  Corrector();
+  static void features(const alcop_problem& prob, const alcop_sched& s, const Device& dev,
+                       double* x /* D */);
+  void add(const double* x, double measured_us);   // one profiled trial
+  void fit();                                      // ridge solve towards the prior
+  double predict_log(const double* x) const;       // log(predicted microseconds)
+
+ private:
+  double xtx_[D][D], xty_[D], w_[D], prior_[D];
+  int n_;
+};
+
 }  // namespace alcop

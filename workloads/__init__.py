@@ -79,6 +79,11 @@ CONFIGS = {
     "ffn1": dict(kind="gemm", M=4096, N=3072, K=768, dtype="bf16", out="bf16", dist="uniform"),
     "ffn2": dict(kind="gemm", M=4096, N=768, K=3072, dtype="bf16", out="bf16", dist="uniform"),
     "gemm8192": dict(kind="gemm", M=8192, N=8192, K=8192, dtype="bf16", out="bf16", dist="uniform"),
+    # the shape the paper names as its best case (small output, long reduction: MM_RN50_FC, Sec. 6.1)
+    # and a short-reduction batched matmul of the kind it names as its worst (GPT-2 style Q.K^T)
+    "mm_rn50_fc": dict(kind="gemm", M=1024, N=64, K=2048, dtype="f16", out="f16", dist="uniform"),
+    "bmm_gpt2_qk": dict(kind="bmm", batch=48, M=1024, N=1024, K=64, dtype="f16", out="f16",
+                        transB=True, dist="attn_qk"),
     # ResNet-style 3x3 convolutions, NHWC
     "conv56": dict(kind="conv", N=32, H=56, W=56, C=64, K=64, R=3, S=3, stride=1, pad=1,
                    dtype="f16", out="f16", dist="conv"),
@@ -87,8 +92,12 @@ CONFIGS = {
 }
 
 
+_SEED_ORDER = ["bmm_pv", "bmm_qk", "conv14", "conv56", "ffn1", "ffn2", "gemm2048", "gemm256",
+               "gemm256_int", "gemm8192", "mm_rn50_fc", "bmm_gpt2_qk"]
+
+
 def _seed(name: str, idx: int) -> int:
-    return BASE_SEED + 100 * sorted(CONFIGS).index(name) + idx
+    return BASE_SEED + 100 * _SEED_ORDER.index(name) + idx
 
 
 def make_inputs(name: str, **override):
