@@ -107,6 +107,34 @@ int alcop_bmm(const void* A, const void* B, void* C, int batch, int M, int N, in
               const alcop_sched* sched /* host */, void* hip_stream);
 
 /*
+ * GEMM / batched matmul with an elementwise function fused on the consumer side
+ * (paper Sec. 3.2, "Fusion": an elementwise f(.) is folded into the operator that consumes the
+ * data instead of into the copy that fills a pipelined buffer, so the buffer is still produced
+ * by an asynchronous copy and stays pipelinable).  Here f is applied to the fp32 accumulators in
+ * the epilogue, before the conversion to the output type:
+ *     C[i][j] = act( alpha * sum_k A(i,k) B(k,j) + bias[j] )
+ * alpha: host scalar (e.g. 1/sqrt(d) for attention scores); bias: DEVICE pointer to N fp32
+ * values, 16-byte aligned, or NULL; act: 0 = identity, 1 = ReLU.  ep == NULL means
+ * alpha = 1, no bias, identity.  For alcop_bmm_fused the same bias vector is used by every batch.
+ */
+typedef struct {
+  float alpha;
+  const void* bias;
+  int act;
+} alcop_epilogue;
+
+int alcop_gemm_fused(const void* A, const void* B, void* C, int M, int N, int K,
+                     long lda, long ldb, long ldc, int transA, int transB,
+                     alcop_dtype in, alcop_dtype out, const alcop_epilogue* ep /* host */,
+                     const alcop_sched* sched /* host */, void* hip_stream);
+
+int alcop_bmm_fused(const void* A, const void* B, void* C, int batch, int M, int N, int K,
+                    long lda, long ldb, long ldc, long strideA, long strideB, long strideC,
+                    int transA, int transB, alcop_dtype in, alcop_dtype out,
+                    const alcop_epilogue* ep /* host */, const alcop_sched* sched /* host */,
+                    void* hip_stream);
+
+/*
  * 2-D convolution as an implicit GEMM (paper Sec. 6.2 "Conv2D": its reduction loop over
  * (r, s, c) is a sequential load-and-use loop in the sense of Sec. 3.1, rule 2).
  *   x: NHWC  [N][H][W][C];  w: RSCK [R][S][C][K];  y: NPQK [N][P][Q][K],

@@ -141,3 +141,14 @@ def conv2d(x, w, dtype: int, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
     if rc:
         raise MemoryError("oracle conv2d failed (%d)" % rc)
     return y
+
+
+def epilogue(C: np.ndarray, alpha: float = 1.0, bias=None, act: int = 0) -> np.ndarray:
+    """Elementwise function fused on the consumer side (paper Sec. 3.2):
+    act(alpha * C[..., j] + bias[j]) in fp64; act 0 = identity, 1 = ReLU."""
+    out = np.asarray(C, dtype=np.float64) * float(alpha)
+    if bias is not None:
+        out = out + np.asarray(bias, dtype=np.float64)
+    if act == 1:
+        out = np.where(out < 0.0, 0.0, out)
+    return out

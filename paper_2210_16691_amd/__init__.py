@@ -22,7 +22,7 @@ ERR_NULL, ERR_DTYPE, ERR_ALIGN, ERR_SHAPE, ERR_SCHED, ERR_LAUNCH, ERR_UNSUPPORTE
     -1, -2, -3, -4, -5, -6, -7, -8)
 
 EXPORTS = [
-    "alcop_gemm", "alcop_bmm", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
+    "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
 ]
 
@@ -48,6 +48,11 @@ class Sched(ctypes.Structure):
 
 def sched(bm, bn, bk, wm, wn, stages=1, reg_stages=1, fuse_inner=0, raster=1, l2_prefetch=0) -> Sched:
     return Sched(bm, bn, bk, wm, wn, stages, reg_stages, fuse_inner, raster, l2_prefetch)
+
+
+class Epilogue(ctypes.Structure):
+    """Mirror of ``alcop_epilogue``: C = act(alpha * A.B + bias[j])."""
+    _fields_ = [("alpha", ctypes.c_float), ("bias", ctypes.c_void_p), ("act", ctypes.c_int)]
 
 
 class Problem(ctypes.Structure):
@@ -76,6 +81,11 @@ def lib() -> ctypes.CDLL:
         L.alcop_gemm.argtypes = [vp, vp, vp, i, i, i, l, l, l, i, i, i, i, sp, vp]
         L.alcop_bmm.restype = i
         L.alcop_bmm.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, sp, vp]
+        ep = ctypes.POINTER(Epilogue)
+        L.alcop_gemm_fused.restype = i
+        L.alcop_gemm_fused.argtypes = [vp, vp, vp, i, i, i, l, l, l, i, i, i, i, ep, sp, vp]
+        L.alcop_bmm_fused.restype = i
+        L.alcop_bmm_fused.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, ep, sp, vp]
         L.alcop_conv2d_igemm.restype = i
         L.alcop_conv2d_igemm.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, vp]
         L.alcop_sched_supported.restype = i
@@ -151,6 +161,34 @@ def alcop_bmm(A, B, C, sched=None, transB=False, stream=None):
                          A.stride(0), B.stride(0), C.stride(0), 0, int(transB),
                          _dtype_code(A), _dtype_code(C), _sp(sched), _stream(stream))
     _check(rc, "alcop_bmm")
+    return C
+
+
+def _epilogue(alpha, bias, act):
+    return Epilogue(float(alpha), bias.data_ptr() if bias is not None else None, int(act))
+
+
+def alcop_gemm_fused(A, B, C, alpha=1.0, bias=None, act=0, sched=None, transB=False, stream=None):
+    """C = act(alpha * A.B + bias[j]); bias is an fp32 CUDA vector of N values or None; act 1 = ReLU."""
+    M, K = A.shape
+    N = B.shape[0] if transB else B.shape[1]
+    e = _epilogue(alpha, bias, act)
+    rc = lib().alcop_gemm_fused(_ptr(A), _ptr(B), _ptr(C), M, N, K, A.stride(0), B.stride(0),
+                                C.stride(0), 0, int(transB), _dtype_code(A), _dtype_code(C),
+                                ctypes.byref(e), _sp(sched), _stream(stream))
+    _check(rc, "alcop_gemm_fused")
+    return C
+
+
+def alcop_bmm_fused(A, B, C, alpha=1.0, bias=None, act=0, sched=None, transB=False, stream=None):
+    b, M, K = A.shape
+    N = B.shape[1] if transB else B.shape[2]
+    e = _epilogue(alpha, bias, act)
+    rc = lib().alcop_bmm_fused(_ptr(A), _ptr(B), _ptr(C), b, M, N, K, A.stride(1), B.stride(1),
+                               C.stride(1), A.stride(0), B.stride(0), C.stride(0), 0, int(transB),
+                               _dtype_code(A), _dtype_code(C), ctypes.byref(e), _sp(sched),
+                               _stream(stream))
+    _check(rc, "alcop_bmm_fused")
     return C
 
 

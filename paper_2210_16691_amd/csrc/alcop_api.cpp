@@ -43,6 +43,10 @@ struct Call {
   alcop_dtype in, out;
   // conv geometry
   int cN, cH, cW, cC, cK, cR, cS, csh, csw, cph, cpw, cP, cQ;
+  // fused epilogue
+  float alpha;
+  const void* bias;
+  int act;
 };
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -172,6 +176,8 @@ int check_call(const Call& c)
   int rc = check_problem(problem_of(c));
   if (rc) return rc;
   if (!aligned16(c.A) || !aligned16(c.B) || !aligned16(c.C)) return ALCOP_ERR_ALIGN;
+  if (c.bias && !aligned16(c.bias)) return ALCOP_ERR_ALIGN;
+  if (c.act != 0 && c.act != 1) return ALCOP_ERR_UNSUPPORTED;
   if (c.op == ALCOP_OP_CONV2D) {
     if (c.cR <= 0 || c.cS <= 0 || c.csh <= 0 || c.csw <= 0 || c.cph < 0 || c.cpw < 0 ||
         c.cP <= 0 || c.cQ <= 0 || c.cC % 8 != 0)
@@ -220,6 +226,9 @@ int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipSt
   p.ntm = (c.M + s.bm - 1) / s.bm;
   p.ntn = (c.N + s.bn - 1) / s.bn;
   p.raster = s.raster;
+  p.alpha = c.alpha;
+  p.bias = (const float*)c.bias;
+  p.act = c.act;
   p.group_m = std::min(8, p.ntm);
   // sharers of a panel among the blocks one XCD runs side by side (32 CUs, blocks per CU by LDS)
   const int per_cu = std::max(1, std::min(2, (160 * 1024) / e->lds_bytes));
@@ -288,6 +297,7 @@ Call gemm_call(alcop_op op, const void* A, const void* B, void* C, int batch, in
   c.transB = transB ? 1 : 0;
   c.in = in;
   c.out = out;
+  c.alpha = 1.0f;
   return c;
 }
 
@@ -329,6 +339,7 @@ int conv_call(Call* c, const void* x, const void* w, void* y, int N, int H, int 
   c->cpw = pw;
   c->cP = (int)P;
   c->cQ = (int)Q;
+  c->alpha = 1.0f;
   return ALCOP_OK;
 }
 
@@ -400,6 +411,36 @@ int alcop_bmm(const void* A, const void* B, void* C, int batch, int M, int N, in
   if (transA) return ALCOP_ERR_UNSUPPORTED;
   Call c = gemm_call(ALCOP_OP_BMM, A, B, C, batch, M, N, K, lda, ldb, ldc, strideA, strideB,
                      strideC, transB, in, out);
+  return run(c, sched, hip_stream);
+}
+
+int alcop_gemm_fused(const void* A, const void* B, void* C, int M, int N, int K, long lda, long ldb,
+                     long ldc, int transA, int transB, alcop_dtype in, alcop_dtype out,
+                     const alcop_epilogue* ep, const alcop_sched* sched, void* hip_stream)
+{
+  if (transA) return ALCOP_ERR_UNSUPPORTED;
+  Call c = gemm_call(ALCOP_OP_GEMM, A, B, C, 1, M, N, K, lda, ldb, ldc, 0, 0, 0, transB, in, out);
+  if (ep) {
+    c.alpha = ep->alpha;
+    c.bias = ep->bias;
+    c.act = ep->act;
+  }
+  return run(c, sched, hip_stream);
+}
+
+int alcop_bmm_fused(const void* A, const void* B, void* C, int batch, int M, int N, int K, long lda,
+                    long ldb, long ldc, long strideA, long strideB, long strideC, int transA,
+                    int transB, alcop_dtype in, alcop_dtype out, const alcop_epilogue* ep,
+                    const alcop_sched* sched, void* hip_stream)
+{
+  if (transA) return ALCOP_ERR_UNSUPPORTED;
+  Call c = gemm_call(ALCOP_OP_BMM, A, B, C, batch, M, N, K, lda, ldb, ldc, strideA, strideB,
+                     strideC, transB, in, out);
+  if (ep) {
+    c.alpha = ep->alpha;
+    c.bias = ep->bias;
+    c.act = ep->act;
+  }
   return run(c, sched, hip_stream);
 }
 

@@ -53,6 +53,10 @@ struct Params {
   // third pipeline level (HBM -> L2): every wave touches lines of k-tile kt + pf_dist when it
   // issues k-tile kt; the lines of a panel are split among the pf_pa (pf_pb) blocks that share it
   int pf_dist, pf_pa, pf_pb;
+  // consumer-side fused elementwise function: act(alpha * acc + bias[n])
+  float alpha;
+  const float* bias;
+  int act;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -104,6 +108,18 @@ struct KCfg {
   static_assert(WAIT <= 63, "vmcnt is a 6-bit counter");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
 };
+
+// Buffer resource for a wave-uniform base address.  The words are passed through
+// readfirstlane so that the descriptor provably lives in scalar registers.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int bytes)
+{
+  const uint64_t a = (uint64_t)(uintptr_t)base;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  const int n = __builtin_amdgcn_readfirstlane(bytes);
+  return __builtin_amdgcn_make_buffer_rsrc((void*)(uintptr_t)(((uint64_t)hi << 32) | lo), 0, n,
+                                           0x00020000);
+}
 
 __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, uint32_t lds_dst)
 {
@@ -207,12 +223,11 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     if constexpr (C::AM == 0) {
       const int rows = (p.M - tm * BM) < BM ? (p.M - tm * BM) : BM;
       const char* base = (const char*)p.A + ((long)batch * p.strideA + (long)tm * BM * p.lda) * 2;
-      rsrcA = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0,
-                                                ((rows - 1) * p.lda + p.K) * 2, 0x00020000);
+      rsrcA = make_rsrc(base, ((rows - 1) * p.lda + p.K) * 2);
       voffA = (uint32_t)(r * p.lda * 2 + c * 16);
       stepA = (uint32_t)(C::RSTEP_A * p.lda * 2);
     } else {
-      rsrcA = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, (int)p.a_span, 0x00020000);
+      rsrcA = make_rsrc(p.A, (int)p.a_span);
       voffA = 0;
 #pragma unroll
       for (int i = 0; i < NLA; i++) {
@@ -234,8 +249,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       const int c = ph ^ ((r >> 1) % C::CPR_B);
       const int cols = (p.N - tn * BN) < BN ? (p.N - tn * BN) : BN;
       const char* base = (const char*)p.B + ((long)batch * p.strideB + (long)tn * BN * p.ldb) * 2;
-      rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0,
-                                                ((cols - 1) * p.ldb + p.K) * 2, 0x00020000);
+      rsrcB = make_rsrc(base, ((cols - 1) * p.ldb + p.K) * 2);
       voffB = (uint32_t)(r * p.ldb * 2 + c * 16);
       stepB = (uint32_t)(C::RSTEP_B * p.ldb * 2);
       kstepB = BK * 2;
@@ -243,8 +257,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       const int c = ph ^ (((r / C::RPB) % C::GM) << 2);
       const int cols = (p.N - tn * BN) < BN ? (p.N - tn * BN) : BN;
       const char* base = (const char*)p.B + ((long)batch * p.strideB + (long)tn * BN) * 2;
-      rsrcB = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0,
-                                                ((p.K - 1) * p.ldb + cols) * 2, 0x00020000);
+      rsrcB = make_rsrc(base, ((p.K - 1) * p.ldb + cols) * 2);
       voffB = (uint32_t)(r * p.ldb * 2 + c * 16);
       stepB = (uint32_t)(C::RSTEP_B * p.ldb * 2);
       kstepB = (uint32_t)(BK * p.ldb * 2);
@@ -538,14 +551,26 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     const uint32_t ebase = lds0 + (uint32_t)wave * C::EPI_WAVE_BYTES;
     const int m0 = tm * BM + wm * WM, n0 = tn * BN + wn * WN;
     char* Cb = (char*)p.C + (long)batch * p.strideC * OB;
+    const bool fused = p.alpha != 1.0f || p.bias != nullptr || p.act != 0;
 #pragma unroll
     for (int j = 0; j < TM; j++) {
 #pragma unroll
       for (int i = 0; i < TN; i++)
 #pragma unroll
         for (int vq = 0; vq < 4; vq++) {
-          ot4 h = {(OT)acc[i][j][4 * vq + 0], (OT)acc[i][j][4 * vq + 1],
-                   (OT)acc[i][j][4 * vq + 2], (OT)acc[i][j][4 * vq + 3]};
+          f32x4 v = {acc[i][j][4 * vq + 0], acc[i][j][4 * vq + 1], acc[i][j][4 * vq + 2],
+                     acc[i][j][4 * vq + 3]};
+          if (fused) {   // f(.) on the accumulators (paper Sec. 3.2: fused into the consumer)
+            const int n = n0 + i * 32 + 8 * vq + 4 * (lane >> 5);
+            f32x4 b = {0.f, 0.f, 0.f, 0.f};
+            if (p.bias != nullptr && n < p.N) b = *(const f32x4*)(p.bias + n);
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+              float t = v[e] * p.alpha + b[e];
+              v[e] = (p.act == 1 && t < 0.f) ? 0.f : t;
+            }
+          }
+          ot4 h = {(OT)v[0], (OT)v[1], (OT)v[2], (OT)v[3]};
           *(ALCOP_LDS ot4*)(uintptr_t)(ebase + (lane & 31) * RS +
                                        (i * 32 + 8 * vq + 4 * (lane >> 5)) * OB) = h;
         }

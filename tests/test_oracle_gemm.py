@@ -165,3 +165,15 @@ def test_bmm_pv_row_sums_and_one_hot_gather():
     got = oracle.bmm(H, wl.bits(V), oracle.F16)
     for i in range(b):
         assert np.array_equal(got[i], _vals(V[i])[idx[i]])
+
+
+# ---- fused elementwise epilogue --------------------------------------------------------------
+def test_epilogue_closed_forms():
+    C = np.array([[-2.0, 0.0, 3.0], [4.0, -5.0, 6.0]])
+    assert np.array_equal(oracle.epilogue(C), C)                                   # identity
+    assert np.array_equal(oracle.epilogue(C, 1.0, None, 1), np.array([[0, 0, 3.0], [4.0, 0, 6.0]]))
+    assert np.array_equal(oracle.epilogue(C, 0.5, [1.0, 2.0, 3.0], 0),
+                          np.array([[0.0, 2.0, 4.5], [3.0, -0.5, 6.0]]))           # bias per column
+    assert np.array_equal(oracle.epilogue(C, -1.0, [0.0, 0.0, 0.0], 1), np.array([[2.0, 0, 0], [0, 5.0, 0]]))
+    # relu(x) - relu(-x) = x
+    assert np.array_equal(oracle.epilogue(C, 1.0, None, 1) - oracle.epilogue(C, -1.0, None, 1), C)
