@@ -32,8 +32,8 @@
  *     round-to-nearest-even to ALCOP_F16 / ALCOP_BF16, or stored as is (ALCOP_F32).
  *   - Alignment: every tensor base pointer is 16-byte aligned; leading dimensions and batch
  *     strides are multiples of 8 elements.
- *   - Shapes: K must be a multiple of the schedule's bk; N a multiple of 8; M is free
- *     (edge tiles in M and N are loaded with zero fill and stored under a mask).  Each
+ *   - Shapes: K and N must be multiples of 8; M is free.  Edge tiles in M, N and K are loaded
+ *     with zero fill and stored under a mask (convolution: C must be a multiple of bk).  Each
  *     operand of one GEMM (one batch entry) must span less than 2 GiB.
  */
 #ifndef ALCOP_H
@@ -50,7 +50,7 @@ typedef enum {
   ALCOP_ERR_NULL = -1,        /* a required pointer is NULL                                  */
   ALCOP_ERR_DTYPE = -2,       /* unsupported input / output element type                     */
   ALCOP_ERR_ALIGN = -3,       /* pointer, leading dimension or stride not aligned as stated  */
-  ALCOP_ERR_SHAPE = -4,       /* non-positive size, K not a multiple of bk, N not of 8, ...  */
+  ALCOP_ERR_SHAPE = -4,       /* non-positive size, K or N not a multiple of 8, conv C % bk   */
   ALCOP_ERR_SCHED = -5,       /* schedule infeasible: no such kernel, LDS or wait-counter    */
                               /* limit exceeded, fuse_inner without reg_stages=2/stages>=2   */
   ALCOP_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch                          */
@@ -152,7 +152,7 @@ int alcop_conv2d_igemm(const void* x, const void* w, void* y, int N, int H, int 
  * schedule rules and "compile fail" marks stand for, Sec. 3.1 and Fig. 9): a kernel with
  * these parameters is built; the LDS ring fits 160 KB; the outstanding-load count
  * (S-2)*loads_per_stage fits the 6-bit vector-memory counter; fuse_inner implies R=2, S>=2;
- * bk divides K (and C for conv).  Returns ALCOP_OK or the error a launch would return.
+ * bk divides C for conv.  Returns ALCOP_OK or the error a launch would return.
  */
 int alcop_sched_supported(const alcop_problem* prob /* host */, const alcop_sched* sched /* host */);
 

@@ -71,7 +71,7 @@ def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Devi
     tiles = ntm * ntn
     n_blocks = tiles * batch
     n_warp = (bm // wm) * (bn // wn)
-    n_smem_loop = K // bk
+    n_smem_loop = math.ceil(K / bk)
     n_reg_loop = bk // 16
     bytes_one_smem_loop = (bm + bn) * bk * 2
     bytes_one_reg_loop = n_warp * (wm + wn) * 16 * 2
@@ -131,8 +131,8 @@ def bottleneck(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, dev: Device = Devi
     memory traffic, each at full rate, no latency and no occupancy effects."""
     n_blocks = math.ceil(M / bm) * math.ceil(N / bn) * batch
     n_warp = (bm // wm) * (bn // wn)
-    steps = (K // bk) * (bk // 16)
+    steps = math.ceil(K / bk) * (bk // 16)
     t_cmp = n_blocks * steps * 2 * bm * bn * 16 / (dev.num_cu * dev.flop_per_us_cu)
     t_lds = n_blocks * steps * n_warp * (wm + wn) * 16 * 2 / (dev.num_cu * dev.bw_lds_cu)
-    t_mem = (n_blocks * (K // bk) * (bm + bn) * bk * 2 + n_blocks * bm * bn * out_bytes) / dev.bw_dram
+    t_mem = (n_blocks * math.ceil(K / bk) * (bm + bn) * bk * 2 + n_blocks * bm * bn * out_bytes) / dev.bw_dram
     return max(t_cmp, t_lds, t_mem)

@@ -104,7 +104,8 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
   if (!e) return ALCOP_ERR_SCHED;
   if (e->lds_bytes > 160 * 1024) return ALCOP_ERR_SCHED;
   if (e->stages >= 2 && (e->stages - 2) * e->loads_per_stage > 63) return ALCOP_ERR_SCHED;
-  if (p.K % s.bk != 0) return ALCOP_ERR_SHAPE;
+  // GEMM / BMM: a partial last k-tile is zero-filled by the loader (K % 8 == 0 is checked with
+  // the problem).  Convolution: a k-tile must stay inside one filter tap.
   if (p.op == ALCOP_OP_CONV2D && p.conv_C % s.bk != 0) return ALCOP_ERR_SHAPE;
   const long ntm = (p.M + s.bm - 1) / s.bm, ntn = (p.N + s.bn - 1) / s.bn;
   if (ntm * ntn > 0x7fffffffL) return ALCOP_ERR_SHAPE;
@@ -605,7 +606,7 @@ const char* alcop_strerror(int code)
     case ALCOP_ERR_NULL: return "null pointer";
     case ALCOP_ERR_DTYPE: return "unsupported element type";
     case ALCOP_ERR_ALIGN: return "pointer, leading dimension or stride not aligned";
-    case ALCOP_ERR_SHAPE: return "bad shape (size <= 0, K not a multiple of bk, N not a multiple of 8, ...)";
+    case ALCOP_ERR_SHAPE: return "bad shape (size <= 0, K or N not a multiple of 8, conv C not a multiple of bk)";
     case ALCOP_ERR_SCHED: return "schedule not built or infeasible";
     case ALCOP_ERR_LAUNCH: return "HIP launch failed";
     case ALCOP_ERR_UNSUPPORTED: return "not supported";

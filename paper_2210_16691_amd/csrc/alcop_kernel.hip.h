@@ -207,12 +207,14 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     tm = lid / p.ntn;
     tn = lid - tm * p.ntn;
   }
-  const int nko = p.K / BK;
+  const int nko = (p.K + BK - 1) / BK;        // the last k-tile may be partial (K % 8 == 0)
+  const bool ktail = (p.K % BK) != 0;
 
   // ---- global -> LDS producers -----------------------------------------------------------
   const int q0 = wave * 64 + lane;            // 16-byte slot of this lane in load 0
   __amdgpu_buffer_rsrc_t rsrcA, rsrcB;
   uint32_t voffA, stepA = 0;
+  int kcA = 0, kcB = 0;                       // first k (within a k-tile) of this lane's chunk
   // conv state: per-load row geometry
   int ih0[NLA], iw0[NLA];
   uint32_t coff[NLA];
@@ -220,6 +222,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   {
     const int r = q0 / C::CPR_A, ph = q0 % C::CPR_A;
     const int c = ph ^ ((r >> 1) % C::CPR_A);
+    kcA = c * 8;
     if constexpr (C::AM == 0) {
       const int rows = (p.M - tm * BM) < BM ? (p.M - tm * BM) : BM;
       const char* base = (const char*)p.A + ((long)batch * p.strideA + (long)tm * BM * p.lda) * 2;
@@ -247,6 +250,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     const int r = q0 / C::CPR_B, ph = q0 % C::CPR_B;
     if constexpr (C::BL == 1) {                // B stored N x K: same shape of loader as A
       const int c = ph ^ ((r >> 1) % C::CPR_B);
+      kcB = c * 8;
       const int cols = (p.N - tn * BN) < BN ? (p.N - tn * BN) : BN;
       const char* base = (const char*)p.B + ((long)batch * p.strideB + (long)tn * BN * p.ldb) * 2;
       rsrcB = make_rsrc(base, ((cols - 1) * p.ldb + p.K) * 2);
@@ -315,9 +319,19 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   // `slot`; issue_one(i) emits load i of the L loads a wave owns (A loads first, then B);
   // stage_end advances the convolution tap.  Always exactly L loads per wave and stage.
   uint32_t st_ka = 0, st_kb = 0, st_dst = 0, st_tap = 0;
+  // Partial last k-tile (K % BK != 0): lanes whose chunk starts at k >= K get an out-of-range
+  // offset for that one k-tile and so zero-fill their 16 bytes.  Decided once per lane here and
+  // selected once per k-tile in stage_begin: nothing is added per load.
+  const uint32_t voffA_t = ((nko - 1) * BK + kcA >= p.K) ? (voffA | 0x80000000u) : voffA;
+  const uint32_t voffB_t =
+      (C::BL == 1 && (nko - 1) * BK + kcB >= p.K) ? (voffB | 0x80000000u) : voffB;
+  uint32_t st_voffA = voffA, st_voffB = voffB;
   bool st_live = false, st_pf_live = false;
   auto stage_begin = [&](int kt, int slot) {
     st_live = kt < nko;
+    const bool tail = ktail && kt == nko - 1;
+    st_voffA = tail ? voffA_t : voffA;
+    st_voffB = tail ? voffB_t : voffB;
     st_pf_live = kt + pf_d + 1 < nko;
     st_dst = lds0 + (uint32_t)slot * STAGE_BYTES + (uint32_t)wave * 1024u;
     if constexpr (C::AM == 0)
@@ -330,7 +344,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     if (idx < NLA) {
       const int i = idx;
       if constexpr (C::AM == 0) {
-        dma16(rsrcA, voffA + st_ka + (uint32_t)i * stepA, st_dst + i * (NWAVES * 1024));
+        dma16(rsrcA, st_voffA + st_ka + (uint32_t)i * stepA, st_dst + i * (NWAVES * 1024));
       } else {
         const bool ok = st_live && (unsigned)(ih0[i] + cr) < (unsigned)p.cH &&
                         (unsigned)(iw0[i] + cs) < (unsigned)p.cW;
@@ -338,7 +352,8 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       }
     } else if (idx < NLA + NLB) {
       const int i = idx - NLA;
-      dma16(rsrcB, voffB + st_kb + (uint32_t)i * stepB, st_dst + A_BYTES + i * (NWAVES * 1024));
+      // (K x N layout: rows k >= K of a partial k-tile lie beyond the descriptor: zero-filled)
+      dma16(rsrcB, st_voffB + st_kb + (uint32_t)i * stepB, st_dst + A_BYTES + i * (NWAVES * 1024));
     } else {
       touch4(pf_ptr, pf_dst);
       if (st_pf_live) pf_ptr += pf_step;      // stop at the last k-tile: never run past the operand

@@ -29,7 +29,7 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   const double tiles = ntm * ntn;
   const double n_blocks = tiles * batch;
   const double n_warp = (bm / wm) * (bn / wn);              // N_warp_per_threadblk
-  const double n_smem_loop = std::floor(prob.K / bk);       // N_smem_loop
+  const double n_smem_loop = std::ceil(prob.K / bk);        // N_smem_loop (a partial tile counts)
   const double n_reg_loop = bk / 16.0;                       // N_reg_loop (MFMA k = 16)
   const double stage_bytes = (bm + bn) * bk * 2.0;          // Bytes_one_smem_loop
   const double frag_bytes = n_warp * (wm + wn) * 16.0 * 2.0; // Bytes_one_reg_loop (LDS reads)

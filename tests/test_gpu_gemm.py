@@ -116,6 +116,20 @@ def test_ragged_edges(shape, transB):
         assert np.array_equal(to_f64(run_gemm(A, B, "f32", s, transB)), ref), repr(s)
 
 
+@pytest.mark.parametrize("K", [8, 40, 72, 96, 200, 328])
+@pytest.mark.parametrize("transB", [False, True])
+def test_partial_last_k_tile(K, transB):
+    # K only a multiple of 8: the chunks of the last k-tile at k >= K are zero-filled
+    M, N = 136, 72
+    for dt in ("f16", "bf16"):
+        A = wl.small_ints((M, K), dt, 117)
+        B = wl.small_ints((N, K) if transB else (K, N), dt, 118)
+        ref = oracle.gemm(wl.bits(A), wl.bits(B), ODT[dt], transB=transB)
+        for s in [al.sched(128, 128, 64, 64, 64, 3, 2, 1), al.sched(64, 64, 32, 32, 32, 2, 2, 1),
+                  al.sched(128, 128, 32, 64, 64, 1, 1, 0), al.sched(64, 64, 64, 32, 32, 2, 1, 0)]:
+            assert np.array_equal(to_f64(run_gemm(A, B, "f32", s, transB)), ref), (dt, repr(s))
+
+
 def test_masked_stores_do_not_touch_memory_outside_c():
     M, N, K = 100, 72, 128
     A = wl.small_ints((M, K), "f16", 113)

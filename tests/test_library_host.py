@@ -51,7 +51,7 @@ def test_null_and_bad_arguments_are_rejected_without_a_launch():
     assert g(odd, fake, fake, 128, 128, 64, 64, 128, 128, 0, 0, 0, 0) == al.ERR_ALIGN
     assert g(fake, fake, fake, 128, 128, 64, 68, 128, 128, 0, 0, 0, 0) == al.ERR_ALIGN   # lda % 8
     assert g(fake, fake, fake, 128, 128, 64, 56, 128, 128, 0, 0, 0, 0) == al.ERR_SHAPE   # lda < K
-    assert g(fake, fake, fake, 128, 128, 96, 96, 128, 128, 0, 0, 0, 0) == al.ERR_SHAPE   # K % bk
+    assert g(fake, fake, fake, 128, 128, 100, 104, 128, 128, 0, 0, 0, 0) == al.ERR_SHAPE  # K % 8
     bad = al.sched(128, 128, 64, 64, 64, 1, 2, 1)      # fusion needs S >= 2
     assert L.alcop_gemm(fake, fake, fake, 128, 128, 64, 64, 128, 128, 0, 0, 0, 0,
                         ctypes.byref(bad), None) == al.ERR_SCHED
@@ -70,9 +70,9 @@ def test_feasibility_rules():
     assert al.alcop_sched_supported(p, al.sched(256, 256, 64, 128, 128, 2, 2, 1)) == al.OK
     assert al.alcop_sched_supported(p, al.sched(128, 128, 64, 64, 64, 2, 1, 1)) == al.ERR_SCHED
     assert al.alcop_sched_supported(p, al.sched(128, 128, 48, 64, 64, 2, 1, 0)) == al.ERR_SCHED
-    p2 = al.problem(al.OP_GEMM, 2048, 2048, 2080, al.F16, al.F16)       # K % 64 != 0, % 32 == 0
-    assert al.alcop_sched_supported(p2, ok) == al.ERR_SHAPE
-    assert al.alcop_sched_supported(p2, al.sched(128, 128, 32, 64, 64, 3, 2, 1)) == al.OK
+    p2 = al.problem(al.OP_GEMM, 2048, 2048, 2080, al.F16, al.F16)       # partial last k-tile: allowed
+    assert al.alcop_sched_supported(p2, ok) == al.OK
+    assert al.alcop_sched_supported(al.problem(al.OP_GEMM, 64, 64, 100, al.F16, al.F16), ok) == al.ERR_SHAPE
     pc = al.problem(al.OP_CONV2D, 32 * 56 * 56, 64, 576, al.F16, al.F16, conv_C=64)
     assert al.alcop_sched_supported(pc, al.sched(128, 64, 64, 64, 32, 3, 2, 1)) == al.OK
     pc32 = al.problem(al.OP_CONV2D, 1024, 64, 9 * 32, al.F16, al.F16, conv_C=32)
