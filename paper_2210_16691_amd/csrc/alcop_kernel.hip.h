@@ -20,11 +20,12 @@
 // LDS image of a tile is linear in (load, wave, lane); the bank-conflict-free swizzle is
 // applied on the source side by choosing which 16-byte chunk of the global tile each lane
 // fetches (the paper applies shared-memory swizzling to all its kernels, Sec. 6.1).
-//   K-contiguous tile (A, or B stored N x K): rows of BK halves, CPR = BK/8 chunks per row,
-//     physical chunk = logical chunk XOR ((row/2) mod CPR); read with ds_read_b128.
-//   N-contiguous tile (B stored K x N): rows of BN halves (one row per k), physical chunk =
-//     logical chunk XOR (((k/RPB) mod min(4,BN/32)) << 2); read with ds_read_b64_tr_b16,
-//     which hands each lane 4 consecutive k of one column.
+//   K-contiguous tile (A stored M x K, B stored N x K): rows of BK halves, CPR = BK/8 chunks per
+//     row, physical chunk = logical chunk XOR ((row/2) mod CPR); read with ds_read_b128.
+//   M/N-contiguous tile (A stored K x M, B stored K x N): one row per k, physical chunk =
+//     logical chunk XOR (((k/RPB) mod min(4,BX/32)) << 2); read with ds_read_b64_tr_b16,
+//     which hands each lane 4 consecutive k of one column (and runs at ~2x the LDS bandwidth
+//     of ds_read_b128 on this machine).
 //
 // Matrix-core mapping.  v_mfma_f32_32x32x16_{f16,bf16} computes D[i][j] += sum_k X[i][k] Y[k][j]
 // with X lane l = row l%32, k = 8*(l/32)..+7, Y lane l = column l%32, same k, and D lane l =
@@ -71,40 +72,64 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define ALCOP_LDS __attribute__((address_space(3)))
 
+// Layout of an operand tile, in global memory and (swizzled) in LDS.
+enum { LAY_K = 0,    // contiguous along k:            A stored M x K, B stored N x K
+       LAY_MN = 1 }; // contiguous along its m or n:   A stored K x M, B stored K x N
+
+// Compile-time description of one operand tile: BX rows/columns of the block tile, WX of them
+// per wave, BK deep, moved by NT threads.
+template <int LAY_, int BX_, int WX_, int BK_, int NT_>
+struct Opnd {
+  static constexpr int LAY = LAY_, BX = BX_, WX = WX_, BK = BK_, NT = NT_;
+  static constexpr int BYTES = BX * BK * 2;
+  static constexpr int CPR = LAY == LAY_K ? BK / 8 : BX / 8;   // 16-byte chunks per LDS row
+  static constexpr int RSTEP = NT / CPR;                       // LDS rows one block-wide load covers
+  static constexpr int NL = BYTES / (NT * 16);                 // loads per thread and k-tile
+  static constexpr int TX = WX / 32;                           // 32-wide sub-tiles per wave
+  // swizzle of the M/N-contiguous layout
+  static constexpr int UPR = BX / 32;                          // 64-byte units per row
+  static constexpr int RPB = (4 / UPR) > 1 ? (4 / UPR) : 1;    // rows per 256-byte bank line
+  static constexpr int GM = UPR < 4 ? UPR : 4;
+  static constexpr int NRD = LAY == LAY_K ? BK / 16 : TX;      // lane-address registers of the reader
+  static constexpr int NRI = LAY == LAY_K ? TX : 2 * TX;       // LDS read instructions per fragment
+  // 128-byte lines (or parts of lines) in the k-slice of one tile, for the L2 touches
+  static constexpr int LINES = LAY == LAY_K ? BX : BK * ((BX * 2) / 128);
+  static_assert(BYTES % (NT * 16) == 0, "loads per thread");
+  static_assert(LAY == LAY_K ? (RSTEP % 2 == 0 && (RSTEP / 2) % CPR == 0)
+                             : (RSTEP % (4 * RPB) == 0), "swizzle period");
+  // logical 16-byte chunk -> physical chunk within LDS row `row`
+  __device__ static __forceinline__ int swz(int row)
+  {
+    return LAY == LAY_K ? ((row >> 1) % CPR) : (((row / RPB) % GM) << 2);
+  }
+};
+
 template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int S_, int R_, int FUSE_,
-          int BL_, int AM_>
+          int BL_, int AM_, int AL_ = 0>
 struct KCfg {
   static constexpr int DT = DT_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
-  static constexpr int S = S_, R = R_, FUSE = FUSE_, BL = BL_, AM = AM_;
+  static constexpr int S = S_, R = R_, FUSE = FUSE_, BL = BL_, AM = AM_, AL = AL_;
   static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, NWAVES = WAVES_M * WAVES_N;
   static constexpr int NT = NWAVES * 64;
+  // AL: 0 = A stored M x K, 1 = A stored K x M.  BL: 0 = B stored K x N, 1 = B stored N x K.
+  using OA = Opnd<AL ? LAY_MN : LAY_K, BM, WM, BK, NT>;
+  using OB = Opnd<BL ? LAY_K : LAY_MN, BN, WN, BK, NT>;
   static constexpr int TM = WM / 32, TN = WN / 32, NKI = BK / 16;
-  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+  static constexpr int A_BYTES = OA::BYTES, B_BYTES = OB::BYTES;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int RING_BYTES = S * STAGE_BYTES;
   static constexpr int EPI_WAVE_BYTES = 32 * (WN * 4 + 16);     // epilogue band, fp32 worst case
   static constexpr int MAIN_BYTES = RING_BYTES + NWAVES * 256;  // + landing pad of the L2 touches
   static constexpr int LDS_BYTES =
       MAIN_BYTES > NWAVES * EPI_WAVE_BYTES ? MAIN_BYTES : NWAVES * EPI_WAVE_BYTES;
-  static constexpr int NLA = A_BYTES / (NT * 16), NLB = B_BYTES / (NT * 16);
+  static constexpr int NLA = OA::NL, NLB = OB::NL;
   static constexpr int L = NLA + NLB + 1;   // per wave and k-tile: tile loads + one L2 touch
-  static constexpr int CPR_A = BK / 8;                       // 16-byte chunks per A-tile row
-  static constexpr int RSTEP_A = NT / CPR_A;                 // tile rows covered by one load
-  static constexpr int CPR_B = BL ? BK / 8 : BN / 8;
-  static constexpr int RSTEP_B = NT / CPR_B;
-  // swizzle of the N-contiguous B tile
-  static constexpr int UPR = BN / 32;                        // 64-byte units per row
-  static constexpr int RPB = (4 / UPR) > 1 ? (4 / UPR) : 1;  // rows per 256-byte bank line
-  static constexpr int GM = UPR < 4 ? UPR : 4;
   static constexpr int WAIT = (S >= 2 ? (S - 2) * L : 0);    // loads allowed in flight at a wait
   static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "wave tile");
   static_assert(BK == 32 || BK == 64, "bk");
-  static_assert(A_BYTES % (NT * 16) == 0 && B_BYTES % (NT * 16) == 0, "loads per thread");
-  static_assert(RSTEP_A % 2 == 0 && (RSTEP_A / 2) % CPR_A == 0, "A swizzle period");
-  static_assert(BL ? (RSTEP_B % 2 == 0 && (RSTEP_B / 2) % CPR_B == 0)
-                   : (RSTEP_B % (4 * RPB) == 0), "B swizzle period");
   static_assert(S >= 1 && S <= 4 && (R == 1 || R == 2), "stages");
   static_assert(!FUSE || (R == 2 && S >= 2), "fusion needs a register double buffer and S>=2");
+  static_assert(!(AM == 1 && AL == 1), "the convolution gather produces a K-contiguous A tile");
   static_assert(WAIT <= 63, "vmcnt is a 6-bit counter");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
 };
@@ -175,6 +200,113 @@ __device__ __forceinline__ u32x2 lds_read_tr8(uint32_t addr)
   return __builtin_bit_cast(u32x2, v);
 }
 
+// Per-lane state of the producer side of one operand.
+struct LoadState {
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t voff;     // byte offset of this lane's chunk in load 0 of k-tile 0
+  uint32_t voff_t;   // the same for a partial last k-tile (out of range if the chunk is past K)
+  uint32_t step;     // byte distance between consecutive loads of one k-tile
+  uint32_t kstep;    // byte distance between consecutive k-tiles
+};
+
+// Producer set-up.  `ptr` is the operand of this batch entry, `t` the tile index along the
+// operand's own dimension, `extent` its size there (M or N), `ld` the leading dimension.
+// Lane q0 of the block owns 16-byte LDS slot q0 (+ NT per further load); which global chunk it
+// fetches follows from the swizzle.  The descriptor covers exactly the valid part of the
+// operand seen from the tile's origin, so rows / columns / k beyond it read as zero.
+template <class O>
+__device__ __forceinline__ LoadState setup_loader(const void* ptr, int t, int extent, int ld, int K,
+                                                  int nko, int q0)
+{
+  LoadState st;
+  const int r = q0 / O::CPR, ph = q0 % O::CPR;
+  const int c = ph ^ O::swz(r);
+  const int valid = (extent - t * O::BX) < O::BX ? (extent - t * O::BX) : O::BX;
+  if constexpr (O::LAY == LAY_K) {
+    const char* base = (const char*)ptr + (long)t * O::BX * ld * 2;
+    st.rsrc = make_rsrc(base, ((valid - 1) * ld + K) * 2);
+    st.voff = (uint32_t)(r * ld * 2 + c * 16);
+    st.step = (uint32_t)(O::RSTEP * ld * 2);
+    st.kstep = O::BK * 2;
+    st.voff_t = ((nko - 1) * O::BK + c * 8 >= K) ? (st.voff | 0x80000000u) : st.voff;
+  } else {
+    const char* base = (const char*)ptr + (long)t * O::BX * 2;
+    st.rsrc = make_rsrc(base, ((K - 1) * ld + valid) * 2);
+    st.voff = (uint32_t)(r * ld * 2 + c * 16);
+    st.step = (uint32_t)(O::RSTEP * ld * 2);
+    st.kstep = (uint32_t)(O::BK * ld * 2);
+    st.voff_t = st.voff;   // rows k >= K lie beyond the descriptor
+  }
+  return st;
+}
+
+// Consumer set-up: lane addresses (relative to the stage base) of the operand fragment that
+// feeds v_mfma_f32_32x32x16: lane l = row/column l%32 of a 32-wide sub-tile, k = 8*(l/32)..+7.
+template <class O>
+__device__ __forceinline__ void setup_reader(int lane, int wx, uint32_t tile_off,
+                                             uint32_t (&rd)[O::NRD])
+{
+  if constexpr (O::LAY == LAY_K) {
+    const int row = wx * O::WX + (lane & 31);
+#pragma unroll
+    for (int ki = 0; ki < O::NRD; ki++)
+      rd[ki] = tile_off + (uint32_t)(row * (O::BK * 2) + (((2 * ki + (lane >> 5)) ^ O::swz(row)) * 16));
+  } else {
+    // transposing read: 16-lane group G reads 4 k-rows x 16 columns; lane s of the group
+    // supplies row s/4, columns 4*(s%4)..+3 and receives column s, rows 0..3.
+    const int G = lane >> 4, s = lane & 15;
+    const int k = 8 * (G >> 1) + (s >> 2);
+#pragma unroll
+    for (int t = 0; t < O::NRD; t++) {
+      const int n = wx * O::WX + t * 32 + 16 * (G & 1) + 4 * (s & 3);
+      const int c = (n >> 3) ^ O::swz(k);
+      rd[t] = tile_off + (uint32_t)(k * (O::BX * 2) + c * 16 + (n & 7) * 2);
+    }
+  }
+}
+
+// LDS read instruction r (0 <= r < O::NRI) of fragment ki; cur[] = slot base + lane addresses.
+template <class O>
+__device__ __forceinline__ void read_instr(const uint32_t (&cur)[O::NRD], int ki, int r,
+                                           u32x4 (&frag)[O::TX])
+{
+  if constexpr (O::LAY == LAY_K) {
+    frag[r] = lds_read16(cur[ki] + r * (32 * O::BK * 2));
+  } else {
+    const int t = r >> 1, h = r & 1;
+    const u32x2 v = lds_read_tr8(cur[t] + ki * (16 * O::BX * 2) + h * (4 * O::BX * 2));
+    frag[t][2 * h] = v[0];
+    frag[t][2 * h + 1] = v[1];
+  }
+}
+
+// Address of the 128-byte line that lane j of an operand's L2-touch share owns in k-tile 0, and
+// the byte step from one k-tile to the next.  The lines of the tile's k-slice are dealt round
+// robin to the `sharers` blocks that load the same panel; `me` is this block's index among them.
+// Returns false when lane j has no line.
+template <class O>
+__device__ __forceinline__ bool touch_line(const void* ptr, int t, int extent, int ld, int j,
+                                           int sharers, int me, const char** out, uint32_t* kstep)
+{
+  if constexpr (O::LAY == LAY_K) {
+    if (j >= O::LINES / sharers) return false;
+    int row = j * sharers + me;
+    if (t * O::BX + row >= extent) row = 0;
+    *out = (const char*)ptr + ((long)t * O::BX + row) * ld * 2;
+    *kstep = O::BK * 2;
+  } else {
+    constexpr int LPR = (O::BX * 2) / 128;                  // lines per k-row of the tile
+    if (j >= O::LINES / sharers) return false;
+    const int line = j * sharers + me;
+    const int row = line / LPR;
+    int seg = line % LPR;
+    if (t * O::BX + seg * 64 >= extent) seg = 0;
+    *out = (const char*)ptr + ((long)row * ld + (long)t * O::BX + seg * 64) * 2;
+    *kstep = (uint32_t)(O::BK * ld * 2);
+  }
+  return true;
+}
+
 template <class C>
 __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
 {
@@ -211,149 +343,97 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   const bool ktail = (p.K % BK) != 0;
 
   // ---- global -> LDS producers -----------------------------------------------------------
-  const int q0 = wave * 64 + lane;            // 16-byte slot of this lane in load 0
-  __amdgpu_buffer_rsrc_t rsrcA, rsrcB;
-  uint32_t voffA, stepA = 0;
-  int kcA = 0, kcB = 0;                       // first k (within a k-tile) of this lane's chunk
-  // conv state: per-load row geometry
+  using OA = typename C::OA;
+  using OB = typename C::OB;
+  const int q0 = wave * 64 + lane;            // 16-byte LDS slot of this lane in load 0
+  const char* Abatch = (const char*)p.A + (long)batch * p.strideA * 2;
+  const char* Bbatch = (const char*)p.B + (long)batch * p.strideB * 2;
+  LoadState la, lb;
+  // convolution: per-load row geometry of the gathered A tile
   int ih0[NLA], iw0[NLA];
   uint32_t coff[NLA];
   int cr = 0, cs = 0, cc0 = 0;                // (r, s, c0) of the next k-tile to issue
-  {
-    const int r = q0 / C::CPR_A, ph = q0 % C::CPR_A;
-    const int c = ph ^ ((r >> 1) % C::CPR_A);
-    kcA = c * 8;
-    if constexpr (C::AM == 0) {
-      const int rows = (p.M - tm * BM) < BM ? (p.M - tm * BM) : BM;
-      const char* base = (const char*)p.A + ((long)batch * p.strideA + (long)tm * BM * p.lda) * 2;
-      rsrcA = make_rsrc(base, ((rows - 1) * p.lda + p.K) * 2);
-      voffA = (uint32_t)(r * p.lda * 2 + c * 16);
-      stepA = (uint32_t)(C::RSTEP_A * p.lda * 2);
-    } else {
-      rsrcA = make_rsrc(p.A, (int)p.a_span);
-      voffA = 0;
+  if constexpr (C::AM == 0) {
+    la = setup_loader<OA>(Abatch, tm, p.M, p.lda, p.K, nko, q0);
+  } else {
+    // implicit GEMM: row m of A is output pixel (img, p, q); a k-tile lies inside one filter tap
+    // (r, s) because bk divides C, so a lane's chunk is 16 contiguous bytes of x or padding.
+    la.rsrc = make_rsrc(p.A, (int)p.a_span);
+    la.voff = la.voff_t = la.step = la.kstep = 0;
+    const int r = q0 / OA::CPR, ph = q0 % OA::CPR;
+    const int c = ph ^ OA::swz(r);
 #pragma unroll
-      for (int i = 0; i < NLA; i++) {
-        const int m = tm * BM + r + i * C::RSTEP_A;
-        const int img = m / (p.cP * p.cQ);
-        const int pq = m - img * (p.cP * p.cQ);
-        const int pp = pq / p.cQ, qq = pq - pp * p.cQ;
-        ih0[i] = (m < p.M) ? pp * p.csh - p.cph : -0x40000000;
-        iw0[i] = qq * p.csw - p.cpw;
-        coff[i] = (uint32_t)((((img * p.cH + (pp * p.csh - p.cph)) * p.cW) + iw0[i]) * p.cC * 2 +
-                             c * 16);
-      }
+    for (int i = 0; i < NLA; i++) {
+      const int m = tm * BM + r + i * OA::RSTEP;
+      const int img = m / (p.cP * p.cQ);
+      const int pq = m - img * (p.cP * p.cQ);
+      const int pp = pq / p.cQ, qq = pq - pp * p.cQ;
+      ih0[i] = (m < p.M) ? pp * p.csh - p.cph : -0x40000000;
+      iw0[i] = qq * p.csw - p.cpw;
+      coff[i] = (uint32_t)((((img * p.cH + (pp * p.csh - p.cph)) * p.cW) + iw0[i]) * p.cC * 2 +
+                           c * 16);
     }
   }
-  uint32_t voffB, stepB, kstepB;
-  {
-    const int r = q0 / C::CPR_B, ph = q0 % C::CPR_B;
-    if constexpr (C::BL == 1) {                // B stored N x K: same shape of loader as A
-      const int c = ph ^ ((r >> 1) % C::CPR_B);
-      kcB = c * 8;
-      const int cols = (p.N - tn * BN) < BN ? (p.N - tn * BN) : BN;
-      const char* base = (const char*)p.B + ((long)batch * p.strideB + (long)tn * BN * p.ldb) * 2;
-      rsrcB = make_rsrc(base, ((cols - 1) * p.ldb + p.K) * 2);
-      voffB = (uint32_t)(r * p.ldb * 2 + c * 16);
-      stepB = (uint32_t)(C::RSTEP_B * p.ldb * 2);
-      kstepB = BK * 2;
-    } else {                                   // B stored K x N: tile rows are k
-      const int c = ph ^ (((r / C::RPB) % C::GM) << 2);
-      const int cols = (p.N - tn * BN) < BN ? (p.N - tn * BN) : BN;
-      const char* base = (const char*)p.B + ((long)batch * p.strideB + (long)tn * BN) * 2;
-      rsrcB = make_rsrc(base, ((p.K - 1) * p.ldb + cols) * 2);
-      voffB = (uint32_t)(r * p.ldb * 2 + c * 16);
-      stepB = (uint32_t)(C::RSTEP_B * p.ldb * 2);
-      kstepB = (uint32_t)(BK * p.ldb * 2);
-    }
-  }
+  lb = setup_loader<OB>(Bbatch, tn, p.N, p.ldb, p.K, nko, q0);
 
   // ---- HBM -> L2 touches (third pipeline level) --------------------------------------------
   // The blocks of one XCD that run side by side load the same A row-panel (those with equal tm)
   // or B column-panel (equal tn) at about the same time, so each line misses L2 once and all
   // sharers wait for that miss.  Touching the line pf_dist k-tiles earlier, once, by one of the
   // sharers, turns the tile loads into L2 hits.  Lane x of the block owns one line per k-tile.
-  const char* pf_ptr;
-  uint32_t pf_step = 0;
   const int pf_d = p.pf_dist < nko - 1 ? p.pf_dist : nko - 1;   // never past the last k-tile
-  {
-    const int x = wave * 64 + lane;
-    const char* abase = (const char*)p.A + ((long)batch * p.strideA + (long)tm * BM * p.lda) * 2;
-    pf_ptr = (C::AM == 0) ? abase : (const char*)p.B;     // a valid address for idle lanes
-    if (pf_d > 0) {
-      const int na = (C::AM == 0) ? BM / p.pf_pa : 0;
-      if (x < na) {
-        int row = x * p.pf_pa + tn % p.pf_pa;
-        if (tm * BM + row >= p.M) row = 0;
-        pf_ptr = abase + (long)row * p.lda * 2;
-        pf_step = BK * 2;
-      } else {
-        const int j = x - na;
-        if constexpr (C::BL == 1) {
-          if (j < BN / p.pf_pb) {
-            int row = j * p.pf_pb + tm % p.pf_pb;
-            if (tn * BN + row >= p.N) row = 0;
-            pf_ptr = (const char*)p.B +
-                     ((long)batch * p.strideB + ((long)tn * BN + row) * p.ldb) * 2;
-            pf_step = BK * 2;
-          }
-        } else {
-          constexpr int LPR = (BN * 2) / 128;               // 128-byte lines per k-row of the tile
-          if (j < BK * LPR / p.pf_pb) {
-            const int line = j * p.pf_pb + tm % p.pf_pb;
-            const int row = line / LPR;
-            int seg = line % LPR;
-            if (tn * BN + seg * 64 >= p.N) seg = 0;
-            pf_ptr = (const char*)p.B +
-                     ((long)batch * p.strideB + (long)row * p.ldb + (long)tn * BN + seg * 64) * 2;
-            pf_step = (uint32_t)(BK * p.ldb * 2);
-          }
-        }
-      }
-      pf_ptr += (long)pf_step * pf_d;
+  const char* pf_ptr = Bbatch;                // a valid address for lanes without a line
+  uint32_t pf_step = 0;
+  if (pf_d > 0) {
+    const int na = (C::AM == 0) ? OA::LINES / p.pf_pa : 0;   // lines of A this block touches
+    bool have = false;
+    if constexpr (C::AM == 0)
+      have = touch_line<OA>(Abatch, tm, p.M, p.lda, q0, p.pf_pa, tn % p.pf_pa, &pf_ptr, &pf_step);
+    if (!have && q0 >= na)
+      have = touch_line<OB>(Bbatch, tn, p.N, p.ldb, q0 - na, p.pf_pb, tm % p.pf_pb, &pf_ptr, &pf_step);
+    if (!have) {
+      pf_ptr = Bbatch;
+      pf_step = 0;
     }
+    pf_ptr += (long)pf_step * pf_d;
   }
   const uint32_t pf_dst = lds0 + C::RING_BYTES + (uint32_t)wave * 256u;
 
   // Loads of one k-tile: stage_begin fixes the wave-uniform offsets of k-tile `kt` and ring slot
-  // `slot`; issue_one(i) emits load i of the L loads a wave owns (A loads first, then B);
+  // `slot`; issue_one(i) emits load i of the L loads a wave owns (A loads, B loads, L2 touch);
   // stage_end advances the convolution tap.  Always exactly L loads per wave and stage.
+  // A partial last k-tile selects the lane offsets that zero-fill chunks at k >= K: one select
+  // per operand and k-tile, nothing per load.
   uint32_t st_ka = 0, st_kb = 0, st_dst = 0, st_tap = 0;
-  // Partial last k-tile (K % BK != 0): lanes whose chunk starts at k >= K get an out-of-range
-  // offset for that one k-tile and so zero-fill their 16 bytes.  Decided once per lane here and
-  // selected once per k-tile in stage_begin: nothing is added per load.
-  const uint32_t voffA_t = ((nko - 1) * BK + kcA >= p.K) ? (voffA | 0x80000000u) : voffA;
-  const uint32_t voffB_t =
-      (C::BL == 1 && (nko - 1) * BK + kcB >= p.K) ? (voffB | 0x80000000u) : voffB;
-  uint32_t st_voffA = voffA, st_voffB = voffB;
+  uint32_t st_voffA = la.voff, st_voffB = lb.voff;
   bool st_live = false, st_pf_live = false;
   auto stage_begin = [&](int kt, int slot) {
     st_live = kt < nko;
     const bool tail = ktail && kt == nko - 1;
-    st_voffA = tail ? voffA_t : voffA;
-    st_voffB = tail ? voffB_t : voffB;
+    st_voffA = tail ? la.voff_t : la.voff;
+    st_voffB = tail ? lb.voff_t : lb.voff;
     st_pf_live = kt + pf_d + 1 < nko;
     st_dst = lds0 + (uint32_t)slot * STAGE_BYTES + (uint32_t)wave * 1024u;
     if constexpr (C::AM == 0)
-      st_ka = st_live ? (uint32_t)kt * (BK * 2) : 0x80000000u;
+      st_ka = st_live ? (uint32_t)kt * la.kstep : 0x80000000u;
     else
       st_tap = (uint32_t)(((cr * p.cW + cs) * p.cC + cc0) * 2);
-    st_kb = st_live ? (uint32_t)kt * kstepB : 0x80000000u;
+    st_kb = st_live ? (uint32_t)kt * lb.kstep : 0x80000000u;
   };
   auto issue_one = [&](int idx) {
     if (idx < NLA) {
       const int i = idx;
       if constexpr (C::AM == 0) {
-        dma16(rsrcA, st_voffA + st_ka + (uint32_t)i * stepA, st_dst + i * (NWAVES * 1024));
+        dma16(la.rsrc, st_voffA + st_ka + (uint32_t)i * la.step, st_dst + i * (NWAVES * 1024));
       } else {
         const bool ok = st_live && (unsigned)(ih0[i] + cr) < (unsigned)p.cH &&
                         (unsigned)(iw0[i] + cs) < (unsigned)p.cW;
-        dma16(rsrcA, ok ? coff[i] + st_tap : 0x80000000u, st_dst + i * (NWAVES * 1024));
+        dma16(la.rsrc, ok ? coff[i] + st_tap : 0x80000000u, st_dst + i * (NWAVES * 1024));
       }
     } else if (idx < NLA + NLB) {
       const int i = idx - NLA;
-      // (K x N layout: rows k >= K of a partial k-tile lie beyond the descriptor: zero-filled)
-      dma16(rsrcB, st_voffB + st_kb + (uint32_t)i * stepB, st_dst + A_BYTES + i * (NWAVES * 1024));
+      dma16(lb.rsrc, st_voffB + st_kb + (uint32_t)i * lb.step,
+            st_dst + A_BYTES + i * (NWAVES * 1024));
     } else {
       touch4(pf_ptr, pf_dst);
       if (st_pf_live) pf_ptr += pf_step;      // stop at the last k-tile: never run past the operand
@@ -373,59 +453,26 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   };
 
   // ---- LDS -> register consumers ---------------------------------------------------------
-  // Y operand (from A): lane reads row wm*WM + t*32 + lane%32, logical chunk 2*ki + lane/32.
-  uint32_t rdA[NKI];
-  {
-    const int row = wm * WM + (lane & 31);
-#pragma unroll
-    for (int ki = 0; ki < NKI; ki++)
-      rdA[ki] = (uint32_t)(row * (BK * 2) + (((2 * ki + (lane >> 5)) ^ ((row >> 1) % C::CPR_A)) * 16));
-  }
-  // X operand (from B)
-  uint32_t rdB[C::BL ? NKI : TN];
-  if constexpr (C::BL == 1) {
-    const int row = wn * WN + (lane & 31);
-#pragma unroll
-    for (int ki = 0; ki < NKI; ki++)
-      rdB[ki] = (uint32_t)(A_BYTES + row * (BK * 2) +
-                           (((2 * ki + (lane >> 5)) ^ ((row >> 1) % C::CPR_B)) * 16));
-  } else {
-    // transposing read: 16-lane group G reads 4 k-rows x 16 columns; lane s of the group
-    // supplies row s/4, columns 4*(s%4)..+3 and receives column s, rows 0..3.
-    const int G = lane >> 4, s = lane & 15;
-    const int k = 8 * (G >> 1) + (s >> 2);
-#pragma unroll
-    for (int t = 0; t < TN; t++) {
-      const int n = wn * WN + t * 32 + 16 * (G & 1) + 4 * (s & 3);
-      const int c = (n >> 3) ^ (((k / C::RPB) % C::GM) << 2);
-      rdB[t] = (uint32_t)(A_BYTES + k * (BN * 2) + c * 16 + (n & 7) * 2);
-    }
-  }
-
-  // One LDS read instruction of fragment `ki`: r < TM reads A sub-tile r; the rest read B
-  // (one ds_read_b128 per sub-tile when K-contiguous, two transposing 8-byte reads otherwise).
-  // Read addresses of the slot being consumed (lane base + slot base), refreshed once per k-tile
-  // so that every read is "register + immediate".
-  constexpr int NRB = C::BL ? NKI : TN;
-  uint32_t curA[NKI], curB[NRB];
+  // Y operand (matrix-core column operand) from A, X operand (row operand) from B.  Lane
+  // addresses are fixed per kernel; cur* = slot base + lane address is refreshed once per
+  // k-tile so that every read is "register + immediate".
+  uint32_t rdA[OA::NRD], rdB[OB::NRD];
+  setup_reader<OA>(lane, wm, 0, rdA);
+  setup_reader<OB>(lane, wn, A_BYTES, rdB);
+  uint32_t curA[OA::NRD], curB[OB::NRD];
   auto set_read_slot = [&](uint32_t sbase) {
 #pragma unroll
-    for (int i = 0; i < NKI; i++) curA[i] = sbase + rdA[i];
+    for (int i = 0; i < OA::NRD; i++) curA[i] = sbase + rdA[i];
 #pragma unroll
-    for (int i = 0; i < NRB; i++) curB[i] = sbase + rdB[i];
+    for (int i = 0; i < OB::NRD; i++) curB[i] = sbase + rdB[i];
   };
-  constexpr int NRI = TM + TN * (C::BL ? 1 : 2);
+  // LDS read instruction r of fragment ki: the A reads come first, then the B reads.
+  constexpr int NRI = OA::NRI + OB::NRI;
   auto read_one = [&](int ki, int r, u32x4(&fa)[TM], u32x4(&fb)[TN]) {
-    if (r < TM) {
-      fa[r] = lds_read16(curA[ki] + r * (32 * BK * 2));
-    } else if constexpr (C::BL == 1) {
-      fb[r - TM] = lds_read16(curB[ki] + (r - TM) * (32 * BK * 2));
-    } else {
-      const int t = (r - TM) >> 1, h = (r - TM) & 1;
-      const u32x2 v = lds_read_tr8(curB[t] + ki * (16 * BN * 2) + h * (4 * BN * 2));
-      fb[t][2 * h] = v[0];
-      fb[t][2 * h + 1] = v[1];
-    }
+    if (r < OA::NRI)
+      read_instr<OA>(curA, ki, r, fa);
+    else
+      read_instr<OB>(curB, ki, r - OA::NRI, fb);
   };
   auto load_frags = [&](int ki, u32x4(&fa)[TM], u32x4(&fb)[TN]) {
 #pragma unroll
