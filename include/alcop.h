@@ -54,7 +54,7 @@ typedef enum {
   ALCOP_ERR_SCHED = -5,       /* schedule infeasible: no such kernel, LDS or wait-counter    */
                               /* limit exceeded, fuse_inner without reg_stages=2/stages>=2   */
   ALCOP_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch                          */
-  ALCOP_ERR_UNSUPPORTED = -7, /* valid request outside what is built (e.g. transA)           */
+  ALCOP_ERR_UNSUPPORTED = -7, /* valid request outside what is built (e.g. an unknown act)   */
   ALCOP_ERR_SIZE = -8         /* an operand spans 2 GiB or more                              */
 } alcop_status;
 
@@ -84,11 +84,13 @@ typedef struct {
   int transB;         /* 1: B stored N x K (K contiguous)                                   */
   alcop_dtype in, out;
   int conv_C;         /* conv only: input channels (bk must divide it)                      */
+  int transA;         /* 1: A stored K x M (M contiguous); GEMM / BMM only                  */
 } alcop_problem;
 
 /*
  * C[M,N] = A[M,K] . B[K,N]        (paper Sec. 6.1 "MatMul")
- *   A: row-major M x K, leading dimension lda (elements).  transA must be 0.
+ *   A: transA == 0: row-major M x K, lda >= K;  transA == 1: stored K x M, lda >= M
+ *      (M must then be a multiple of 8).
  *   B: transB == 0: row-major K x N, ldb >= N;  transB == 1: stored N x K, ldb >= K.
  *   C: row-major M x N, ldc >= N, element type `out`.
  */

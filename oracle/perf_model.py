@@ -65,7 +65,7 @@ def pipeline_latency_caption_form(t_load, t_use, n_loop, n_pipe, n_mplx):
 
 
 def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Device = Device(),
-            transB: bool = False):
+            transB: bool = False, transA: bool = False):
     """Returns a dict of the Table 1 quantities (microseconds)."""
     ntm, ntn = math.ceil(M / bm), math.ceil(N / bn)
     tiles = ntm * ntn
@@ -100,7 +100,7 @@ def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Devi
     # LDS port occupancy: fragment reads of all waves + DMA writes of the next k-tile share one port
     a_read = bm * bk * 2 * (bn // wn)
     b_read = bn * bk * 2 * (bm // wm)
-    t_port = (a_read / dev.bw_lds_cu + b_read / (dev.bw_lds_cu if transB else dev.bw_lds_tr_cu)
+    t_port = (a_read / (dev.bw_lds_tr_cu if transA else dev.bw_lds_cu) + b_read / (dev.bw_lds_cu if transB else dev.bw_lds_tr_cu)
               + bytes_one_smem_loop / dev.bw_lds_cu) * n_blk_per_cu
     t_smem_use = max(t_smem_use, t_port)
 

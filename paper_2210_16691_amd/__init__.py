@@ -59,7 +59,8 @@ class Problem(ctypes.Structure):
     """Mirror of ``alcop_problem``."""
     _fields_ = [("op", ctypes.c_int), ("batch", ctypes.c_int), ("M", ctypes.c_int),
                 ("N", ctypes.c_int), ("K", ctypes.c_int), ("transB", ctypes.c_int),
-                ("in_", ctypes.c_int), ("out", ctypes.c_int), ("conv_C", ctypes.c_int)]
+                ("in_", ctypes.c_int), ("out", ctypes.c_int), ("conv_C", ctypes.c_int),
+                ("transA", ctypes.c_int)]
 
 
 _lib = None
@@ -142,23 +143,25 @@ def _check(rc, what):
 
 
 # ---- the entry points (same names as the C ABI) ----------------------------------------------
-def alcop_gemm(A, B, C, sched=None, transB=False, stream=None):
-    """C[M,N] = A[M,K] . B  (B is [K,N], or [N,K] if transB).  Tensors are 2-D CUDA tensors whose
-    last dimension is contiguous; C's dtype selects the output type."""
-    M, K = A.shape
+def alcop_gemm(A, B, C, sched=None, transB=False, stream=None, transA=False):
+    """C[M,N] = A . B  (A is [M,K], or [K,M] if transA; B is [K,N], or [N,K] if transB).  Tensors
+    are 2-D CUDA tensors whose last dimension is contiguous; C's dtype selects the output type."""
+    K, M = A.shape if transA else A.shape[::-1]
     N = B.shape[0] if transB else B.shape[1]
     rc = lib().alcop_gemm(_ptr(A), _ptr(B), _ptr(C), M, N, K, A.stride(0), B.stride(0), C.stride(0),
-                          0, int(transB), _dtype_code(A), _dtype_code(C), _sp(sched), _stream(stream))
+                          int(transA), int(transB), _dtype_code(A), _dtype_code(C), _sp(sched),
+                          _stream(stream))
     _check(rc, "alcop_gemm")
     return C
 
 
-def alcop_bmm(A, B, C, sched=None, transB=False, stream=None):
-    """Batched: A [b,M,K], B [b,K,N] (or [b,N,K] if transB), C [b,M,N]."""
-    b, M, K = A.shape
+def alcop_bmm(A, B, C, sched=None, transB=False, stream=None, transA=False):
+    """Batched: A [b,M,K] (or [b,K,M] if transA), B [b,K,N] (or [b,N,K] if transB), C [b,M,N]."""
+    b = A.shape[0]
+    K, M = A.shape[1:] if transA else A.shape[:0:-1]
     N = B.shape[1] if transB else B.shape[2]
     rc = lib().alcop_bmm(_ptr(A), _ptr(B), _ptr(C), b, M, N, K, A.stride(1), B.stride(1), C.stride(1),
-                         A.stride(0), B.stride(0), C.stride(0), 0, int(transB),
+                         A.stride(0), B.stride(0), C.stride(0), int(transA), int(transB),
                          _dtype_code(A), _dtype_code(C), _sp(sched), _stream(stream))
     _check(rc, "alcop_bmm")
     return C
@@ -203,8 +206,8 @@ def alcop_conv2d_igemm(x, w, y, stride=(1, 1), pad=(0, 0), sched=None, stream=No
     return y
 
 
-def problem(op, M, N, K, in_dtype, out_dtype, batch=1, transB=False, conv_C=0) -> Problem:
-    return Problem(op, batch, M, N, K, int(transB), in_dtype, out_dtype, conv_C)
+def problem(op, M, N, K, in_dtype, out_dtype, batch=1, transB=False, conv_C=0, transA=False) -> Problem:
+    return Problem(op, batch, M, N, K, int(transB), in_dtype, out_dtype, conv_C, int(transA))
 
 
 def alcop_sched_supported(prob: Problem, s: Sched) -> int:

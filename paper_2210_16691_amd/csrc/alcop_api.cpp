@@ -26,6 +26,7 @@ const std::vector<KernelEntry>& registry()
     register_bf16_kn(t);
     register_nk(t);
     register_conv(t);
+    register_ta(t);
     return t;
   }();
   return table;
@@ -39,7 +40,7 @@ struct Call {
   void* C;
   int batch, M, N, K;
   long lda, ldb, ldc, strideA, strideB, strideC;
-  int transB;
+  int transA, transB;
   alcop_dtype in, out;
   // conv geometry
   int cN, cH, cW, cC, cK, cR, cS, csh, csw, cph, cpw, cP, cQ;
@@ -60,6 +61,7 @@ alcop_problem problem_of(const Call& c)
   p.N = c.N;
   p.K = c.K;
   p.transB = c.transB;
+  p.transA = c.transA;
   p.in = c.in;
   p.out = c.out;
   p.conv_C = c.op == ALCOP_OP_CONV2D ? c.cC : 0;
@@ -70,7 +72,8 @@ const KernelEntry* find_entry(const alcop_problem& p, const alcop_sched& s)
 {
   const int am = p.op == ALCOP_OP_CONV2D ? 1 : 0;
   for (const KernelEntry& e : registry())
-    if (e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.am == am && e.bm == s.bm &&
+    if (e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.al == (p.transA ? 1 : 0) &&
+        e.am == am && e.bm == s.bm &&
         e.bn == s.bn && e.bk == s.bk && e.wm == s.wm && e.wn == s.wn && e.stages == s.stages &&
         e.reg_stages == s.reg_stages && e.fuse == (s.fuse_inner ? 1 : 0))
       return &e;
@@ -85,7 +88,8 @@ int check_problem(const alcop_problem& p)
     return ALCOP_ERR_UNSUPPORTED;
   if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.batch <= 0 || p.batch > 65535) return ALCOP_ERR_SHAPE;
   if (p.N % 8 != 0 || p.K % 8 != 0) return ALCOP_ERR_SHAPE;
-  if (p.op == ALCOP_OP_CONV2D && (p.transB || p.conv_C <= 0 || p.K % p.conv_C != 0))
+  if (p.transA && p.M % 8 != 0) return ALCOP_ERR_SHAPE;
+  if (p.op == ALCOP_OP_CONV2D && (p.transA || p.transB || p.conv_C <= 0 || p.K % p.conv_C != 0))
     return ALCOP_ERR_SHAPE;
   return ALCOP_OK;
 }
@@ -122,7 +126,7 @@ std::vector<alcop_sched> space_of(const alcop_problem& p)
   std::vector<alcop_sched> v;
   const int am = p.op == ALCOP_OP_CONV2D ? 1 : 0;
   for (const KernelEntry& e : registry())
-    if (e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.am == am)
+    if (e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.al == (p.transA ? 1 : 0) && e.am == am)
     {
       v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1, 0});
       // the fused multi-level kernels are also offered with the third (HBM -> L2) level on
@@ -133,13 +137,14 @@ std::vector<alcop_sched> space_of(const alcop_problem& p)
   return v;
 }
 
-using CacheKey = std::tuple<int, int, int, int, int, int, int, int, int>;
+using CacheKey = std::tuple<int, int, int, int, int, int, int, int, int, int>;
 std::mutex g_cache_mu;
 std::map<CacheKey, alcop_sched> g_cache;   // problem -> chosen schedule (tuned or model top-1)
 
 CacheKey key_of(const alcop_problem& p)
 {
-  return CacheKey{(int)p.op, p.batch, p.M, p.N, p.K, p.transB, (int)p.in, (int)p.out, p.conv_C};
+  return CacheKey{(int)p.op, p.batch, p.M, p.N, p.K, p.transB, (int)p.in, (int)p.out, p.conv_C,
+                  p.transA};
 }
 
 // Model's top-1 among the feasible schedules (used when the caller passes no schedule).
@@ -189,7 +194,8 @@ int check_call(const Call& c)
   }
   if ((c.lda | c.ldb | c.ldc) & 7) return ALCOP_ERR_ALIGN;
   if (c.batch > 1 && ((c.strideA | c.strideB | c.strideC) & 7)) return ALCOP_ERR_ALIGN;
-  if (c.lda < c.K || c.ldb < (c.transB ? c.K : c.N) || c.ldc < c.N) return ALCOP_ERR_SHAPE;
+  if (c.lda < (c.transA ? c.M : c.K) || c.ldb < (c.transB ? c.K : c.N) || c.ldc < c.N)
+    return ALCOP_ERR_SHAPE;
   if (c.lda >= (1L << 30) || c.ldb >= (1L << 30) || c.ldc >= (1L << 30)) return ALCOP_ERR_SIZE;
   return ALCOP_OK;
 }
@@ -201,7 +207,7 @@ int span_check(const Call& c, const alcop_sched& s)
     return ALCOP_OK;
   }
   const double rows = std::min(s.bm, c.M), cols = std::min(s.bn, c.N);
-  const double a = 2.0 * ((rows - 1) * c.lda + c.K);
+  const double a = c.transA ? 2.0 * ((double)(c.K - 1) * c.lda + rows) : 2.0 * ((rows - 1) * c.lda + c.K);
   const double b = c.transB ? 2.0 * ((cols - 1) * c.ldb + c.K) : 2.0 * ((double)(c.K - 1) * c.ldb + cols);
   if (a >= 2147483648.0 || b >= 2147483648.0) return ALCOP_ERR_SIZE;
   return ALCOP_OK;
@@ -276,7 +282,7 @@ int run(const Call& c, const alcop_sched* sched, void* stream)
 }
 
 Call gemm_call(alcop_op op, const void* A, const void* B, void* C, int batch, int M, int N, int K,
-               long lda, long ldb, long ldc, long sA, long sB, long sC, int transB,
+               long lda, long ldb, long ldc, long sA, long sB, long sC, int transA, int transB,
                alcop_dtype in, alcop_dtype out)
 {
   Call c;
@@ -295,6 +301,7 @@ Call gemm_call(alcop_op op, const void* A, const void* B, void* C, int batch, in
   c.strideA = sA;
   c.strideB = sB;
   c.strideC = sC;
+  c.transA = transA ? 1 : 0;
   c.transB = transB ? 1 : 0;
   c.in = in;
   c.out = out;
@@ -358,7 +365,7 @@ int call_of_problem(const alcop_problem* prob, const void* A, const void* B, voi
     return ALCOP_OK;
   }
   *out = gemm_call(prob->op, A, B, C, prob->batch, prob->M, prob->N, prob->K, lda, ldb, ldc, sA,
-                   sB, sC, prob->transB, prob->in, prob->out);
+                   sB, sC, prob->transA, prob->transB, prob->in, prob->out);
   return ALCOP_OK;
 }
 
@@ -400,8 +407,7 @@ int alcop_gemm(const void* A, const void* B, void* C, int M, int N, int K, long 
                long ldc, int transA, int transB, alcop_dtype in, alcop_dtype out,
                const alcop_sched* sched, void* hip_stream)
 {
-  if (transA) return ALCOP_ERR_UNSUPPORTED;
-  Call c = gemm_call(ALCOP_OP_GEMM, A, B, C, 1, M, N, K, lda, ldb, ldc, 0, 0, 0, transB, in, out);
+  Call c = gemm_call(ALCOP_OP_GEMM, A, B, C, 1, M, N, K, lda, ldb, ldc, 0, 0, 0, transA, transB, in, out);
   return run(c, sched, hip_stream);
 }
 
@@ -409,9 +415,8 @@ int alcop_bmm(const void* A, const void* B, void* C, int batch, int M, int N, in
               long ldb, long ldc, long strideA, long strideB, long strideC, int transA, int transB,
               alcop_dtype in, alcop_dtype out, const alcop_sched* sched, void* hip_stream)
 {
-  if (transA) return ALCOP_ERR_UNSUPPORTED;
   Call c = gemm_call(ALCOP_OP_BMM, A, B, C, batch, M, N, K, lda, ldb, ldc, strideA, strideB,
-                     strideC, transB, in, out);
+                     strideC, transA, transB, in, out);
   return run(c, sched, hip_stream);
 }
 
@@ -419,8 +424,7 @@ int alcop_gemm_fused(const void* A, const void* B, void* C, int M, int N, int K,
                      long ldc, int transA, int transB, alcop_dtype in, alcop_dtype out,
                      const alcop_epilogue* ep, const alcop_sched* sched, void* hip_stream)
 {
-  if (transA) return ALCOP_ERR_UNSUPPORTED;
-  Call c = gemm_call(ALCOP_OP_GEMM, A, B, C, 1, M, N, K, lda, ldb, ldc, 0, 0, 0, transB, in, out);
+  Call c = gemm_call(ALCOP_OP_GEMM, A, B, C, 1, M, N, K, lda, ldb, ldc, 0, 0, 0, transA, transB, in, out);
   if (ep) {
     c.alpha = ep->alpha;
     c.bias = ep->bias;
@@ -434,9 +438,8 @@ int alcop_bmm_fused(const void* A, const void* B, void* C, int batch, int M, int
                     int transB, alcop_dtype in, alcop_dtype out, const alcop_epilogue* ep,
                     const alcop_sched* sched, void* hip_stream)
 {
-  if (transA) return ALCOP_ERR_UNSUPPORTED;
   Call c = gemm_call(ALCOP_OP_BMM, A, B, C, batch, M, N, K, lda, ldb, ldc, strideA, strideB,
-                     strideC, transB, in, out);
+                     strideC, transA, transB, in, out);
   if (ep) {
     c.alpha = ep->alpha;
     c.bias = ep->bias;

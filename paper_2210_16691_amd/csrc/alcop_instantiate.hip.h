@@ -31,13 +31,14 @@ constexpr bool instance_feasible(int bm, int bn, int bk, int wm, int wn, int s, 
   return true;
 }
 
-template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int R, int F, int BL, int AM>
+template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int R, int F, int BL, int AM,
+          int AL = 0>
 void add_instance(std::vector<KernelEntry>& t)
 {
   if constexpr (instance_feasible(BM, BN, BK, WM, WN, S, R, F)) {
-    using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM>;
-    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, C::LDS_BYTES, C::NT, C::L,
-                            &launch_instance<C>});
+    using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL>;
+    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, C::LDS_BYTES, C::NT,
+                            C::L, &launch_instance<C>});
   }
 }
 
@@ -66,6 +67,15 @@ void add_instance(std::vector<KernelEntry>& t)
   add_instance<DT, BM, BN, BK, WM, WN, 2, 2, 1, BL, AM>(T);      \
   add_instance<DT, BM, BN, BK, WM, WN, 3, 2, 1, BL, AM>(T);      \
   add_instance<DT, BM, BN, BK, WM, WN, 4, 2, 1, BL, AM>(T);
+
+// The same reduced set for A stored K x M (transA).
+#define ALCOP_KEY_PIPES_TA(T, DT, BM, BN, BK, WM, WN, BL)          \
+  add_instance<DT, BM, BN, BK, WM, WN, 1, 1, 0, BL, 0, 1>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 2, 1, 0, BL, 0, 1>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 3, 1, 0, BL, 0, 1>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 2, 2, 1, BL, 0, 1>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 3, 2, 1, BL, 0, 1>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 4, 2, 1, BL, 0, 1>(T);
 
 #define ALCOP_BOTH_BK(MACRO, T, DT, BM, BN, WM, WN, BL, AM) \
   MACRO(T, DT, BM, BN, 32, WM, WN, BL, AM)                  \

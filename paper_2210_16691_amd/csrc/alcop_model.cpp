@@ -82,7 +82,7 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   {
     const double a_read = bm * bk * 2.0 * (bn / wn);   // every A row is read by the waves along n
     const double b_read = bn * bk * 2.0 * (bm / wm);
-    const double t_port = (a_read / dev.bw_lds_cu +
+    const double t_port = (a_read / (prob.transA ? dev.bw_lds_tr_cu : dev.bw_lds_cu) +
                            b_read / (prob.transB ? dev.bw_lds_cu : dev.bw_lds_tr_cu) +
                            stage_bytes / dev.bw_lds_cu) * blk_per_cu;
     t_smem_use = std::max(t_smem_use, t_port);

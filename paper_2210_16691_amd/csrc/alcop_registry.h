@@ -8,7 +8,7 @@
 namespace alcop {
 
 struct KernelEntry {
-  int dt, bm, bn, bk, wm, wn, stages, reg_stages, fuse, bl, am;
+  int dt, bm, bn, bk, wm, wn, stages, reg_stages, fuse, bl, am, al;
   int lds_bytes, threads, loads_per_stage;
   hipError_t (*launch)(const Params&, dim3, hipStream_t);
 };
@@ -20,6 +20,7 @@ void register_f16_kn_small(std::vector<KernelEntry>&);
 void register_bf16_kn(std::vector<KernelEntry>&);
 void register_nk(std::vector<KernelEntry>&);
 void register_conv(std::vector<KernelEntry>&);
+void register_ta(std::vector<KernelEntry>&);
 
 const std::vector<KernelEntry>& registry();
 

@@ -43,7 +43,8 @@ def test_null_and_bad_arguments_are_rejected_without_a_launch():
         A, B, C, M, N, K, lda, ldb, ldc, tA, tB, i, o, ctypes.byref(s), None)
     assert g(None, fake, fake, 128, 128, 64, 64, 128, 128, 0, 0, 0, 0) == al.ERR_NULL
     assert g(fake, fake, None, 128, 128, 64, 64, 128, 128, 0, 0, 0, 0) == al.ERR_NULL
-    assert g(fake, fake, fake, 128, 128, 64, 64, 128, 128, 1, 0, 0, 0) == al.ERR_UNSUPPORTED
+    assert g(fake, fake, fake, 128, 128, 64, 64, 128, 128, 1, 0, 0, 0) == al.ERR_SHAPE   # transA: lda < M
+    assert g(fake, fake, fake, 100, 128, 64, 104, 128, 128, 1, 0, 0, 0) == al.ERR_SHAPE  # transA: M % 8
     assert g(fake, fake, fake, 128, 128, 64, 64, 128, 128, 0, 0, 2, 0) == al.ERR_DTYPE
     assert g(fake, fake, fake, 128, 128, 64, 64, 128, 128, 0, 0, 0, 7) == al.ERR_DTYPE
     assert g(fake, fake, fake, 0, 128, 64, 64, 128, 128, 0, 0, 0, 0) == al.ERR_SHAPE

@@ -87,19 +87,23 @@ PROBLEMS = [
     dict(op=al.OP_GEMM, M=1000, N=264, K=512, i=al.F16, o=al.F32, batch=1, tb=False),
     dict(op=al.OP_BMM, M=512, N=512, K=64, i=al.F16, o=al.F16, batch=96, tb=True),
     dict(op=al.OP_BMM, M=512, N=64, K=512, i=al.F16, o=al.F16, batch=96, tb=False),
+    dict(op=al.OP_GEMM, M=2048, N=2048, K=2048, i=al.F16, o=al.F16, batch=1, tb=False, ta=True),
+    dict(op=al.OP_GEMM, M=1024, N=512, K=4096, i=al.BF16, o=al.F32, batch=1, tb=True, ta=True),
 ]
 
 
 @pytest.mark.parametrize("P", PROBLEMS)
 def test_library_model_matches_oracle(P):
-    prob = al.problem(P["op"], P["M"], P["N"], P["K"], P["i"], P["o"], batch=P["batch"], transB=P["tb"])
+    prob = al.problem(P["op"], P["M"], P["N"], P["K"], P["i"], P["o"], batch=P["batch"], transB=P["tb"],
+                      transA=P.get("ta", False))
     space = al.alcop_sched_space(prob)
     assert len(space) > 0
     ob = 4 if P["o"] == al.F32 else 2
     for s in space:
         us, terms = al.alcop_model_predict(prob, s, 0)
         r = pm.predict(P["M"], P["N"], P["K"], P["batch"], ob, s.bm, s.bn, s.bk, s.wm, s.wn,
-                       s.stages, s.reg_stages, bool(s.fuse_inner), transB=P["tb"])
+                       s.stages, s.reg_stages, bool(s.fuse_inner), transB=P["tb"],
+                       transA=P.get("ta", False))
         want = [r[k] for k in ("t_kernel", "t_threadblk", "t_init", "t_main_loop", "t_epilogue",
                                "t_smem_load", "t_smem_use", "n_threadblk_batch")]
         assert us == pytest.approx(r["t_kernel"], rel=1e-12)
