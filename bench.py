@@ -27,8 +27,9 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--quick", action="store_true", help="skip the other shapes and the CPU baseline")
-    ap.add_argument("--workload", default="gemm2048", choices=["gemm2048", "gemm8192", "ffn1", "ffn2"],
-                    help="GEMM configuration to time (the headline is gemm2048)")
+    ap.add_argument("--workload", default="gemm2048",
+                    help="configuration to time (the headline is gemm2048; other names of "
+                         "workloads.CONFIGS only together with --sched)")
     ap.add_argument("--tune-report", action="store_true",
                     help="exhaustive search on every configuration and the best-in-top-k curves of the "
                          "two static models (the paper's Sec. 6.4 experiment); prints one JSON object")
@@ -66,6 +67,38 @@ def main():
         print(json.dumps(tune_report(al, wl, torch, dev)))
         return
 
+    if a.sched:
+        # profiling mode: one fixed schedule of any configuration, no tuning, a minimal JSON line
+        s = al.sched(*[int(v) for v in a.sched.split(",")])
+        prob, Ad, Bd, Cd, conv, flops, byts = _setup(al, wl, torch, dev, a.workload)
+        cfg = wl.CONFIGS[a.workload]
+
+        def launch():
+            if cfg["kind"] == "gemm":
+                al.alcop_gemm(Ad, Bd, Cd, s, stream=stream)
+            elif cfg["kind"] == "bmm":
+                al.alcop_bmm(Ad, Bd, Cd, s, transB=cfg["transB"], stream=stream)
+            else:
+                al.alcop_conv2d_igemm(Ad, Bd, Cd, (1, 1), (1, 1), s, stream=stream)
+
+        for _ in range(a.warmup):
+            launch()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(a.steps):
+            launch()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / a.steps
+        print(json.dumps({"workload": a.workload, "schedule": repr(s), "kernel_us": round(us, 3),
+                          "tflops": round(flops / us / 1e6, 1),
+                          "gbs_algorithmic": round(byts / us / 1e3, 1), "steps": a.steps}))
+        return
+
+    if a.workload not in ("gemm2048", "gemm8192", "ffn1", "ffn2"):
+        sys.exit("bench.py: the tuned headline run supports the GEMM configurations; use --sched for " + a.workload)
     cfg, A, B = wl.make_inputs(a.workload)
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
     Ad, Bd = A.to(dev), B.to(dev)
@@ -73,24 +106,6 @@ def main():
     Cd = torch.empty(M, N, dtype=torch.float16 if cfg["out"] == "f16" else torch.bfloat16, device=dev)
     prob = al.problem(al.OP_GEMM, M, N, K, it, it)
     flops = 2.0 * M * N * K
-
-    if a.sched:
-        # profiling mode: one fixed schedule, no tuning, a minimal JSON line
-        s = al.sched(*[int(v) for v in a.sched.split(",")])
-        for _ in range(a.warmup):
-            al.alcop_gemm(Ad, Bd, Cd, s)
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record(stream)
-        for _ in range(a.steps):
-            al.alcop_gemm(Ad, Bd, Cd, s, stream=stream)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / a.steps
-        print(json.dumps({"workload": a.workload, "schedule": repr(s), "kernel_us": round(us, 3),
-                          "tflops": round(flops / us / 1e6, 1), "steps": a.steps}))
-        return
 
     # ---- tuning: exhaustive (the 100 % reference) and model-ranked top-k ------------------------
     ex = al.alcop_tune(prob, Ad, Bd, Cd, top_k=0, model=0, iters=30)

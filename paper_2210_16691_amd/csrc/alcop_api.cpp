@@ -239,7 +239,9 @@ int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipSt
   p.group_m = std::min(8, p.ntm);
   // sharers of a panel among the blocks one XCD runs side by side (32 CUs, blocks per CU by LDS)
   const int per_cu = std::max(1, std::min(2, (160 * 1024) / e->lds_bytes));
-  p.pf_dist = s.l2_prefetch;
+  // The touch addresses of an M/N-contiguous operand walk whole k-tiles; with a partial last
+  // k-tile some of them would lie past the operand's last row, so the level is switched off.
+  p.pf_dist = (c.K % s.bk == 0) ? s.l2_prefetch : 0;
   p.pf_pb = std::max(1, p.group_m);
   p.pf_pa = std::max(1, std::min(p.ntn, 32 * per_cu / p.pf_pb));
   while (p.pf_pa > 1 && s.bm / p.pf_pa < 1) p.pf_pa--;
