@@ -2,7 +2,7 @@
 tests - TEST INFRASTRUCTURE ONLY; shares no code with the library's C++ model.
 
 Symbols are the paper's.  Table 1 gives the structure; the terms it leaves open are read as
-follows (the same readings are listed in the design doc):
+follows:
 
   * Util(N_warp_per_threadblk, N_threadblk_per_SM): share of one CU's matrix throughput that one
     threadblock obtains = min(1, N_warp*N_blk/4) / N_blk  (4 matrix pipes per CU).
