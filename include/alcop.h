@@ -55,7 +55,8 @@ typedef enum {
                               /* limit exceeded, fuse_inner without reg_stages=2/stages>=2   */
   ALCOP_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch                          */
   ALCOP_ERR_UNSUPPORTED = -7, /* valid request outside what is built (e.g. an unknown act)   */
-  ALCOP_ERR_SIZE = -8         /* an operand spans 2 GiB or more                              */
+  ALCOP_ERR_SIZE = -8,        /* an operand spans 2 GiB or more                              */
+  ALCOP_ERR_IO = -9           /* a cache file could not be opened, read or written           */
 } alcop_status;
 
 /*
@@ -201,6 +202,24 @@ int alcop_tune(const alcop_problem* prob /* host */, const void* A, const void* 
                int* trials_run /* host */, int* space_size /* host */,
                alcop_sched* log_sched /* host */, double* log_pred_us /* host */,
                double* log_meas_us /* host */, int log_cap, void* hip_stream);
+
+/*
+ * The schedule a NULL / zero schedule argument resolves to for this problem: the entry of the
+ * tuning cache if there is one (written by alcop_tune or alcop_cache_load), else the feasible
+ * schedule with the lowest predicted latency under model 0.  Host only, launches nothing.
+ */
+int alcop_sched_auto(const alcop_problem* prob /* host */, alcop_sched* out /* host */);
+
+/*
+ * Tuning cache on disk (the tuner's trial outcome per problem, so that a later process skips the
+ * timing).  Text file, one line per problem:
+ *   op batch M N K transA transB in out conv_C : bm bn bk wm wn stages reg_stages fuse raster l2
+ * alcop_cache_save writes every cached entry and returns their number; alcop_cache_load merges
+ * the file's entries into the cache (entries that name a schedule this library cannot run for
+ * that problem are skipped) and returns the number accepted.  Negative return = alcop_status.
+ */
+int alcop_cache_save(const char* path /* host */);
+int alcop_cache_load(const char* path /* host */);
 
 /* Times `iters` back-to-back launches of one schedule with HIP events on the given stream
  * (after `warmup` untimed ones); writes the mean microseconds per launch.  Same operand

@@ -18,12 +18,13 @@ F16, BF16, F32 = 0, 1, 2
 OP_GEMM, OP_BMM, OP_CONV2D = 0, 1, 2
 
 OK = 0
-ERR_NULL, ERR_DTYPE, ERR_ALIGN, ERR_SHAPE, ERR_SCHED, ERR_LAUNCH, ERR_UNSUPPORTED, ERR_SIZE = (
-    -1, -2, -3, -4, -5, -6, -7, -8)
+ERR_NULL, ERR_DTYPE, ERR_ALIGN, ERR_SHAPE, ERR_SCHED, ERR_LAUNCH, ERR_UNSUPPORTED, ERR_SIZE, ERR_IO = (
+    -1, -2, -3, -4, -5, -6, -7, -8, -9)
 
 EXPORTS = [
     "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
+    "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
 ]
 
 
@@ -100,6 +101,12 @@ def lib() -> ctypes.CDLL:
                                  sp, dp, dp, i, vp]
         L.alcop_time.restype = i
         L.alcop_time.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, sp, i, i, dp, vp]
+        L.alcop_sched_auto.restype = i
+        L.alcop_sched_auto.argtypes = [pp, sp]
+        L.alcop_cache_save.restype = i
+        L.alcop_cache_save.argtypes = [ctypes.c_char_p]
+        L.alcop_cache_load.restype = i
+        L.alcop_cache_load.argtypes = [ctypes.c_char_p]
         L.alcop_strerror.restype = ctypes.c_char_p
         L.alcop_strerror.argtypes = [i]
         L.alcop_version.restype = ctypes.c_char_p
@@ -219,6 +226,27 @@ def alcop_sched_space(prob: Problem):
     arr = (Sched * max(n, 1))()
     lib().alcop_sched_space(ctypes.byref(prob), arr, n)
     return [Sched(*arr[i].key()) for i in range(n)]
+
+
+def alcop_sched_auto(prob: Problem) -> Sched:
+    """The schedule a None schedule resolves to (tuning cache, else the model's top-1)."""
+    s = Sched()
+    _check(lib().alcop_sched_auto(ctypes.byref(prob), ctypes.byref(s)), "alcop_sched_auto")
+    return s
+
+
+def alcop_cache_save(path: str) -> int:
+    n = lib().alcop_cache_save(os.fsencode(path))
+    if n < 0:
+        raise AlcopError(n, "alcop_cache_save")
+    return n
+
+
+def alcop_cache_load(path: str) -> int:
+    n = lib().alcop_cache_load(os.fsencode(path))
+    if n < 0:
+        raise AlcopError(n, "alcop_cache_load")
+    return n
 
 
 def alcop_model_predict(prob: Problem, s: Sched, model: int = 0):

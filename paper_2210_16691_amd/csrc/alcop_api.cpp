@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdio>
 #include <cstdint>
 #include <cstring>
 #include <map>
@@ -604,6 +605,71 @@ int alcop_tune(const alcop_problem* prob, const void* A, const void* B, void* C,
   return ALCOP_OK;
 }
 
+int alcop_sched_auto(const alcop_problem* prob, alcop_sched* out)
+{
+  if (!prob || !out) return ALCOP_ERR_NULL;
+  int rc = check_problem(*prob);
+  if (rc) return rc;
+  return auto_sched(*prob, out);
+}
+
+int alcop_cache_save(const char* path)
+{
+  if (!path) return ALCOP_ERR_NULL;
+  std::FILE* f = std::fopen(path, "w");
+  if (!f) return ALCOP_ERR_IO;
+  int n = 0;
+  {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    for (const auto& kv : g_cache) {
+      const CacheKey& k = kv.first;
+      const alcop_sched& s = kv.second;
+      // key order: op batch M N K transB in out conv_C transA
+      std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d : %d %d %d %d %d %d %d %d %d %d\n", std::get<0>(k),
+                   std::get<1>(k), std::get<2>(k), std::get<3>(k), std::get<4>(k), std::get<9>(k),
+                   std::get<5>(k), std::get<6>(k), std::get<7>(k), std::get<8>(k), s.bm, s.bn, s.bk,
+                   s.wm, s.wn, s.stages, s.reg_stages, s.fuse_inner, s.raster, s.l2_prefetch);
+      n++;
+    }
+  }
+  if (std::fclose(f) != 0) return ALCOP_ERR_IO;
+  return n;
+}
+
+int alcop_cache_load(const char* path)
+{
+  if (!path) return ALCOP_ERR_NULL;
+  std::FILE* f = std::fopen(path, "r");
+  if (!f) return ALCOP_ERR_IO;
+  int n = 0;
+  char line[512];
+  while (std::fgets(line, sizeof(line), f)) {
+    int op, batch, M, N, K, tA, tB, in, out, cc;
+    alcop_sched s;
+    if (std::sscanf(line, "%d %d %d %d %d %d %d %d %d %d : %d %d %d %d %d %d %d %d %d %d", &op, &batch,
+                    &M, &N, &K, &tA, &tB, &in, &out, &cc, &s.bm, &s.bn, &s.bk, &s.wm, &s.wn,
+                    &s.stages, &s.reg_stages, &s.fuse_inner, &s.raster, &s.l2_prefetch) != 20)
+      continue;
+    alcop_problem p;
+    p.op = (alcop_op)op;
+    p.batch = batch;
+    p.M = M;
+    p.N = N;
+    p.K = K;
+    p.transA = tA;
+    p.transB = tB;
+    p.in = (alcop_dtype)in;
+    p.out = (alcop_dtype)out;
+    p.conv_C = cc;
+    if (check_sched(p, s, nullptr) != ALCOP_OK) continue;   // not runnable here: ignore the entry
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    g_cache[key_of(p)] = s;
+    n++;
+  }
+  std::fclose(f);
+  return n;
+}
+
 const char* alcop_strerror(int code)
 {
   switch (code) {
@@ -616,6 +682,7 @@ const char* alcop_strerror(int code)
     case ALCOP_ERR_LAUNCH: return "HIP launch failed";
     case ALCOP_ERR_UNSUPPORTED: return "not supported";
     case ALCOP_ERR_SIZE: return "operand spans 2 GiB or more";
+    case ALCOP_ERR_IO: return "cache file could not be opened, read or written";
     default: return "unknown status";
   }
 }

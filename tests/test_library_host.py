@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported():
 def test_version_and_strerror():
     assert "gfx950" in al.version()
     assert al.strerror(0) == "ok"
-    for code in range(-8, 0):
+    for code in range(-9, 0):
         assert al.strerror(code) != "unknown status"
     assert al.strerror(-99) == "unknown status"
 
@@ -105,3 +105,67 @@ def test_space_is_not_empty_for_every_operator():
         sp = al.alcop_sched_space(p)
         assert len(sp) >= 6
         assert any(al.alcop_sched_supported(p, s) == al.OK for s in sp)
+
+
+def test_ctypes_mirrors_match_the_c_structs(tmp_path):
+    # compile a tiny C program against include/alcop.h and compare sizes / field offsets
+    import subprocess
+    src = tmp_path / "layout.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "alcop.h"
+int main(void) {
+  printf("%zu %zu %zu\n", sizeof(alcop_sched), sizeof(alcop_problem), sizeof(alcop_epilogue));
+  printf("%zu %zu %zu\n", offsetof(alcop_sched, l2_prefetch), offsetof(alcop_problem, transA),
+         offsetof(alcop_epilogue, act));
+  printf("%zu %zu\n", offsetof(alcop_problem, conv_C), offsetof(alcop_epilogue, bias));
+  return 0;
+}''')
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    out = subprocess.check_output([str(exe)]).decode().split()
+    got = [int(v) for v in out]
+    want = [ctypes.sizeof(al.Sched), ctypes.sizeof(al.Problem), ctypes.sizeof(al.Epilogue),
+            al.Sched.l2_prefetch.offset, al.Problem.transA.offset, al.Epilogue.act.offset,
+            al.Problem.conv_C.offset, al.Epilogue.bias.offset]
+    assert got == want
+
+
+def test_model_prefers_pipelining_and_large_tiles_on_a_large_square():
+    # sanity of the ranking on 8192^3: a multi-stage 256x256 schedule is predicted faster than its
+    # own 1-stage version and than any 64x64 schedule
+    p = al.problem(al.OP_GEMM, 8192, 8192, 8192, al.BF16, al.BF16)
+    t = lambda s: al.alcop_model_predict(p, s, 0)[0]
+    big = t(al.sched(256, 256, 32, 128, 64, 4, 2, 1))
+    assert big < t(al.sched(256, 256, 32, 128, 64, 1, 1, 0))
+    assert big < min(t(s) for s in al.alcop_sched_space(p) if s.bm == 64 and s.bn == 64)
+    # every prediction is finite and positive, for both models
+    for s in al.alcop_sched_space(p):
+        for m in (0, 1):
+            v = t(s) if m == 0 else al.alcop_model_predict(p, s, 1)[0]
+            assert v > 0 and v < 1e9
+
+
+def test_auto_schedule_is_the_models_top_one_and_cache_round_trip(tmp_path):
+    p = al.problem(al.OP_GEMM, 1536, 1024, 768, al.BF16, al.BF16)
+    feas = [s for s in al.alcop_sched_space(p) if al.alcop_sched_supported(p, s) == al.OK]
+    best = min(feas, key=lambda s: al.alcop_model_predict(p, s, 0)[0])
+    auto = al.alcop_sched_auto(p)
+    assert al.alcop_model_predict(p, auto, 0)[0] == al.alcop_model_predict(p, best, 0)[0]
+    # a cache file overrides the model's pick; lines that cannot run are ignored
+    f = tmp_path / "cache.txt"
+    f.write_text(
+        "0 1 1536 1024 768 0 0 1 1 0 : 64 64 32 32 32 2 2 1 1 0\n"      # valid
+        "0 1 1536 1024 768 0 0 1 1 0 : 96 64 32 32 32 2 2 1 1 0\n"      # no such kernel
+        "0 1 1000 1001 768 0 0 1 1 0 : 64 64 32 32 32 2 2 1 1 0\n"      # N % 8 != 0
+        "garbage\n")
+    assert al.alcop_cache_load(str(f)) == 1
+    assert al.alcop_sched_auto(p).key() == (64, 64, 32, 32, 32, 2, 2, 1, 1, 0)
+    out = tmp_path / "saved.txt"
+    n = al.alcop_cache_save(str(out))
+    assert n >= 1
+    assert "0 1 1536 1024 768 0 0 1 1 0 : 64 64 32 32 32 2 2 1 1 0" in out.read_text()
+    with pytest.raises(al.AlcopError) as e:
+        al.alcop_cache_load(str(tmp_path / "missing.txt"))
+    assert e.value.code == al.ERR_IO
