@@ -223,6 +223,8 @@ def alcop_sched_supported(prob: Problem, s: Sched) -> int:
 
 def alcop_sched_space(prob: Problem):
     n = lib().alcop_sched_space(ctypes.byref(prob), None, 0)
+    if n < 0:
+        raise AlcopError(n, "alcop_sched_space")
     arr = (Sched * max(n, 1))()
     lib().alcop_sched_space(ctypes.byref(prob), arr, n)
     return [Sched(*arr[i].key()) for i in range(n)]

@@ -195,6 +195,7 @@ int check_call(const Call& c)
   }
   if ((c.lda | c.ldb | c.ldc) & 7) return ALCOP_ERR_ALIGN;
   if (c.batch > 1 && ((c.strideA | c.strideB | c.strideC) & 7)) return ALCOP_ERR_ALIGN;
+  if (c.strideA < 0 || c.strideB < 0 || c.strideC < 0) return ALCOP_ERR_SHAPE;
   if (c.lda < (c.transA ? c.M : c.K) || c.ldb < (c.transB ? c.K : c.N) || c.ldc < c.N)
     return ALCOP_ERR_SHAPE;
   if (c.lda >= (1L << 30) || c.ldb >= (1L << 30) || c.ldc >= (1L << 30)) return ALCOP_ERR_SIZE;
@@ -207,9 +208,15 @@ int span_check(const Call& c, const alcop_sched& s)
     if (2.0 * ((double)(c.K - 1) * c.N + c.N) >= 2147483648.0) return ALCOP_ERR_SIZE;
     return ALCOP_OK;
   }
+  // The loaders form 32-bit byte offsets from a tile's origin.  For an operand whose rows run
+  // along k (A stored K x M, B stored K x N) the rows of a partial last k-tile lie past the
+  // descriptor and must stay below 2^31 as offsets, so that neither they nor the out-of-range
+  // mark added to the loads of the ring's tail can wrap into the valid range: K is rounded up
+  // to whole k-tiles there.
   const double rows = std::min(s.bm, c.M), cols = std::min(s.bn, c.N);
-  const double a = c.transA ? 2.0 * ((double)(c.K - 1) * c.lda + rows) : 2.0 * ((rows - 1) * c.lda + c.K);
-  const double b = c.transB ? 2.0 * ((cols - 1) * c.ldb + c.K) : 2.0 * ((double)(c.K - 1) * c.ldb + cols);
+  const double kceil = (double)((c.K + s.bk - 1) / s.bk) * s.bk;
+  const double a = c.transA ? 2.0 * ((kceil - 1) * c.lda + rows) : 2.0 * ((rows - 1) * c.lda + c.K);
+  const double b = c.transB ? 2.0 * ((cols - 1) * c.ldb + c.K) : 2.0 * ((kceil - 1) * c.ldb + cols);
   if (a >= 2147483648.0 || b >= 2147483648.0) return ALCOP_ERR_SIZE;
   return ALCOP_OK;
 }
@@ -470,6 +477,8 @@ int alcop_sched_supported(const alcop_problem* prob, const alcop_sched* sched)
 int alcop_sched_space(const alcop_problem* prob, alcop_sched* out, int cap)
 {
   if (!prob) return ALCOP_ERR_NULL;
+  const int rc = check_problem(*prob);
+  if (rc) return rc;
   const std::vector<alcop_sched> v = space_of(*prob);
   if (out)
     for (int i = 0; i < (int)v.size() && i < cap; i++) out[i] = v[i];

@@ -62,6 +62,30 @@ def test_null_and_bad_arguments_are_rejected_without_a_launch():
                                 None, None) == al.ERR_SHAPE       # filter larger than image
 
 
+def test_spans_strides_and_invalid_problems():
+    L = al.lib()
+    fake = ctypes.c_void_p(0x10000)
+    s = al.sched(128, 128, 64, 64, 64, 2, 2, 1)
+    bmm = lambda sA, sB, sC: L.alcop_bmm(fake, fake, fake, 4, 128, 128, 64, 64, 128, 128, sA, sB, sC,
+                                         0, 0, 0, 0, ctypes.byref(s), None)
+    assert bmm(-8192, 8192, 16384) == al.ERR_SHAPE            # a stride that walks backwards
+    assert bmm(8192, 8196, 16384) == al.ERR_ALIGN
+    # B stored K x N with a partial last k-tile: its rows k = K .. 63 are addressed past the
+    # operand, (64 - 1) * ldb * 2 bytes must stay below 2 GiB although (K - 1) * ldb * 2 does
+    ldb = 1 << 25
+    g = lambda K: L.alcop_gemm(fake, fake, fake, 128, 128, K, 64, ldb, 128, 0, 0, 0, 0,
+                               ctypes.byref(s), None)
+    assert 2 * (24 - 1) * ldb < 2 ** 31 <= 2 * (64 - 1) * ldb
+    assert g(24) == al.ERR_SIZE
+    # the same rule for A stored K x M
+    assert L.alcop_gemm(fake, fake, fake, 128, 128, 24, 1 << 25, 128, 128, 1, 0, 0, 0,
+                        ctypes.byref(al.sched(128, 128, 64, 64, 64, 3, 2, 1)), None) == al.ERR_SIZE
+    bad = al.problem(al.OP_GEMM, 128, 100, 64, al.F16, al.F16)
+    with pytest.raises(al.AlcopError) as e:
+        al.alcop_sched_space(bad)
+    assert e.value.code == al.ERR_SHAPE
+
+
 def test_feasibility_rules():
     p = al.problem(al.OP_GEMM, 2048, 2048, 2048, al.F16, al.F16)
     ok = al.sched(128, 128, 64, 64, 64, 3, 2, 1)
