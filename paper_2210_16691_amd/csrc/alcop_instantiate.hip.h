@@ -1,5 +1,6 @@
 // Helpers used by the instance shards: launcher template and cartesian-product macros.
 #pragma once
+#include "alcop_gfx950.hip.h"
 #include "alcop_registry.h"
 
 namespace alcop {
@@ -10,12 +11,12 @@ hipError_t launch_instance(const Params& p, dim3 grid, hipStream_t st)
   static bool attr_set = false;
   if (!attr_set) {
     // LDS rings above the default 64 KB per-block limit need an explicit opt-in.
-    hipError_t e = hipFuncSetAttribute((const void*)alcop_mainloop<C>,
+    hipError_t e = hipFuncSetAttribute((const void*)alcop_mainloop<C, Gfx950>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  alcop_mainloop<C><<<grid, dim3(C::NT), C::LDS_BYTES, st>>>(p);
+  alcop_mainloop<C, Gfx950><<<grid, dim3(C::NT), C::LDS_BYTES, st>>>(p);
   return hipGetLastError();
 }
 

@@ -31,9 +31,16 @@
 // with X lane l = row l%32, k = 8*(l/32)..+7, Y lane l = column l%32, same k, and D lane l =
 // column l%32, rows 8*(v/4) + 4*(l/32) + v%4 for v = 0..15.  We feed X from B (i = n) and Y
 // from A (j = m), so a lane owns 4 consecutive n of one output row m: a vector store.
+//
+// Hardware access.  Every machine-specific operation the loop uses (direct-to-LDS loads, wait
+// counters, the barrier, LDS reads, the matrix instruction, global stores) is a static member of
+// the policy class HW that the templates below take.  alcop_gfx950.hip.h implements it with
+// gfx950 instructions; a test build substitutes a functional model of the same operations and
+// runs this very loop on the CPU, one fibre per lane, with bounds checks.  This header contains
+// no device intrinsic itself; __global__, __device__, __forceinline__ and __launch_bounds__
+// come from the HIP runtime header (or from the test build) that is included before it.
 
 #pragma once
-#include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace alcop {
@@ -69,8 +76,6 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-#define ALCOP_LDS __attribute__((address_space(3)))
 
 // Layout of an operand tile, in global memory and (swizzled) in LDS.
 enum { LAY_K = 0,    // contiguous along k:            A stored M x K, B stored N x K
@@ -134,75 +139,10 @@ struct KCfg {
   static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
 };
 
-// Buffer resource for a wave-uniform base address.  The words are passed through
-// readfirstlane so that the descriptor provably lives in scalar registers.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int bytes)
-{
-  const uint64_t a = (uint64_t)(uintptr_t)base;
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
-  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
-  const int n = __builtin_amdgcn_readfirstlane(bytes);
-  return __builtin_amdgcn_make_buffer_rsrc((void*)(uintptr_t)(((uint64_t)hi << 32) | lo), 0, n,
-                                           0x00020000);
-}
-
-__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, uint32_t lds_dst)
-{
-  // M0 holds the wave-uniform LDS destination; lane l lands at M0 + 16*l.
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-               :
-               : "s"(lds_dst), "v"(voff), "s"(rsrc)
-               : "memory");
-}
-
-__device__ __forceinline__ void touch4(const char* gptr, uint32_t lds_dst)
-{
-  // 4-byte direct-to-LDS load per lane into a landing pad nobody reads: its only purpose is to
-  // bring the 128-byte line it touches into L2 ahead of the tile loads.
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
-               :
-               : "s"(lds_dst), "v"(gptr)
-               : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vm()
-{
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-__device__ __forceinline__ void wait_lds()
-{
-  asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
-}
-__device__ __forceinline__ void block_barrier()
-{
-  __builtin_amdgcn_s_barrier();
-}
-
-template <int DT>
-__device__ __forceinline__ f32x16 mma(u32x4 x, u32x4 y, f32x16 acc)
-{
-  if constexpr (DT == 0)
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, x),
-                                                  __builtin_bit_cast(f16x8, y), acc, 0, 0, 0);
-  else
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x),
-                                                   __builtin_bit_cast(bf16x8, y), acc, 0, 0, 0);
-}
-
-__device__ __forceinline__ u32x4 lds_read16(uint32_t addr)
-{
-  return *(const ALCOP_LDS u32x4*)(uintptr_t)addr;
-}
-__device__ __forceinline__ u32x2 lds_read_tr8(uint32_t addr)
-{
-  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ALCOP_LDS s16x4*)(uintptr_t)addr);
-  return __builtin_bit_cast(u32x2, v);
-}
-
 // Per-lane state of the producer side of one operand.
+template <class HW>
 struct LoadState {
-  __amdgpu_buffer_rsrc_t rsrc;
+  typename HW::Rsrc rsrc;
   uint32_t voff;     // byte offset of this lane's chunk in load 0 of k-tile 0
   uint32_t voff_t;   // the same for a partial last k-tile (out of range if the chunk is past K)
   uint32_t step;     // byte distance between consecutive loads of one k-tile
@@ -214,24 +154,24 @@ struct LoadState {
 // Lane q0 of the block owns 16-byte LDS slot q0 (+ NT per further load); which global chunk it
 // fetches follows from the swizzle.  The descriptor covers exactly the valid part of the
 // operand seen from the tile's origin, so rows / columns / k beyond it read as zero.
-template <class O>
-__device__ __forceinline__ LoadState setup_loader(const void* ptr, int t, int extent, int ld, int K,
-                                                  int nko, int q0)
+template <class O, class HW>
+__device__ __forceinline__ LoadState<HW> setup_loader(const void* ptr, int t, int extent, int ld,
+                                                      int K, int nko, int q0)
 {
-  LoadState st;
+  LoadState<HW> st;
   const int r = q0 / O::CPR, ph = q0 % O::CPR;
   const int c = ph ^ O::swz(r);
   const int valid = (extent - t * O::BX) < O::BX ? (extent - t * O::BX) : O::BX;
   if constexpr (O::LAY == LAY_K) {
     const char* base = (const char*)ptr + (long)t * O::BX * ld * 2;
-    st.rsrc = make_rsrc(base, ((valid - 1) * ld + K) * 2);
+    st.rsrc = HW::make_rsrc(base, ((valid - 1) * ld + K) * 2);
     st.voff = (uint32_t)(r * ld * 2 + c * 16);
     st.step = (uint32_t)(O::RSTEP * ld * 2);
     st.kstep = O::BK * 2;
     st.voff_t = ((nko - 1) * O::BK + c * 8 >= K) ? (st.voff | 0x80000000u) : st.voff;
   } else {
     const char* base = (const char*)ptr + (long)t * O::BX * 2;
-    st.rsrc = make_rsrc(base, ((K - 1) * ld + valid) * 2);
+    st.rsrc = HW::make_rsrc(base, ((K - 1) * ld + valid) * 2);
     st.voff = (uint32_t)(r * ld * 2 + c * 16);
     st.step = (uint32_t)(O::RSTEP * ld * 2);
     st.kstep = (uint32_t)(O::BK * ld * 2);
@@ -266,15 +206,15 @@ __device__ __forceinline__ void setup_reader(int lane, int wx, uint32_t tile_off
 }
 
 // LDS read instruction r (0 <= r < O::NRI) of fragment ki; cur[] = slot base + lane addresses.
-template <class O>
+template <class O, class HW>
 __device__ __forceinline__ void read_instr(const uint32_t (&cur)[O::NRD], int ki, int r,
                                            u32x4 (&frag)[O::TX])
 {
   if constexpr (O::LAY == LAY_K) {
-    frag[r] = lds_read16(cur[ki] + r * (32 * O::BK * 2));
+    frag[r] = HW::lds_read16(cur[ki] + r * (32 * O::BK * 2));
   } else {
     const int t = r >> 1, h = r & 1;
-    const u32x2 v = lds_read_tr8(cur[t] + ki * (16 * O::BX * 2) + h * (4 * O::BX * 2));
+    const u32x2 v = HW::lds_read_tr8(cur[t] + ki * (16 * O::BX * 2) + h * (4 * O::BX * 2));
     frag[t][2 * h] = v[0];
     frag[t][2 * h + 1] = v[1];
   }
@@ -307,23 +247,22 @@ __device__ __forceinline__ bool touch_line(const void* ptr, int t, int extent, i
   return true;
 }
 
-template <class C>
+template <class C, class HW>
 __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
 {
   constexpr int BM = C::BM, BN = C::BN, BK = C::BK, WM = C::WM, WN = C::WN, S = C::S;
   constexpr int TM = C::TM, TN = C::TN, NKI = C::NKI, NLA = C::NLA, NLB = C::NLB;
   constexpr int NWAVES = C::NWAVES, STAGE_BYTES = C::STAGE_BYTES, A_BYTES = C::A_BYTES;
 
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(ALCOP_LDS unsigned char*)smem;
+  const uint32_t lds0 = HW::lds_base();      // dynamic LDS of the block, 1024-byte aligned
 
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int lane = HW::lane_id();
+  const int wave = HW::wave_id();
   const int wm = wave % C::WAVES_M, wn = wave / C::WAVES_M;
-  const int batch = blockIdx.y;
+  const int batch = HW::block_y();
 
   // ---- block -> tile (paper Sec. 1: inter-tile parallelism; the order only affects L2 reuse)
-  int lid = blockIdx.x;
+  int lid = HW::block_x();
   const int nblk = p.ntm * p.ntn;
   int tm, tn;
   if (p.raster == 1) {
@@ -348,17 +287,17 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   const int q0 = wave * 64 + lane;            // 16-byte LDS slot of this lane in load 0
   const char* Abatch = (const char*)p.A + (long)batch * p.strideA * 2;
   const char* Bbatch = (const char*)p.B + (long)batch * p.strideB * 2;
-  LoadState la, lb;
+  LoadState<HW> la, lb;
   // convolution: per-load row geometry of the gathered A tile
   int ih0[NLA], iw0[NLA];
   uint32_t coff[NLA];
   int cr = 0, cs = 0, cc0 = 0;                // (r, s, c0) of the next k-tile to issue
   if constexpr (C::AM == 0) {
-    la = setup_loader<OA>(Abatch, tm, p.M, p.lda, p.K, nko, q0);
+    la = setup_loader<OA, HW>(Abatch, tm, p.M, p.lda, p.K, nko, q0);
   } else {
     // implicit GEMM: row m of A is output pixel (img, p, q); a k-tile lies inside one filter tap
     // (r, s) because bk divides C, so a lane's chunk is 16 contiguous bytes of x or padding.
-    la.rsrc = make_rsrc(p.A, (int)p.a_span);
+    la.rsrc = HW::make_rsrc(p.A, (int)p.a_span);
     la.voff = la.voff_t = la.step = la.kstep = 0;
     const int r = q0 / OA::CPR, ph = q0 % OA::CPR;
     const int c = ph ^ OA::swz(r);
@@ -374,7 +313,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
                            c * 16);
     }
   }
-  lb = setup_loader<OB>(Bbatch, tn, p.N, p.ldb, p.K, nko, q0);
+  lb = setup_loader<OB, HW>(Bbatch, tn, p.N, p.ldb, p.K, nko, q0);
 
   // ---- HBM -> L2 touches (third pipeline level) --------------------------------------------
   // The blocks of one XCD that run side by side load the same A row-panel (those with equal tm)
@@ -424,18 +363,18 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     if (idx < NLA) {
       const int i = idx;
       if constexpr (C::AM == 0) {
-        dma16(la.rsrc, st_voffA + st_ka + (uint32_t)i * la.step, st_dst + i * (NWAVES * 1024));
+        HW::dma16(la.rsrc, st_voffA + st_ka + (uint32_t)i * la.step, st_dst + i * (NWAVES * 1024));
       } else {
         const bool ok = st_live && (unsigned)(ih0[i] + cr) < (unsigned)p.cH &&
                         (unsigned)(iw0[i] + cs) < (unsigned)p.cW;
-        dma16(la.rsrc, ok ? coff[i] + st_tap : 0x80000000u, st_dst + i * (NWAVES * 1024));
+        HW::dma16(la.rsrc, ok ? coff[i] + st_tap : 0x80000000u, st_dst + i * (NWAVES * 1024));
       }
     } else if (idx < NLA + NLB) {
       const int i = idx - NLA;
-      dma16(lb.rsrc, st_voffB + st_kb + (uint32_t)i * lb.step,
+      HW::dma16(lb.rsrc, st_voffB + st_kb + (uint32_t)i * lb.step,
             st_dst + A_BYTES + i * (NWAVES * 1024));
     } else {
-      touch4(pf_ptr, pf_dst);
+      HW::touch4(pf_ptr, pf_dst);
       if (st_pf_live) pf_ptr += pf_step;      // stop at the last k-tile: never run past the operand
     }
   };
@@ -470,9 +409,9 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   constexpr int NRI = OA::NRI + OB::NRI;
   auto read_one = [&](int ki, int r, u32x4(&fa)[TM], u32x4(&fb)[TN]) {
     if (r < OA::NRI)
-      read_instr<OA>(curA, ki, r, fa);
+      read_instr<OA, HW>(curA, ki, r, fa);
     else
-      read_instr<OB>(curB, ki, r - OA::NRI, fb);
+      read_instr<OB, HW>(curB, ki, r - OA::NRI, fb);
   };
   auto load_frags = [&](int ki, u32x4(&fa)[TM], u32x4(&fb)[TN]) {
 #pragma unroll
@@ -501,7 +440,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
 #pragma unroll
     for (int m = 0; m < NMM; m++) {
       const int i = m / TM, j = m % TM;
-      acc[i][j] = mma<C::DT>(ub[i], ua[j], acc[i][j]);
+      acc[i][j] = HW::template mma<C::DT>(ub[i], ua[j], acc[i][j]);
       if (m + 1 == first || (first >= NMM && m == NMM - 1)) sync();
       if (nread && (m >= first || m == NMM - 1)) {
         const int g = m >= first ? m - first : 0;
@@ -510,7 +449,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       }
 #pragma unroll
       for (int d = d0 + m * (d1 - d0) / NMM; d < d0 + (m + 1) * (d1 - d0) / NMM; d++) issue_one(d);
-      __builtin_amdgcn_sched_barrier(0);
+      HW::sched_fence();
     }
   };
   auto no_sync = [] {};
@@ -524,8 +463,8 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     // already fetch the first fragment of k-tile ko+1.
 #pragma unroll
     for (int s = 0; s < S - 1; s++) issue(s, s);
-    wait_vm<C::WAIT>();
-    block_barrier();
+    HW::template wait_vm<C::WAIT>();
+    HW::block_barrier();
     set_read_slot(lds0);
     load_frags(0, fa[0], fb[0]);
     int rslot = 0, wslot = S - 1;
@@ -538,9 +477,9 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
           // the synchronisation sits after the first quarter of this step's matrix instructions
           constexpr int FIRST = NMM >= 8 ? NMM / 4 : 1;
           step(fa[ki & 1], fb[ki & 1], true, 0, fa[(ki + 1) & 1], fb[(ki + 1) & 1], 0, 0, FIRST, [&] {
-            wait_vm<C::WAIT>();          // consumer_wait: k-tile ko+1 has landed (this wave)
-            wait_lds();                  // consumer_release: my reads of slot ko are done
-            block_barrier();             // ... for every wave
+            HW::template wait_vm<C::WAIT>();          // consumer_wait: k-tile ko+1 has landed (this wave)
+            HW::wait_lds();                  // consumer_release: my reads of slot ko are done
+            HW::block_barrier();             // ... for every wave
             rslot = (rslot + 1 == S) ? 0 : rslot + 1;
             set_read_slot(lds0 + rslot * STAGE_BYTES);
           });
@@ -559,16 +498,16 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     int rslot = 0, wslot = (S >= 2) ? S - 1 : 0;
     for (int ko = 0; ko < nko; ko++) {
       if constexpr (S >= 2) {
-        wait_vm<C::WAIT>();              // consumer_wait for k-tile ko
-        wait_lds();
-        block_barrier();                 // also releases slot (ko-1) mod S
+        HW::template wait_vm<C::WAIT>();              // consumer_wait for k-tile ko
+        HW::wait_lds();
+        HW::block_barrier();                 // also releases slot (ko-1) mod S
         stage_begin(ko + S - 1, wslot);  // its loads are spread over the steps below
       } else {
-        wait_lds();
-        block_barrier();                 // producer_acquire: slot 0 is free
+        HW::wait_lds();
+        HW::block_barrier();                 // producer_acquire: slot 0 is free
         issue(ko, 0);
-        wait_vm<0>();                    // consumer_wait
-        block_barrier();
+        HW::template wait_vm<0>();                    // consumer_wait
+        HW::block_barrier();
       }
       wslot = (wslot + 1 == S) ? 0 : wslot + 1;
       set_read_slot(lds0 + rslot * STAGE_BYTES);
@@ -577,7 +516,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       if constexpr (C::R == 2) {
         // register-level pipeline restarted in every ko: Fig. 3(c)
         load_frags(0, fa[0], fb[0]);
-        __builtin_amdgcn_sched_barrier(0);
+        HW::sched_fence();
 #pragma unroll
         for (int ki = 0; ki < NKI; ki++)
           step(fa[ki & 1], fb[ki & 1], ki + 1 < NKI, (ki + 1) % NKI, fa[(ki + 1) & 1],
@@ -587,16 +526,16 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
 #pragma unroll
         for (int ki = 0; ki < NKI; ki++) {
           load_frags(ki, fa[0], fb[0]);
-          __builtin_amdgcn_sched_barrier(0);
+          HW::sched_fence();
           step(fa[0], fb[0], false, 0, fa[0], fb[0], ki * DL / NKI, (ki + 1) * DL / NKI, 0, no_sync);
         }
       }
       if constexpr (S >= 2) stage_end();
     }
   }
-  wait_vm<0>();   // drain the zero-fill loads of the ring's tail before the ring is reused
-  wait_lds();
-  block_barrier();   // every wave has finished reading the ring
+  HW::template wait_vm<0>();   // drain the zero-fill loads of the ring's tail before the ring is reused
+  HW::wait_lds();
+  HW::block_barrier();   // every wave has finished reading the ring
 
   // ---- epilogue: convert, transpose through LDS, store rows (Table 1, epilogue term) --------
   // A lane holds 4 consecutive n of one row m (16 such groups per 32x32 sub-tile); stored as is,
@@ -625,24 +564,24 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
           if (fused) {   // f(.) on the accumulators (paper Sec. 3.2: fused into the consumer)
             const int n = n0 + i * 32 + 8 * vq + 4 * (lane >> 5);
             f32x4 b = {0.f, 0.f, 0.f, 0.f};
-            if (p.bias != nullptr && n < p.N) b = *(const f32x4*)(p.bias + n);
+            if (p.bias != nullptr && n < p.N) b = HW::global_load_f32x4(p.bias + n);
 #pragma unroll
             for (int e = 0; e < 4; e++) {
               float t = v[e] * p.alpha + b[e];
               v[e] = (p.act == 1 && t < 0.f) ? 0.f : t;
             }
           }
-          ot4 h = {(OT)v[0], (OT)v[1], (OT)v[2], (OT)v[3]};
-          *(ALCOP_LDS ot4*)(uintptr_t)(ebase + (lane & 31) * RS +
-                                       (i * 32 + 8 * vq + 4 * (lane >> 5)) * OB) = h;
+          const ot4 h = {HW::template cvt<OT>(v[0]), HW::template cvt<OT>(v[1]),
+                         HW::template cvt<OT>(v[2]), HW::template cvt<OT>(v[3])};
+          HW::lds_write(ebase + (lane & 31) * RS + (i * 32 + 8 * vq + 4 * (lane >> 5)) * OB, h);
         }
 #pragma unroll
       for (int t = 0; t < 32 / RPI; t++) {
         const int r = t * RPI + lane / LPR, c16 = lane % LPR;
-        const u32x4 v = *(const ALCOP_LDS u32x4*)(uintptr_t)(ebase + r * RS + c16 * 16);
+        const u32x4 v = HW::lds_read16(ebase + r * RS + c16 * 16);
         const int m = m0 + j * 32 + r, n = n0 + c16 * (16 / OB);
         if (m < p.M && n < p.N)
-          __builtin_nontemporal_store(v, (u32x4*)(Cb + ((long)m * p.ldc + n) * OB));
+          HW::global_store16(Cb + ((long)m * p.ldc + n) * OB, v);
       }
     }
   };
