@@ -67,51 +67,55 @@ class Problem(ctypes.Structure):
 _lib = None
 
 
+def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
+    """Sets the argument and result types of every entry point of include/alcop.h on L."""
+    vp, i, l = ctypes.c_void_p, ctypes.c_int, ctypes.c_long
+    dp = ctypes.POINTER(ctypes.c_double)
+    ip = ctypes.POINTER(ctypes.c_int)
+    sp = ctypes.POINTER(Sched)
+    pp = ctypes.POINTER(Problem)
+    ep = ctypes.POINTER(Epilogue)
+    L.alcop_gemm.restype = i
+    L.alcop_gemm.argtypes = [vp, vp, vp, i, i, i, l, l, l, i, i, i, i, sp, vp]
+    L.alcop_bmm.restype = i
+    L.alcop_bmm.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, sp, vp]
+    L.alcop_gemm_fused.restype = i
+    L.alcop_gemm_fused.argtypes = [vp, vp, vp, i, i, i, l, l, l, i, i, i, i, ep, sp, vp]
+    L.alcop_bmm_fused.restype = i
+    L.alcop_bmm_fused.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, ep, sp, vp]
+    L.alcop_conv2d_igemm.restype = i
+    L.alcop_conv2d_igemm.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, vp]
+    L.alcop_sched_supported.restype = i
+    L.alcop_sched_supported.argtypes = [pp, sp]
+    L.alcop_sched_space.restype = i
+    L.alcop_sched_space.argtypes = [pp, sp, i]
+    L.alcop_model_predict.restype = i
+    L.alcop_model_predict.argtypes = [pp, sp, i, dp, dp]
+    L.alcop_tune.restype = i
+    L.alcop_tune.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, i, i, i, sp, dp, ip, ip,
+                             sp, dp, dp, i, vp]
+    L.alcop_time.restype = i
+    L.alcop_time.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, sp, i, i, dp, vp]
+    L.alcop_sched_auto.restype = i
+    L.alcop_sched_auto.argtypes = [pp, sp]
+    L.alcop_cache_save.restype = i
+    L.alcop_cache_save.argtypes = [ctypes.c_char_p]
+    L.alcop_cache_load.restype = i
+    L.alcop_cache_load.argtypes = [ctypes.c_char_p]
+    L.alcop_strerror.restype = ctypes.c_char_p
+    L.alcop_strerror.argtypes = [i]
+    L.alcop_version.restype = ctypes.c_char_p
+    L.alcop_version.argtypes = []
+    return L
+
+
 def lib() -> ctypes.CDLL:
     """Loads libalcop.so (built by ``python -m paper_2210_16691_amd.build``); fails loudly if absent."""
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError("libalcop.so is not built: run `python -m paper_2210_16691_amd.build`")
-        L = ctypes.CDLL(LIB_PATH)
-        vp, i, l = ctypes.c_void_p, ctypes.c_int, ctypes.c_long
-        dp = ctypes.POINTER(ctypes.c_double)
-        ip = ctypes.POINTER(ctypes.c_int)
-        sp = ctypes.POINTER(Sched)
-        pp = ctypes.POINTER(Problem)
-        L.alcop_gemm.restype = i
-        L.alcop_gemm.argtypes = [vp, vp, vp, i, i, i, l, l, l, i, i, i, i, sp, vp]
-        L.alcop_bmm.restype = i
-        L.alcop_bmm.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, sp, vp]
-        ep = ctypes.POINTER(Epilogue)
-        L.alcop_gemm_fused.restype = i
-        L.alcop_gemm_fused.argtypes = [vp, vp, vp, i, i, i, l, l, l, i, i, i, i, ep, sp, vp]
-        L.alcop_bmm_fused.restype = i
-        L.alcop_bmm_fused.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, ep, sp, vp]
-        L.alcop_conv2d_igemm.restype = i
-        L.alcop_conv2d_igemm.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, vp]
-        L.alcop_sched_supported.restype = i
-        L.alcop_sched_supported.argtypes = [pp, sp]
-        L.alcop_sched_space.restype = i
-        L.alcop_sched_space.argtypes = [pp, sp, i]
-        L.alcop_model_predict.restype = i
-        L.alcop_model_predict.argtypes = [pp, sp, i, dp, dp]
-        L.alcop_tune.restype = i
-        L.alcop_tune.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, i, i, i, sp, dp, ip, ip,
-                                 sp, dp, dp, i, vp]
-        L.alcop_time.restype = i
-        L.alcop_time.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, sp, i, i, dp, vp]
-        L.alcop_sched_auto.restype = i
-        L.alcop_sched_auto.argtypes = [pp, sp]
-        L.alcop_cache_save.restype = i
-        L.alcop_cache_save.argtypes = [ctypes.c_char_p]
-        L.alcop_cache_load.restype = i
-        L.alcop_cache_load.argtypes = [ctypes.c_char_p]
-        L.alcop_strerror.restype = ctypes.c_char_p
-        L.alcop_strerror.argtypes = [i]
-        L.alcop_version.restype = ctypes.c_char_p
-        L.alcop_version.argtypes = []
-        _lib = L
+        _lib = _declare(ctypes.CDLL(LIB_PATH))
     return _lib
 
 

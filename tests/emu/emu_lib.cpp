@@ -1,0 +1,155 @@
+// CPU build of the library for tests: the product's host code (alcop_api.cpp, alcop_model.cpp,
+// compiled unchanged) linked with a kernel table whose launchers run the kernel template on the
+// functional hardware model of emu_hw.h instead of launching it on a GPU.  Operands are host
+// memory.  Only a sample of the product's instances is built (each costs compile time); the
+// sample covers both element types, every operand layout, the convolution gather, 4- and
+// 8-wave blocks, one to four stages, single- and multi-level, fused and unfused.
+#include <hip/hip_runtime.h>
+
+#include "emu_hw.h"
+#include "alcop_registry.h"
+
+namespace alcop {
+
+template <class C>
+hipError_t launch_emulated(const Params& p, dim3 grid, hipStream_t)
+{
+  emu::run_grid<C>(p, grid.x, grid.y);
+  return hipSuccess;
+}
+
+template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int R, int F, int BL, int AM,
+          int AL = 0>
+void add(std::vector<KernelEntry>& t)
+{
+  using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL>;
+  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, C::LDS_BYTES, C::NT, C::L,
+                          &launch_emulated<C>});
+}
+
+#if EMU_PART == 0
+void emu_part_0(std::vector<KernelEntry>& t)
+{
+  // every pipelining variant of one tile
+  add<0, 128, 128, 64, 64, 64, 1, 1, 0, 0, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 2, 1, 0, 0, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 3, 1, 0, 0, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 1, 2, 0, 0, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 2, 2, 0, 0, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 4, 2, 0, 0, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 2, 2, 1, 0, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 3, 2, 1, 0, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 4, 2, 1, 0, 0>(t);
+  add<0, 128, 128, 32, 64, 64, 3, 2, 1, 0, 0>(t);
+}
+#elif EMU_PART == 1
+void emu_part_1(std::vector<KernelEntry>& t)
+{
+  add<0, 256, 256, 32, 128, 64, 2, 2, 1, 0, 0>(t);     // 8 waves
+  add<0, 256, 128, 64, 128, 64, 2, 2, 1, 0, 0>(t);
+  add<0, 64, 64, 32, 32, 32, 1, 1, 0, 0, 0>(t);
+  add<0, 64, 64, 32, 32, 32, 4, 2, 1, 0, 0>(t);
+  add<0, 64, 64, 64, 32, 32, 3, 2, 1, 0, 0>(t);
+  add<0, 256, 64, 64, 64, 64, 3, 1, 0, 0, 0>(t);
+  add<0, 64, 128, 64, 32, 64, 3, 2, 1, 0, 0>(t);
+  add<1, 128, 128, 64, 64, 64, 3, 2, 1, 0, 0>(t);      // bf16
+  add<1, 64, 64, 32, 32, 32, 2, 1, 0, 0, 0>(t);
+}
+#elif EMU_PART == 2
+void emu_part_2(std::vector<KernelEntry>& t)
+{
+  add<0, 128, 128, 64, 64, 64, 1, 1, 0, 1, 0>(t);      // B stored N x K
+  add<0, 128, 128, 64, 64, 64, 2, 2, 0, 1, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 4, 2, 1, 1, 0>(t);
+  add<0, 128, 128, 32, 64, 64, 3, 2, 1, 1, 0>(t);
+  add<0, 64, 64, 64, 32, 32, 3, 2, 1, 1, 0>(t);
+  add<1, 64, 64, 32, 32, 32, 3, 2, 1, 1, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 3, 2, 1, 0, 0, 1>(t);   // A stored K x M
+  add<0, 128, 128, 64, 64, 64, 2, 1, 0, 0, 0, 1>(t);
+  add<0, 64, 64, 32, 32, 32, 4, 2, 1, 0, 0, 1>(t);
+  add<0, 128, 128, 64, 64, 64, 3, 2, 1, 1, 0, 1>(t);   // A stored K x M, B stored N x K
+  add<1, 64, 64, 32, 32, 32, 2, 2, 1, 1, 0, 1>(t);
+}
+#elif EMU_PART == 3
+void emu_part_3(std::vector<KernelEntry>& t)
+{
+  add<0, 128, 64, 64, 64, 32, 1, 1, 0, 0, 1>(t);       // convolution gather
+  add<0, 128, 64, 64, 64, 32, 2, 2, 0, 0, 1>(t);
+  add<0, 128, 64, 64, 64, 32, 3, 2, 1, 0, 1>(t);
+  add<0, 128, 64, 32, 64, 32, 4, 2, 1, 0, 1>(t);
+  add<0, 64, 64, 32, 32, 32, 3, 2, 1, 0, 1>(t);
+  add<0, 256, 64, 64, 64, 64, 1, 2, 0, 0, 1>(t);
+  add<0, 64, 128, 64, 32, 64, 3, 2, 1, 0, 1>(t);
+  add<1, 128, 64, 64, 64, 32, 3, 2, 1, 0, 1>(t);
+}
+#else
+// the part that is compiled once: the product's sub-table hooks and the test controls
+void emu_part_0(std::vector<KernelEntry>&);
+void emu_part_1(std::vector<KernelEntry>&);
+void emu_part_2(std::vector<KernelEntry>&);
+void emu_part_3(std::vector<KernelEntry>&);
+void register_f16_kn_mid(std::vector<KernelEntry>& t)
+{
+  emu_part_0(t);
+  emu_part_1(t);
+  emu_part_2(t);
+  emu_part_3(t);
+}
+void register_f16_kn_big(std::vector<KernelEntry>&) {}
+void register_f16_kn_small(std::vector<KernelEntry>&) {}
+void register_bf16_kn(std::vector<KernelEntry>&) {}
+void register_nk(std::vector<KernelEntry>&) {}
+void register_conv(std::vector<KernelEntry>&) {}
+void register_ta(std::vector<KernelEntry>&) {}
+#endif
+
+}  // namespace alcop
+
+#if EMU_PART < 0
+extern "C" {
+
+// Forget all registered buffers and logged errors; choose the timing policy of the next runs:
+// late_landing != 0: direct-to-LDS data arrives only when a wait forces it (else at issue);
+// last_wave_first != 0: the scheduler lets the last wave of a block run ahead (else the first).
+void emu_reset(int late_landing, int last_wave_first)
+{
+  emu::Config& c = emu::cfg();
+  c.buffers.clear();
+  c.errors.clear();
+  c.n_errors = 0;
+  c.late_landing = late_landing != 0;
+  c.last_wave_first = last_wave_first != 0;
+}
+
+// Declares [ptr, ptr + bytes) as memory the kernel may read (and write, if writable != 0).
+void emu_register_buffer(const void* ptr, size_t bytes, int writable)
+{
+  emu::cfg().buffers.push_back(emu::Buffer{(const char*)ptr, bytes, writable != 0});
+}
+
+// Plants a mistake in the model's synchronisation, to show that the checks notice it:
+// 1 = every vmcnt wait lets two more loads stay in flight than asked (one more would be
+// harmless: the last load of every stage is the L2 touch, which nobody reads); 2 = the block
+// barrier does not wait; 3 = vmcnt waits are ignored (loads land only at the final wait).
+void emu_set_mutation(int m) { emu::cfg().mutation = m; }
+
+long emu_error_count(void) { return emu::cfg().n_errors; }
+
+// Copies the logged error messages (newline separated, at most cap - 1 characters) into out.
+void emu_error_text(char* out, size_t cap)
+{
+  std::string s;
+  for (const std::string& e : emu::cfg().errors) s += e + "\n";
+  if (cap == 0) return;
+  const size_t n = s.size() < cap - 1 ? s.size() : cap - 1;
+  memcpy(out, s.data(), n);
+  out[n] = 0;
+}
+
+// the model's own number conversions, exported so that a test can pin them
+uint16_t emu_f32_to_f16(float v) { return emu::float_to_f16(v); }
+uint16_t emu_f32_to_bf16(float v) { return emu::float_to_bf16(v); }
+float emu_f16_to_f32(uint16_t h) { return emu::f16_to_float(h); }
+
+}  // extern "C"
+#endif

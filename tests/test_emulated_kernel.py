@@ -1,0 +1,218 @@
+"""The kernel template itself, run on the CPU.
+
+tests/emu builds the product's host code and kernel header against a functional model of the
+gfx950 operations the loop uses (one fibre per lane).  These tests compare its results with the
+oracle bit for bit on integer data, under timing policies chosen to expose a missing wait or
+barrier, and require that no access left the operands or the block's LDS.  They also plant
+synchronisation mistakes in the model to show that the checks would notice one.  No GPU is
+involved: what this proves is the kernel's indexing, bounds and synchronisation logic, not its
+speed."""
+import numpy as np
+import pytest
+import torch
+
+import emu_util as emu
+import oracle
+import paper_2210_16691_amd as al
+import workloads as wl
+
+TDT = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}
+ODT = {"f16": oracle.F16, "bf16": oracle.BF16}
+ADT = {"f16": al.F16, "bf16": al.BF16, "f32": al.F32}
+
+
+def _exact(C, ref):
+    return np.array_equal(C.double().numpy(), ref)
+
+
+# ---- the model's own arithmetic, pinned against numpy / torch -------------------------------
+def test_model_number_conversions():
+    L = emu.lib()
+    h = np.arange(65536, dtype=np.uint16)
+    want = h.view(np.float16).astype(np.float32)
+    got = np.array([L.emu_f16_to_f32(int(v)) for v in h], dtype=np.float32)
+    assert np.array_equal(got.view(np.uint32)[~np.isnan(want)], want.view(np.uint32)[~np.isnan(want)])
+    assert np.isnan(got[np.isnan(want)]).all()
+    # fp32 -> fp16, round to nearest even: every fp16 value, every midpoint between neighbours,
+    # values just off the midpoints, the overflow threshold, and random numbers
+    fin = want[np.isfinite(want)]
+    fin = np.unique(fin)
+    mids = ((fin[:-1].astype(np.float64) + fin[1:].astype(np.float64)) / 2).astype(np.float32)
+    rng = np.random.default_rng(5)
+    rnd = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 12, 20000))).astype(np.float32)
+    xs = np.concatenate([fin, mids, np.nextafter(mids, np.float32(np.inf)), np.nextafter(mids, np.float32(-np.inf)),
+                         np.float32([65504, 65519.9, 65520, 65536, 1e9, -65520, 2.0 ** -25, 2.0 ** -24, 0.0, -0.0]),
+                         rnd])
+    with np.errstate(over="ignore"):
+        want16 = xs.astype(np.float16).view(np.uint16)
+    got16 = np.array([L.emu_f32_to_f16(float(v)) for v in xs], dtype=np.uint16)
+    assert np.array_equal(got16, want16)
+    t = torch.from_numpy(rnd)
+    want_bf = t.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got_bf = np.array([L.emu_f32_to_bf16(float(v)) for v in rnd], dtype=np.uint16)
+    assert np.array_equal(got_bf, want_bf)
+
+
+# ---- GEMM: every emulated schedule, every layout, ragged edges ------------------------------
+def _gemm_case(dt, transA, transB, s, M, N, K, policy, out="f16", seed=0, mutation=0):
+    A = wl.small_ints((K, M) if transA else (M, K), dt, 900 + seed)
+    B = wl.small_ints((N, K) if transB else (K, N), dt, 901 + seed)
+    C = torch.full((M, N), float("nan"), dtype=TDT[out])
+    errs = emu.call(al.alcop_gemm, A, B, C, s, transB=bool(transB), transA=bool(transA),
+                    reads=[A, B], writes=[C], policy=policy, mutation=mutation)
+    ref = oracle.gemm(wl.bits(A.t().contiguous() if transA else A),
+                      wl.bits(B.t().contiguous() if transB else B), ODT[dt])
+    return errs, _exact(C, ref)
+
+
+@pytest.mark.parametrize("dt,transA,transB", [("f16", 0, 0), ("f16", 0, 1), ("f16", 1, 0), ("f16", 1, 1),
+                                               ("bf16", 0, 0), ("bf16", 0, 1), ("bf16", 1, 1)])
+def test_gemm_exact_and_in_bounds_every_emulated_schedule(dt, transA, transB):
+    prob = al.problem(al.OP_GEMM, 512, 512, 512, ADT[dt], ADT[dt], transB=bool(transB), transA=bool(transA))
+    scheds = emu.space(prob)
+    assert scheds
+    for n, s in enumerate(scheds):
+        # two row tiles (the second ragged), a ragged column tile, three k-tiles and a partial one
+        M = s.bm + 40
+        N = s.bn - 24 if s.bn > 64 else 64 + 8
+        K = 3 * s.bk + 8
+        for policy in (emu.POLICIES[n % 4], emu.POLICIES[(n + 1) % 4]):
+            errs, ok = _gemm_case(dt, transA, transB, s, M, N, K, policy, seed=n)
+            assert not errs, (repr(s), policy, errs[:4])
+            assert ok, (repr(s), policy)
+
+
+def test_gemm_all_timing_policies_many_k_tiles_and_fp32_output():
+    # more k-tiles than ring slots, so that every slot is refilled several times
+    for s in (al.sched(128, 128, 64, 64, 64, 4, 2, 1), al.sched(128, 128, 64, 64, 64, 3, 1, 0),
+              al.sched(64, 64, 32, 32, 32, 4, 2, 1)):
+        for policy in emu.POLICIES:
+            errs, ok = _gemm_case("f16", 0, 0, s, 2 * s.bm, s.bn, 11 * s.bk, policy, out="f32")
+            assert not errs and ok, (repr(s), policy, errs[:4])
+
+
+def test_gemm_tiny_and_single_k_tile():
+    s = al.sched(64, 64, 32, 32, 32, 4, 2, 1)
+    for (M, N, K) in ((1, 8, 8), (8, 8, 32), (64, 64, 16), (65, 72, 40)):
+        errs, ok = _gemm_case("f16", 0, 0, s, M, N, K, (1, 0))
+        assert not errs and ok, (M, N, K, errs[:4])
+
+
+def test_l2_touches_stay_inside_the_operands():
+    # the third (HBM -> L2) level reads ahead with plain global loads: several tiles in both
+    # directions, ragged edges, more k-tiles than the look-ahead, both layouts of B
+    for transB in (0, 1):
+        s = al.sched(128, 128, 64, 64, 64, 4, 2, 1, 1, 4)
+        errs, ok = _gemm_case("f16", 0, transB, s, 3 * 128 - 56, 2 * 128 + 8, 7 * 64, (1, 0))
+        assert not errs and ok, (transB, errs[:4])
+    s = al.sched(64, 64, 32, 32, 32, 4, 2, 1, 1, 8)
+    errs, ok = _gemm_case("f16", 0, 0, s, 5 * 64, 3 * 64, 3 * 32, (0, 1))     # look-ahead > k-tiles
+    assert not errs and ok, errs[:4]
+    errs, ok = _gemm_case("f16", 0, 0, s, 5 * 64 - 8, 3 * 64 - 8, 5 * 32 + 8, (1, 1))   # partial k-tile: level off
+    assert not errs and ok, errs[:4]
+
+
+def test_leading_dimensions_and_output_guard():
+    # operands and output are views into larger arrays; only the views are registered, so a read
+    # or store one element outside them is an error
+    s = al.sched(128, 128, 32, 64, 64, 3, 2, 1)
+    M, N, K = 136, 200, 72
+    Abig = wl.small_ints((M, K + 24), "f16", 1)
+    Bbig = wl.small_ints((K, N + 16), "f16", 2)
+    Cbig = torch.full((M, N + 8), float("nan"), dtype=torch.float16)
+    A, B, C = Abig[:, :K], Bbig[:, :N], Cbig[:, :N]
+    errs = emu.call(al.alcop_gemm, A, B, C, s, reads=[A, B], writes=[C], policy=(1, 1))
+    assert not errs, errs[:4]
+    ref = oracle.gemm(wl.bits(A.contiguous()), wl.bits(B.contiguous()), oracle.F16)
+    assert _exact(C, ref)
+    assert torch.isnan(Cbig[:, N:]).all()
+
+
+# ---- fused epilogue, BMM, convolution ---------------------------------------------------------
+def test_fused_epilogue_and_bmm():
+    s = al.sched(128, 128, 64, 64, 64, 3, 2, 1)
+    M, N, K = 136, 72, 136
+    A = wl.small_ints((M, K), "f16", 11)
+    B = wl.small_ints((K, N), "f16", 12)
+    bias = torch.arange(N, dtype=torch.float32) - 30
+    C = torch.full((M, N), float("nan"), dtype=torch.float32)
+    errs = emu.call(al.alcop_gemm_fused, A, B, C, 0.5, bias, 1, s, reads=[A, B, bias], writes=[C])
+    assert not errs, errs[:4]
+    ref = oracle.epilogue(oracle.gemm(wl.bits(A), wl.bits(B), oracle.F16), 0.5, bias.double().numpy(), 1)
+    assert _exact(C, ref)
+    # batched, B stored N x K, batch strides of views
+    b = 3
+    Q = wl.small_ints((b, 72, 64), "f16", 13)
+    Kt = wl.small_ints((b + 1, 136, 64), "f16", 14)[1:]
+    P = torch.full((b, 72, 136), float("nan"), dtype=torch.float16)
+    for policy in ((1, 0), (0, 1)):
+        errs = emu.call(al.alcop_bmm, Q, Kt, P, al.sched(64, 64, 64, 32, 32, 3, 2, 1), transB=True,
+                        reads=[Q, Kt], writes=[P], policy=policy)
+        assert not errs, errs[:4]
+        ref = oracle.bmm(wl.bits(Q), wl.bits(Kt.contiguous().transpose(1, 2).contiguous()), oracle.F16)
+        assert _exact(P, ref)
+
+
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=9, W=7, C=64, K=64, R=3, S=3, stride=(1, 1), pad=(1, 1)),
+    dict(N=1, H=12, W=10, C=32, K=72, R=3, S=3, stride=(2, 2), pad=(1, 1)),
+    dict(N=3, H=6, W=6, C=64, K=64, R=1, S=1, stride=(1, 1), pad=(0, 0)),
+    dict(N=1, H=8, W=8, C=64, K=128, R=5, S=3, stride=(1, 2), pad=(2, 0)),
+])
+def test_conv_gather_exact_and_in_bounds(geom):
+    g = geom
+    x = wl.small_ints((g["N"], g["H"], g["W"], g["C"]), "f16", 21)
+    w = wl.small_ints((g["R"], g["S"], g["C"], g["K"]), "f16", 22)
+    P = (g["H"] + 2 * g["pad"][0] - g["R"]) // g["stride"][0] + 1
+    Q = (g["W"] + 2 * g["pad"][1] - g["S"]) // g["stride"][1] + 1
+    ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, g["stride"], g["pad"])
+    prob = al.problem(al.OP_CONV2D, g["N"] * P * Q, g["K"], g["R"] * g["S"] * g["C"], al.F16, al.F16,
+                      conv_C=g["C"])
+    scheds = emu.space(prob)
+    assert len(scheds) >= 2
+    for n, s in enumerate(scheds):
+        y = torch.full((g["N"], P, Q, g["K"]), float("nan"), dtype=torch.float16)
+        errs = emu.call(al.alcop_conv2d_igemm, x, w, y, g["stride"], g["pad"], s,
+                        reads=[x, w], writes=[y], policy=emu.POLICIES[n % 4])
+        assert not errs, (repr(s), errs[:4])
+        assert _exact(y, ref), repr(s)
+
+
+# ---- the checks notice planted mistakes ------------------------------------------------------------
+def test_planted_synchronisation_mistakes_are_noticed():
+    s4 = al.sched(128, 128, 64, 64, 64, 4, 2, 1)
+    s3u = al.sched(128, 128, 64, 64, 64, 3, 1, 0)
+    M, N, K = 128, 128, 8 * 64
+    # sound kernel: clean under every policy (the control)
+    for s in (s4, s3u):
+        for policy in emu.POLICIES:
+            errs, ok = _gemm_case("f16", 0, 0, s, M, N, K, policy)
+            assert not errs and ok
+    # a wait that lets too many loads stay in flight: a late-landing load is read too early
+    for s in (s4, s3u):
+        errs, ok = _gemm_case("f16", 0, 0, s, M, N, K, (1, 0), mutation=1)
+        assert not ok, repr(s)
+    # no block barrier: a wave that runs ahead reads tiles the others have not delivered, or
+    # refills a slot the others still read
+    for policy in ((0, 0), (0, 1), (1, 0)):
+        errs, ok = _gemm_case("f16", 0, 0, s4, M, N, K, policy, mutation=2)
+        assert not ok, policy
+    # waits ignored altogether
+    errs, ok = _gemm_case("f16", 0, 0, s4, M, N, K, (1, 0), mutation=3)
+    assert not ok
+
+
+def test_out_of_bounds_accesses_are_noticed():
+    # the same correct call, but the test "forgets" the last row of A / the last row of C when it
+    # declares the operands: the model must report the accesses that leave the declared ranges
+    s = al.sched(128, 128, 64, 64, 64, 2, 2, 1)
+    A = wl.small_ints((128, 128), "f16", 31)
+    B = wl.small_ints((128, 128), "f16", 32)
+    C = torch.zeros(128, 128, dtype=torch.float16)
+    assert not emu.call(al.alcop_gemm, A, B, C, s, reads=[A, B], writes=[C])
+    errs = emu.call(al.alcop_gemm, A, B, C, s, reads=[A[:127], B], writes=[C])
+    assert errs and "descriptor admits" in " ".join(errs)
+    errs = emu.call(al.alcop_gemm, A, B, C, s, reads=[A, B], writes=[C[:127]])
+    assert errs and "global store outside" in " ".join(errs)
+    errs = emu.call(al.alcop_gemm, A, B, C, s, reads=[A, B, C], writes=[])
+    assert errs      # C declared read-only
