@@ -39,6 +39,8 @@
 #ifndef ALCOP_H
 #define ALCOP_H
 
+#include <stddef.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -149,6 +151,55 @@ int alcop_conv2d_igemm(const void* x, const void* w, void* y, int N, int H, int 
                        int K, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
                        alcop_dtype in, alcop_dtype out, const alcop_sched* sched /* host */,
                        void* hip_stream);
+
+/*
+ * Split-K: the reduction axis is cut into `split` slices of whole k-tiles, every slice is a block
+ * of its own (grid.z), and a second kernel adds the slices' fp32 partial tiles in ascending
+ * order, applies f(.) and converts to the output type.  For outputs with few tiles and a long
+ * reduction axis, the case the paper singles out as gaining most from pipelining (Sec. 6.2, the
+ * 1024 x 64 output with K = 2048) and where tiling alone leaves most compute units idle
+ * (Sec. 1, Fig. 1: tile size against inter-tile parallelism).  The result is deterministic but,
+ * unlike every unsplit schedule of a tile, not bit-identical to the unsplit one.
+ *   workspace: DEVICE memory, 16-byte aligned, at least alcop_splitk_workspace_bytes(batch, M, N,
+ *     split) bytes (4 * split * batch * M * N); owned by the caller, overwritten by the call,
+ *     holds nothing afterwards.  Calls that share a workspace must be ordered on one stream.
+ *   split: 1..64 slices (fewer are used if K has fewer k-tiles; 1 runs the unsplit kernel's
+ *     loop through the workspace), or 0 = the model's choice.
+ *   sched: one of the split-K variants built into the library (alcop_splitk_auto returns the
+ *     model's pick), or NULL / zero = that pick.  l2_prefetch must be 0.
+ *   batch = 1 with strides 0 is a plain GEMM.  A stored K x M (transA) is not built: UNSUPPORTED.
+ * Errors as for alcop_gemm; ALCOP_ERR_SIZE also if the workspace is too small.
+ */
+size_t alcop_splitk_workspace_bytes(int batch, int M, int N, int split);
+
+int alcop_gemm_splitk(const void* A, const void* B, void* C, int batch, int M, int N, int K,
+                      long lda, long ldb, long ldc, long strideA, long strideB, long strideC,
+                      int transA, int transB, alcop_dtype in, alcop_dtype out,
+                      const alcop_epilogue* ep /* host, may be NULL */,
+                      const alcop_sched* sched /* host */, int split,
+                      void* workspace /* device */, size_t workspace_bytes, void* hip_stream);
+
+/* GEMM view of the convolution: M = N*P*Q, N = K, reduction R*S*C; workspace as above. */
+int alcop_conv2d_igemm_splitk(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                              int K, int R, int S, int stride_h, int stride_w, int pad_h,
+                              int pad_w, alcop_dtype in, alcop_dtype out,
+                              const alcop_sched* sched /* host */, int split,
+                              void* workspace /* device */, size_t workspace_bytes,
+                              void* hip_stream);
+
+/* The split-K variants built into the library for the problem's dtype / layout / operator
+ * (same conventions as alcop_sched_space). */
+int alcop_splitk_space(const alcop_problem* prob /* host */, alcop_sched* out /* host */, int cap);
+
+/*
+ * The (schedule, split) the static model ranks first among the split-K variants: the model of
+ * Sec. 5 applied to the sliced problem (batch x split blocks, reduction axis of one slice, fp32
+ * output) plus the reduction pass.  split = 0 searches the split as well; predicted_us (host,
+ * may be NULL) receives the predicted time.  Host only, launches nothing.
+ */
+int alcop_splitk_auto(const alcop_problem* prob /* host */, int split,
+                      alcop_sched* sched_out /* host */, int* split_out /* host */,
+                      double* predicted_us /* host */);
 
 /*
  * Feasibility of a schedule for a problem, without launching (the checks the paper's

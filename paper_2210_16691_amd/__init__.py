@@ -25,6 +25,7 @@ EXPORTS = [
     "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
+    "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space",
 ]
 
 
@@ -102,6 +103,18 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
     L.alcop_cache_save.argtypes = [ctypes.c_char_p]
     L.alcop_cache_load.restype = i
     L.alcop_cache_load.argtypes = [ctypes.c_char_p]
+    sz = ctypes.c_size_t
+    L.alcop_splitk_workspace_bytes.restype = sz
+    L.alcop_splitk_workspace_bytes.argtypes = [i, i, i, i]
+    L.alcop_gemm_splitk.restype = i
+    L.alcop_gemm_splitk.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, ep, sp, i,
+                                    vp, sz, vp]
+    L.alcop_conv2d_igemm_splitk.restype = i
+    L.alcop_conv2d_igemm_splitk.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, i, vp, sz, vp]
+    L.alcop_splitk_space.restype = i
+    L.alcop_splitk_space.argtypes = [pp, sp, i]
+    L.alcop_splitk_auto.restype = i
+    L.alcop_splitk_auto.argtypes = [pp, i, sp, ip, dp]
     L.alcop_strerror.restype = ctypes.c_char_p
     L.alcop_strerror.argtypes = [i]
     L.alcop_version.restype = ctypes.c_char_p
@@ -215,6 +228,64 @@ def alcop_conv2d_igemm(x, w, y, stride=(1, 1), pad=(0, 0), sched=None, stream=No
                                   _dtype_code(x), _dtype_code(y), _sp(sched), _stream(stream))
     _check(rc, "alcop_conv2d_igemm")
     return y
+
+
+def alcop_splitk_workspace_bytes(batch: int, M: int, N: int, split: int) -> int:
+    return int(lib().alcop_splitk_workspace_bytes(batch, M, N, split))
+
+
+def alcop_gemm_splitk(A, B, C, split, workspace, sched=None, alpha=1.0, bias=None, act=0,
+                      transB=False, stream=None):
+    """C = act(alpha * A.B + bias) with the reduction axis cut into `split` slices (0 = the model's
+    choice).  A, B, C are 2-D (GEMM) or 3-D (batched) tensors; `workspace` is a tensor of at least
+    alcop_splitk_workspace_bytes(batch, M, N, split) bytes that the call overwrites."""
+    if A.dim() == 2:
+        b, (M, K), sA, sB, sC = 1, A.shape, 0, 0, 0
+        N = B.shape[0] if transB else B.shape[1]
+        lda, ldb, ldc = A.stride(0), B.stride(0), C.stride(0)
+    else:
+        b, M, K = A.shape
+        N = B.shape[1] if transB else B.shape[2]
+        lda, ldb, ldc = A.stride(1), B.stride(1), C.stride(1)
+        sA, sB, sC = A.stride(0), B.stride(0), C.stride(0)
+    e = _epilogue(alpha, bias, act)
+    rc = lib().alcop_gemm_splitk(_ptr(A), _ptr(B), _ptr(C), b, M, N, K, lda, ldb, ldc, sA, sB, sC,
+                                 0, int(transB), _dtype_code(A), _dtype_code(C), ctypes.byref(e),
+                                 _sp(sched), int(split), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "alcop_gemm_splitk")
+    return C
+
+
+def alcop_conv2d_igemm_splitk(x, w, y, split, workspace, stride=(1, 1), pad=(0, 0), sched=None,
+                              stream=None):
+    """alcop_conv2d_igemm with the reduction axis R*S*C cut into `split` slices."""
+    N, H, W, Cc = x.shape
+    R, S, _, K = w.shape
+    rc = lib().alcop_conv2d_igemm_splitk(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cc, K, R, S,
+                                         stride[0], stride[1], pad[0], pad[1],
+                                         _dtype_code(x), _dtype_code(y), _sp(sched), int(split),
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                         _stream(stream))
+    _check(rc, "alcop_conv2d_igemm_splitk")
+    return y
+
+
+def alcop_splitk_space(prob: "Problem"):
+    n = lib().alcop_splitk_space(ctypes.byref(prob), None, 0)
+    if n < 0:
+        raise AlcopError(n, "alcop_splitk_space")
+    arr = (Sched * max(n, 1))()
+    lib().alcop_splitk_space(ctypes.byref(prob), arr, n)
+    return [Sched(*arr[i].key()) for i in range(n)]
+
+
+def alcop_splitk_auto(prob: "Problem", split: int = 0):
+    """Returns (schedule, split, predicted_us): the model's pick among the split-K variants."""
+    s, n, us = Sched(), ctypes.c_int(), ctypes.c_double()
+    _check(lib().alcop_splitk_auto(ctypes.byref(prob), int(split), ctypes.byref(s), ctypes.byref(n),
+                                   ctypes.byref(us)), "alcop_splitk_auto")
+    return s, n.value, us.value
 
 
 def problem(op, M, N, K, in_dtype, out_dtype, batch=1, transB=False, conv_C=0, transA=False) -> Problem:

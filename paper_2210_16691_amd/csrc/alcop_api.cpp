@@ -28,6 +28,8 @@ const std::vector<KernelEntry>& registry()
     register_nk(t);
     register_conv(t);
     register_ta(t);
+    register_splitk_gemm(t);
+    register_splitk_conv(t);
     return t;
   }();
   return table;
@@ -69,11 +71,11 @@ alcop_problem problem_of(const Call& c)
   return p;
 }
 
-const KernelEntry* find_entry(const alcop_problem& p, const alcop_sched& s)
+const KernelEntry* find_entry(const alcop_problem& p, const alcop_sched& s, int sk)
 {
   const int am = p.op == ALCOP_OP_CONV2D ? 1 : 0;
   for (const KernelEntry& e : registry())
-    if (e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.al == (p.transA ? 1 : 0) &&
+    if (e.sk == sk && e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.al == (p.transA ? 1 : 0) &&
         e.am == am && e.bm == s.bm &&
         e.bn == s.bn && e.bk == s.bk && e.wm == s.wm && e.wn == s.wn && e.stages == s.stages &&
         e.reg_stages == s.reg_stages && e.fuse == (s.fuse_inner ? 1 : 0))
@@ -95,8 +97,9 @@ int check_problem(const alcop_problem& p)
   return ALCOP_OK;
 }
 
-// Feasibility of a schedule for a problem (no pointers involved).
-int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry** out)
+// Feasibility of a schedule for a problem (no pointers involved); sk = 1 looks among the
+// split-K variants.
+int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry** out, int sk = 0)
 {
   int rc = check_problem(p);
   if (rc) return rc;
@@ -105,7 +108,7 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
   if (s.raster != 0 && s.raster != 1) return ALCOP_ERR_SCHED;
   if (s.l2_prefetch < 0 || s.l2_prefetch > 64 || (s.l2_prefetch > 0 && s.raster != 1))
     return ALCOP_ERR_SCHED;
-  const KernelEntry* e = find_entry(p, s);
+  const KernelEntry* e = find_entry(p, s, sk);
   if (!e) return ALCOP_ERR_SCHED;
   if (e->lds_bytes > 160 * 1024) return ALCOP_ERR_SCHED;
   if (e->stages >= 2 && (e->stages - 2) * e->loads_per_stage > 63) return ALCOP_ERR_SCHED;
@@ -122,16 +125,17 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
 // latencies of matrix work at any tile size).
 int default_l2_prefetch(int bk) { return 256 / bk; }
 
-std::vector<alcop_sched> space_of(const alcop_problem& p)
+std::vector<alcop_sched> space_of(const alcop_problem& p, int sk = 0)
 {
   std::vector<alcop_sched> v;
   const int am = p.op == ALCOP_OP_CONV2D ? 1 : 0;
   for (const KernelEntry& e : registry())
-    if (e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.al == (p.transA ? 1 : 0) && e.am == am)
+    if (e.sk == sk && e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) &&
+        e.al == (p.transA ? 1 : 0) && e.am == am)
     {
       v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1, 0});
       // the fused multi-level kernels are also offered with the third (HBM -> L2) level on
-      if (e.fuse && e.am == 0)
+      if (e.fuse && e.am == 0 && sk == 0)
         v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1,
                                 default_l2_prefetch(e.bk)});
     }
@@ -221,7 +225,27 @@ int span_check(const Call& c, const alcop_sched& s)
   return ALCOP_OK;
 }
 
-int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipStream_t st)
+// Slicing of the reduction axis for the split-K kernels: nz slices of len elements each (len is
+// a multiple of the k-tile; the last slice may be shorter), fp32 partial tiles in ws.
+struct Split {
+  int nz = 1;
+  int len = 0;
+  void* ws = nullptr;
+};
+
+Split make_split(int K, int bk, int requested, void* ws)
+{
+  Split sp;
+  const int nkt = (K + bk - 1) / bk;                            // k-tiles in all
+  const int per = (nkt + requested - 1) / requested;            // k-tiles per slice
+  sp.len = per * bk;
+  sp.nz = (nkt + per - 1) / per;                                // no slice is empty
+  sp.ws = ws;
+  return sp;
+}
+
+int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipStream_t st,
+                const Split* split = nullptr)
 {
   Params p;
   std::memset(&p, 0, sizeof(p));
@@ -267,8 +291,45 @@ int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipSt
     p.a_span = (unsigned)(2L * c.cN * c.cH * c.cW * c.cC);
   }
   dim3 grid((unsigned)(p.ntm * p.ntn), (unsigned)c.batch, 1);
+  if (split) {
+    // the slices write plain fp32 tiles into the workspace; f(.) and the conversion to the
+    // output type happen in the reduction step
+    const long mn = (long)c.M * c.N;
+    p.C = split->ws;
+    p.ldc = c.N;
+    p.strideC = mn;
+    p.zstrideC = mn * c.batch;
+    p.out_dtype = (int)ALCOP_F32;
+    p.alpha = 1.0f;
+    p.bias = nullptr;
+    p.act = 0;
+    p.pf_dist = 0;
+    p.ksplit_len = split->len;
+    grid.z = (unsigned)split->nz;
+  }
   hipError_t err = e->launch(p, grid, st);
-  return err == hipSuccess ? ALCOP_OK : ALCOP_ERR_LAUNCH;
+  if (err != hipSuccess) return ALCOP_ERR_LAUNCH;
+  if (split) {
+    ReduceParams r;
+    std::memset(&r, 0, sizeof(r));
+    r.ws = (const float*)split->ws;
+    r.C = c.C;
+    r.M = c.M;
+    r.N = c.N;
+    r.ldc = (int)c.ldc;
+    r.strideC = c.strideC;
+    r.split = split->nz;
+    r.zstride = (long)c.M * c.N * c.batch;
+    r.out_dtype = (int)c.out;
+    r.alpha = c.alpha;
+    r.bias = (const float*)c.bias;
+    r.act = c.act;
+    const long threads = (long)c.M * (c.N / 8);
+    dim3 rgrid((unsigned)((threads + REDUCE_THREADS - 1) / REDUCE_THREADS), (unsigned)c.batch, 1);
+    err = launch_splitk_reduce(r, rgrid, st);
+    if (err != hipSuccess) return ALCOP_ERR_LAUNCH;
+  }
+  return ALCOP_OK;
 }
 
 int run(const Call& c, const alcop_sched* sched, void* stream)
@@ -289,6 +350,87 @@ int run(const Call& c, const alcop_sched* sched, void* stream)
   rc = span_check(c, s);
   if (rc) return rc;
   return launch_call(c, s, e, (hipStream_t)stream);
+}
+
+// Predicted time of a split-K schedule: the main loop as a problem with batch x nz blocks over
+// a reduction axis of one slice and fp32 output, plus the reduction pass (one launch latency and
+// its traffic at DRAM rate).  Same model, applied to the transformed problem.
+double predict_splitk(const alcop_problem& p, const alcop_sched& s, int requested, const Device& dev)
+{
+  const Split sp = make_split(p.K, s.bk, requested, nullptr);
+  alcop_problem q = p;
+  q.batch = p.batch * sp.nz;
+  q.K = sp.len;
+  q.out = ALCOP_F32;
+  double t = predict(q, s, 0, dev, nullptr);
+  if (sp.nz > 1) {
+    const double out_b = p.out == ALCOP_F32 ? 4.0 : 2.0;
+    const double bytes = (double)p.batch * p.M * p.N * (4.0 * sp.nz + out_b);
+    t += dev.lat_dram + dev.lat_dram_write + bytes / dev.bw_dram;
+  }
+  return t;
+}
+
+const int kSplitChoices[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
+
+// Model's pick of (schedule, split) among the split-K variants; split = 0 searches it too.
+int auto_splitk(const alcop_problem& p, int split, alcop_sched* out, int* split_out)
+{
+  const Device dev;
+  double best = 0;
+  bool have = false;
+  for (const alcop_sched& s : space_of(p, 1)) {
+    if (check_sched(p, s, nullptr, 1) != ALCOP_OK) continue;
+    auto consider = [&](int n) {
+      const double t = predict_splitk(p, s, n, dev);
+      if (!have || t < best) {
+        best = t;
+        *out = s;
+        *split_out = n;
+        have = true;
+      }
+    };
+    if (split > 0) {
+      consider(split);
+      continue;
+    }
+    for (int cand : kSplitChoices)
+      if (cand <= (p.K + s.bk - 1) / s.bk) consider(cand);
+  }
+  return have ? ALCOP_OK : ALCOP_ERR_SCHED;
+}
+
+int run_splitk(const Call& c, const alcop_sched* sched, int split, void* ws, size_t ws_bytes,
+               void* stream)
+{
+  int rc = check_call(c);
+  if (rc) return rc;
+  if (split < 0 || split > 64) return ALCOP_ERR_SHAPE;
+  if (!ws) return ALCOP_ERR_NULL;
+  if (!aligned16(ws)) return ALCOP_ERR_ALIGN;
+  const alcop_problem prob = problem_of(c);
+  alcop_sched s;
+  if (!sched || sched->bm == 0) {
+    rc = auto_splitk(prob, split, &s, &split);
+    if (rc) return rc;
+  } else {
+    s = *sched;
+    if (split == 0) {
+      alcop_sched ignored;
+      rc = auto_splitk(prob, 0, &ignored, &split);
+      if (rc) return rc;
+    }
+  }
+  const KernelEntry* e = nullptr;
+  rc = check_sched(prob, s, &e, 1);
+  if (rc) return rc;
+  if (s.l2_prefetch != 0) return ALCOP_ERR_SCHED;
+  rc = span_check(c, s);
+  if (rc) return rc;
+  const Split sp = make_split(c.K, s.bk, split, ws);
+  const double need = 4.0 * sp.nz * c.batch * c.M * c.N;
+  if (need > (double)ws_bytes) return ALCOP_ERR_SIZE;
+  return launch_call(c, s, e, (hipStream_t)stream, &sp);
 }
 
 Call gemm_call(alcop_op op, const void* A, const void* B, void* C, int batch, int M, int N, int K,
@@ -466,6 +608,65 @@ int alcop_conv2d_igemm(const void* x, const void* w, void* y, int N, int H, int 
   int rc = conv_call(&c, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, in, out);
   if (rc) return rc;
   return run(c, sched, hip_stream);
+}
+
+size_t alcop_splitk_workspace_bytes(int batch, int M, int N, int split)
+{
+  if (batch <= 0 || M <= 0 || N <= 0 || split <= 0) return 0;
+  return (size_t)4 * (size_t)split * (size_t)batch * (size_t)M * (size_t)N;
+}
+
+int alcop_gemm_splitk(const void* A, const void* B, void* C, int batch, int M, int N, int K,
+                      long lda, long ldb, long ldc, long strideA, long strideB, long strideC,
+                      int transA, int transB, alcop_dtype in, alcop_dtype out,
+                      const alcop_epilogue* ep, const alcop_sched* sched, int split,
+                      void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+  if (transA) return ALCOP_ERR_UNSUPPORTED;
+  Call c = gemm_call(batch > 1 ? ALCOP_OP_BMM : ALCOP_OP_GEMM, A, B, C, batch, M, N, K, lda, ldb, ldc,
+                     strideA, strideB, strideC, 0, transB, in, out);
+  if (ep) {
+    c.alpha = ep->alpha;
+    c.bias = ep->bias;
+    c.act = ep->act;
+  }
+  return run_splitk(c, sched, split, workspace, workspace_bytes, hip_stream);
+}
+
+int alcop_conv2d_igemm_splitk(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                              int K, int R, int S, int stride_h, int stride_w, int pad_h,
+                              int pad_w, alcop_dtype in, alcop_dtype out, const alcop_sched* sched,
+                              int split, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+  Call c;
+  int rc = conv_call(&c, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, in, out);
+  if (rc) return rc;
+  return run_splitk(c, sched, split, workspace, workspace_bytes, hip_stream);
+}
+
+int alcop_splitk_space(const alcop_problem* prob, alcop_sched* out, int cap)
+{
+  if (!prob) return ALCOP_ERR_NULL;
+  const int rc = check_problem(*prob);
+  if (rc) return rc;
+  const std::vector<alcop_sched> v = space_of(*prob, 1);
+  if (out)
+    for (int i = 0; i < (int)v.size() && i < cap; i++) out[i] = v[i];
+  return (int)v.size();
+}
+
+int alcop_splitk_auto(const alcop_problem* prob, int split, alcop_sched* sched_out, int* split_out,
+                      double* predicted_us)
+{
+  if (!prob || !sched_out || !split_out) return ALCOP_ERR_NULL;
+  int rc = check_problem(*prob);
+  if (rc) return rc;
+  if (prob->transA) return ALCOP_ERR_UNSUPPORTED;
+  if (split < 0 || split > 64) return ALCOP_ERR_SHAPE;
+  rc = auto_splitk(*prob, split, sched_out, split_out);
+  if (rc) return rc;
+  if (predicted_us) *predicted_us = predict_splitk(*prob, *sched_out, *split_out, Device());
+  return ALCOP_OK;
 }
 
 int alcop_sched_supported(const alcop_problem* prob, const alcop_sched* sched)

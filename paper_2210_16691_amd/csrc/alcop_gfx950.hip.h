@@ -32,6 +32,7 @@ struct Gfx950 {
   }
   __device__ static __forceinline__ uint32_t block_x() { return blockIdx.x; }
   __device__ static __forceinline__ uint32_t block_y() { return blockIdx.y; }
+  __device__ static __forceinline__ uint32_t block_z() { return blockIdx.z; }
 
   __device__ static __forceinline__ uint32_t lds_base()
   {

@@ -33,12 +33,12 @@ constexpr bool instance_feasible(int bm, int bn, int bk, int wm, int wn, int s, 
 }
 
 template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int R, int F, int BL, int AM,
-          int AL = 0>
+          int AL = 0, int SK = 0>
 void add_instance(std::vector<KernelEntry>& t)
 {
   if constexpr (instance_feasible(BM, BN, BK, WM, WN, S, R, F)) {
-    using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL>;
-    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, C::LDS_BYTES, C::NT,
+    using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK>;
+    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, C::LDS_BYTES, C::NT,
                             C::L, &launch_instance<C>});
   }
 }
@@ -77,6 +77,13 @@ void add_instance(std::vector<KernelEntry>& t)
   add_instance<DT, BM, BN, BK, WM, WN, 2, 2, 1, BL, 0, 1>(T);      \
   add_instance<DT, BM, BN, BK, WM, WN, 3, 2, 1, BL, 0, 1>(T);      \
   add_instance<DT, BM, BN, BK, WM, WN, 4, 2, 1, BL, 0, 1>(T);
+
+// Split-K variants: the unpipelined baseline and the fused multi-level pipelines.
+#define ALCOP_SPLITK_PIPES(T, DT, BM, BN, BK, WM, WN, BL, AM)         \
+  add_instance<DT, BM, BN, BK, WM, WN, 1, 1, 0, BL, AM, 0, 1>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 2, 2, 1, BL, AM, 0, 1>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 3, 2, 1, BL, AM, 0, 1>(T);      \
+  add_instance<DT, BM, BN, BK, WM, WN, 4, 2, 1, BL, AM, 0, 1>(T);
 
 #define ALCOP_BOTH_BK(MACRO, T, DT, BM, BN, WM, WN, BL, AM) \
   MACRO(T, DT, BM, BN, 32, WM, WN, BL, AM)                  \

@@ -65,6 +65,11 @@ struct Params {
   float alpha;
   const float* bias;
   int act;
+  // split-K kernels (SK == 1): grid.z blocks share an output tile, block z reduces over
+  // k in [z * ksplit_len, min(K, (z + 1) * ksplit_len)) and stores its fp32 partial tile at
+  // C + z * zstrideC elements (C is then the caller's workspace)
+  int ksplit_len;
+  long zstrideC;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -110,10 +115,10 @@ struct Opnd {
 };
 
 template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int S_, int R_, int FUSE_,
-          int BL_, int AM_, int AL_ = 0>
+          int BL_, int AM_, int AL_ = 0, int SK_ = 0>
 struct KCfg {
   static constexpr int DT = DT_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
-  static constexpr int S = S_, R = R_, FUSE = FUSE_, BL = BL_, AM = AM_, AL = AL_;
+  static constexpr int S = S_, R = R_, FUSE = FUSE_, BL = BL_, AM = AM_, AL = AL_, SK = SK_;
   static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, NWAVES = WAVES_M * WAVES_N;
   static constexpr int NT = NWAVES * 64;
   // AL: 0 = A stored M x K, 1 = A stored K x M.  BL: 0 = B stored K x N, 1 = B stored N x K.
@@ -278,8 +283,14 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     tm = lid / p.ntn;
     tn = lid - tm * p.ntn;
   }
-  const int nko = (p.K + BK - 1) / BK;        // the last k-tile may be partial (K % 8 == 0)
-  const bool ktail = (p.K % BK) != 0;
+  // the k range of this block: all of K, or one slice of it (split-K; slices are whole k-tiles)
+  int k0 = 0, Kb = p.K;
+  if constexpr (C::SK) {
+    k0 = (int)HW::block_z() * p.ksplit_len;
+    Kb = (p.K - k0) < p.ksplit_len ? (p.K - k0) : p.ksplit_len;
+  }
+  const int nko = (Kb + BK - 1) / BK;         // the last k-tile may be partial (K % 8 == 0)
+  const bool ktail = (Kb % BK) != 0;
 
   // ---- global -> LDS producers -----------------------------------------------------------
   using OA = typename C::OA;
@@ -287,13 +298,23 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   const int q0 = wave * 64 + lane;            // 16-byte LDS slot of this lane in load 0
   const char* Abatch = (const char*)p.A + (long)batch * p.strideA * 2;
   const char* Bbatch = (const char*)p.B + (long)batch * p.strideB * 2;
+  if constexpr (C::SK) {   // origin of the slice: k0 columns (k-contiguous) or k0 rows further
+    if constexpr (C::AM == 0) Abatch += (long)k0 * (C::AL ? p.lda : 1) * 2;
+    Bbatch += (long)k0 * (C::BL ? 1 : p.ldb) * 2;
+  }
   LoadState<HW> la, lb;
   // convolution: per-load row geometry of the gathered A tile
   int ih0[NLA], iw0[NLA];
   uint32_t coff[NLA];
   int cr = 0, cs = 0, cc0 = 0;                // (r, s, c0) of the next k-tile to issue
+  if constexpr (C::SK && C::AM == 1) {        // the slice starts at tap k0 / C, channel k0 % C
+    const int tap = k0 / p.cC;
+    cc0 = k0 - tap * p.cC;
+    cr = tap / p.cS;
+    cs = tap - cr * p.cS;
+  }
   if constexpr (C::AM == 0) {
-    la = setup_loader<OA, HW>(Abatch, tm, p.M, p.lda, p.K, nko, q0);
+    la = setup_loader<OA, HW>(Abatch, tm, p.M, p.lda, Kb, nko, q0);
   } else {
     // implicit GEMM: row m of A is output pixel (img, p, q); a k-tile lies inside one filter tap
     // (r, s) because bk divides C, so a lane's chunk is 16 contiguous bytes of x or padding.
@@ -313,7 +334,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
                            c * 16);
     }
   }
-  lb = setup_loader<OB, HW>(Bbatch, tn, p.N, p.ldb, p.K, nko, q0);
+  lb = setup_loader<OB, HW>(Bbatch, tn, p.N, p.ldb, Kb, nko, q0);
 
   // ---- HBM -> L2 touches (third pipeline level) --------------------------------------------
   // The blocks of one XCD that run side by side load the same A row-panel (those with equal tm)
@@ -552,6 +573,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     const uint32_t ebase = lds0 + (uint32_t)wave * C::EPI_WAVE_BYTES;
     const int m0 = tm * BM + wm * WM, n0 = tn * BN + wn * WN;
     char* Cb = (char*)p.C + (long)batch * p.strideC * OB;
+    if constexpr (C::SK) Cb += (long)HW::block_z() * p.zstrideC * OB;
     const bool fused = p.alpha != 1.0f || p.bias != nullptr || p.act != 0;
 #pragma unroll
     for (int j = 0; j < TM; j++) {

@@ -4,11 +4,13 @@
 #include <vector>
 
 #include "alcop_kernel.hip.h"
+#include "alcop_splitk.hip.h"
 
 namespace alcop {
 
 struct KernelEntry {
   int dt, bm, bn, bk, wm, wn, stages, reg_stages, fuse, bl, am, al;
+  int sk;   // 1: split-K variant (grid.z slices of the reduction axis, fp32 partial tiles)
   int lds_bytes, threads, loads_per_stage;
   hipError_t (*launch)(const Params&, dim3, hipStream_t);
 };
@@ -21,6 +23,11 @@ void register_bf16_kn(std::vector<KernelEntry>&);
 void register_nk(std::vector<KernelEntry>&);
 void register_conv(std::vector<KernelEntry>&);
 void register_ta(std::vector<KernelEntry>&);
+void register_splitk_gemm(std::vector<KernelEntry>&);
+void register_splitk_conv(std::vector<KernelEntry>&);
+
+// Second step of a split-K product (alcop_splitk.hip.h).
+hipError_t launch_splitk_reduce(const ReduceParams& p, dim3 grid, hipStream_t st);
 
 const std::vector<KernelEntry>& registry();
 

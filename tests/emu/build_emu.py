@@ -34,11 +34,11 @@ def _compile(job) -> str:
 def build() -> str:
     os.makedirs(OUT, exist_ok=True)
     emu = os.path.join(HERE, "emu_lib.cpp")
-    jobs = [(emu, os.path.join(OUT, "emu_part%d.o" % p), ["-DEMU_PART=%d" % p]) for p in range(4)]
+    jobs = [(emu, os.path.join(OUT, "emu_part%d.o" % p), ["-DEMU_PART=%d" % p]) for p in range(5)]
     jobs.append((emu, os.path.join(OUT, "emu_main.o"), ["-DEMU_PART=-1"]))
     for name in ("alcop_api.cpp", "alcop_model.cpp"):
         jobs.append((os.path.join(CSRC, name), os.path.join(OUT, name + ".o"), []))
-    with cf.ThreadPoolExecutor(max_workers=7) as ex:
+    with cf.ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(_compile, jobs))
     if not os.path.exists(LIB) or any(os.path.getmtime(o) > os.path.getmtime(LIB) for o in objs):
         subprocess.check_call([CXX, "-shared", "-o", LIB] + objs +

@@ -119,7 +119,7 @@ struct Wave {
 };
 struct Block {
   int nt = 0, nwaves = 0;
-  uint32_t bx = 0, by = 0;
+  uint32_t bx = 0, by = 0, bz = 0;
   std::vector<unsigned char> lds;  // LDS_BASE + lds_bytes
   uint32_t lds_bytes = 0;
   std::vector<Lane> lanes;
@@ -127,8 +127,8 @@ struct Block {
   int block_arrived = 0, done = 0;
   int cur = 0;
   ucontext_t sched;
-  void (*entry)(const alcop::Params&) = nullptr;
-  const alcop::Params* params = nullptr;
+  void (*entry)(const void*) = nullptr;   // the kernel, applied to its parameter struct
+  const void* params = nullptr;
 };
 inline Block*& blk()
 {
@@ -264,6 +264,7 @@ struct Emu {
   static int wave_id() { return blk()->cur >> 6; }
   static uint32_t block_x() { return blk()->bx; }
   static uint32_t block_y() { return blk()->by; }
+  static uint32_t block_z() { return blk()->bz; }
   static uint32_t lds_base() { return LDS_BASE; }
 
   static Rsrc make_rsrc(const void* base, int bytes)
@@ -470,7 +471,7 @@ inline void lane_main()
 {
   Block& b = *blk();
   const int me = b.cur;
-  b.entry(*b.params);
+  b.entry(b.params);
   // the lane has left the kernel
   b.cur = me;
   if (!b.lanes[me].pending.empty())
@@ -522,34 +523,37 @@ inline void run_block(Block& b)
   blk() = nullptr;
 }
 
-template <class C>
-void kernel_entry(const alcop::Params& p)
+// Runs a whole grid, block after block (threads per block a multiple of 64).  Returns the
+// number of errors logged so far.
+inline long run_grid(void (*entry)(const void*), const void* params, int threads, uint32_t lds_bytes,
+                     unsigned gx, unsigned gy, unsigned gz)
 {
-  alcop::alcop_mainloop<C, Emu>(p);
+  for (unsigned bz = 0; bz < gz; bz++)
+    for (unsigned by = 0; by < gy; by++)
+      for (unsigned bx = 0; bx < gx; bx++) {
+        Block b;
+        b.nt = threads;
+        b.nwaves = threads / 64;
+        b.bx = bx;
+        b.by = by;
+        b.bz = bz;
+        b.lds_bytes = lds_bytes;
+        b.lds.assign(LDS_BASE + lds_bytes, 0);
+        for (size_t i = 0; i + 1 < b.lds.size(); i += 2) memcpy(b.lds.data() + i, &POISON16, 2);
+        b.lanes.resize(threads);
+        b.waves.resize(threads / 64);
+        b.entry = entry;
+        b.params = params;
+        run_block(b);
+        if (cfg().n_errors > 1000) return cfg().n_errors;
+      }
+  return cfg().n_errors;
 }
 
-// Runs the whole grid, block after block.  Returns the number of errors logged so far.
 template <class C>
-long run_grid(const alcop::Params& p, unsigned gx, unsigned gy)
+void mainloop_entry(const void* p)
 {
-  for (unsigned by = 0; by < gy; by++)
-    for (unsigned bx = 0; bx < gx; bx++) {
-      Block b;
-      b.nt = C::NT;
-      b.nwaves = C::NWAVES;
-      b.bx = bx;
-      b.by = by;
-      b.lds_bytes = C::LDS_BYTES;
-      b.lds.assign(LDS_BASE + C::LDS_BYTES, 0);
-      for (size_t i = 0; i + 1 < b.lds.size(); i += 2) memcpy(b.lds.data() + i, &POISON16, 2);
-      b.lanes.resize(C::NT);
-      b.waves.resize(C::NWAVES);
-      b.entry = &kernel_entry<C>;
-      b.params = &p;
-      run_block(b);
-      if (cfg().n_errors > 1000) return cfg().n_errors;
-    }
-  return cfg().n_errors;
+  alcop::alcop_mainloop<C, Emu>(*(const alcop::Params*)p);
 }
 
 }  // namespace emu

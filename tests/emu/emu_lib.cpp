@@ -14,16 +14,16 @@ namespace alcop {
 template <class C>
 hipError_t launch_emulated(const Params& p, dim3 grid, hipStream_t)
 {
-  emu::run_grid<C>(p, grid.x, grid.y);
+  emu::run_grid(&emu::mainloop_entry<C>, &p, C::NT, C::LDS_BYTES, grid.x, grid.y, grid.z);
   return hipSuccess;
 }
 
 template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int R, int F, int BL, int AM,
-          int AL = 0>
+          int AL = 0, int SK = 0>
 void add(std::vector<KernelEntry>& t)
 {
-  using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL>;
-  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, C::LDS_BYTES, C::NT, C::L,
+  using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK>;
+  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, C::LDS_BYTES, C::NT, C::L,
                           &launch_emulated<C>});
 }
 
@@ -70,6 +70,20 @@ void emu_part_2(std::vector<KernelEntry>& t)
   add<0, 128, 128, 64, 64, 64, 3, 2, 1, 1, 0, 1>(t);   // A stored K x M, B stored N x K
   add<1, 64, 64, 32, 32, 32, 2, 2, 1, 1, 0, 1>(t);
 }
+#elif EMU_PART == 4
+void emu_part_4(std::vector<KernelEntry>& t)
+{
+  // split-K variants
+  add<0, 128, 128, 64, 64, 64, 1, 1, 0, 0, 0, 0, 1>(t);
+  add<0, 128, 128, 64, 64, 64, 3, 2, 1, 0, 0, 0, 1>(t);
+  add<0, 64, 64, 64, 32, 32, 4, 2, 1, 0, 0, 0, 1>(t);
+  add<1, 128, 128, 64, 64, 64, 2, 2, 1, 0, 0, 0, 1>(t);
+  add<0, 128, 128, 64, 64, 64, 3, 2, 1, 1, 0, 0, 1>(t);   // B stored N x K
+  add<0, 64, 64, 64, 32, 32, 2, 2, 1, 1, 0, 0, 1>(t);
+  add<0, 128, 64, 64, 64, 32, 3, 2, 1, 0, 1, 0, 1>(t);    // convolution
+  add<0, 64, 64, 64, 32, 32, 1, 1, 0, 0, 1, 0, 1>(t);
+  add<0, 64, 128, 64, 32, 64, 4, 2, 1, 0, 1, 0, 1>(t);
+}
 #elif EMU_PART == 3
 void emu_part_3(std::vector<KernelEntry>& t)
 {
@@ -88,12 +102,26 @@ void emu_part_0(std::vector<KernelEntry>&);
 void emu_part_1(std::vector<KernelEntry>&);
 void emu_part_2(std::vector<KernelEntry>&);
 void emu_part_3(std::vector<KernelEntry>&);
+void emu_part_4(std::vector<KernelEntry>&);
 void register_f16_kn_mid(std::vector<KernelEntry>& t)
 {
   emu_part_0(t);
   emu_part_1(t);
   emu_part_2(t);
   emu_part_3(t);
+  emu_part_4(t);
+}
+void register_splitk_gemm(std::vector<KernelEntry>&) {}
+void register_splitk_conv(std::vector<KernelEntry>&) {}
+
+static void reduce_entry(const void* p)
+{
+  alcop_splitk_reduce<emu::Emu>(*(const ReduceParams*)p);
+}
+hipError_t launch_splitk_reduce(const ReduceParams& p, dim3 grid, hipStream_t)
+{
+  emu::run_grid(&reduce_entry, &p, REDUCE_THREADS, 0, grid.x, grid.y, grid.z);
+  return hipSuccess;
 }
 void register_f16_kn_big(std::vector<KernelEntry>&) {}
 void register_f16_kn_small(std::vector<KernelEntry>&) {}

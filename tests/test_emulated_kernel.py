@@ -216,3 +216,83 @@ def test_out_of_bounds_accesses_are_noticed():
     assert errs and "global store outside" in " ".join(errs)
     errs = emu.call(al.alcop_gemm, A, B, C, s, reads=[A, B, C], writes=[])
     assert errs      # C declared read-only
+
+
+# ---- split-K ---------------------------------------------------------------------------------------
+def _ws(batch, M, N, split):
+    n = al.alcop_splitk_workspace_bytes(batch, M, N, split)
+    assert n == 4 * split * batch * M * N
+    return torch.full((n // 4,), float("nan"), dtype=torch.float32)
+
+
+@pytest.mark.parametrize("transB", [0, 1])
+def test_splitk_gemm_exact_in_bounds_every_emulated_variant(transB):
+    dt = "f16"
+    scheds = [al.sched(128, 128, 64, 64, 64, 3, 2, 1), al.sched(64, 64, 64, 32, 32, 2 if transB else 4, 2, 1)]
+    if not transB:
+        scheds.append(al.sched(128, 128, 64, 64, 64, 1, 1, 0))
+    for n, s in enumerate(scheds):
+        # ragged M and N, 9 k-tiles and a partial one: slices of unequal length, the last one short
+        M, N, K = s.bm + 24, s.bn + 8, 9 * 64 + 24
+        A = wl.small_ints((M, K), dt, 40 + n)
+        B = wl.small_ints((N, K) if transB else (K, N), dt, 41 + n)
+        ref = oracle.gemm(wl.bits(A), wl.bits(B.t().contiguous() if transB else B), ODT[dt])
+        for split in (2, 4, 7, 10, 64):
+            C = torch.full((M, N), float("nan"), dtype=torch.float16)
+            ws = _ws(1, M, N, split)
+            errs = emu.call(al.alcop_gemm_splitk, A, B, C, split, ws, s, transB=bool(transB),
+                            reads=[A, B], writes=[C, ws], policy=emu.POLICIES[(n + split) % 4])
+            assert not errs, (repr(s), split, errs[:4])
+            assert _exact(C, ref), (repr(s), split)
+
+
+def test_splitk_fused_epilogue_batched_bf16_and_auto():
+    b, M, N, K = 2, 72, 136, 5 * 64
+    A = wl.small_ints((b, M, K), "bf16", 51)
+    B = wl.small_ints((b, K, N), "bf16", 52)
+    bias = (torch.arange(N, dtype=torch.float32) % 7) - 3
+    C = torch.full((b, M, N), float("nan"), dtype=torch.float32)
+    s = al.sched(128, 128, 64, 64, 64, 2, 2, 1)
+    ws = _ws(b, M, N, 3)
+    errs = emu.call(al.alcop_gemm_splitk, A, B, C, 3, ws, s, 0.25, bias, 1,
+                    reads=[A, B, bias], writes=[C, ws], policy=(0, 1))
+    assert not errs, errs[:4]
+    ref = oracle.epilogue(oracle.bmm(wl.bits(A), wl.bits(B), oracle.BF16), 0.25, bias.double().numpy(), 1)
+    assert _exact(C, ref)
+    # the model's pick for a small output with a long reduction axis uses several slices and is
+    # predicted faster than the best unsplit schedule; too small a workspace is refused
+    with emu._swapped():
+        prob = al.problem(al.OP_GEMM, 128, 64, 4096, al.F16, al.F16)
+        s2, split, us = al.alcop_splitk_auto(prob)
+        assert split > 1
+        assert us < al.alcop_model_predict(prob, al.alcop_sched_auto(prob), 0)[0]
+        assert al.alcop_splitk_auto(prob, 4)[1] == 4
+    A2 = wl.small_ints((128, 512), "f16", 53)
+    B2 = wl.small_ints((512, 64), "f16", 54)
+    C2 = torch.zeros(128, 64, dtype=torch.float16)
+    small = torch.zeros(128 * 64 * 4 - 1, dtype=torch.float32)
+    with pytest.raises(al.AlcopError) as e:
+        emu.call(al.alcop_gemm_splitk, A2, B2, C2, 4, small, None, reads=[A2, B2], writes=[C2, small])
+    assert e.value.code == al.ERR_SIZE
+    # automatic schedule and split on the emulator's own table
+    ws2 = _ws(1, 128, 64, 64)
+    errs = emu.call(al.alcop_gemm_splitk, A2, B2, C2, 0, ws2, None, reads=[A2, B2], writes=[C2, ws2])
+    assert not errs, errs[:4]
+    assert _exact(C2, oracle.gemm(wl.bits(A2), wl.bits(B2), oracle.F16))
+
+
+def test_splitk_conv_exact_and_in_bounds():
+    g = dict(N=1, H=7, W=9, C=128, K=72, R=3, S=3, stride=(1, 1), pad=(1, 1))
+    x = wl.small_ints((g["N"], g["H"], g["W"], g["C"]), "f16", 61)
+    w = wl.small_ints((g["R"], g["S"], g["C"], g["K"]), "f16", 62)
+    ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, g["stride"], g["pad"])
+    M = g["N"] * g["H"] * g["W"]
+    for n, s in enumerate((al.sched(128, 64, 64, 64, 32, 3, 2, 1), al.sched(64, 64, 64, 32, 32, 1, 1, 0),
+                           al.sched(64, 128, 64, 32, 64, 4, 2, 1))):
+        for split in (2, 3, 5, 18):       # 18 k-tiles of 64: slices start inside taps and at taps
+            y = torch.full((g["N"], g["H"], g["W"], g["K"]), float("nan"), dtype=torch.float16)
+            ws = _ws(1, M, g["K"], split)
+            errs = emu.call(al.alcop_conv2d_igemm_splitk, x, w, y, split, ws, g["stride"], g["pad"], s,
+                            reads=[x, w], writes=[y, ws], policy=emu.POLICIES[(n + split) % 4])
+            assert not errs, (repr(s), split, errs[:4])
+            assert _exact(y, ref), (repr(s), split)

@@ -193,3 +193,33 @@ def test_auto_schedule_is_the_models_top_one_and_cache_round_trip(tmp_path):
     with pytest.raises(al.AlcopError) as e:
         al.alcop_cache_load(str(tmp_path / "missing.txt"))
     assert e.value.code == al.ERR_IO
+
+
+def test_splitk_space_model_pick_and_argument_checks():
+    L = al.lib()
+    rn50 = al.problem(al.OP_GEMM, 1024, 64, 2048, al.F16, al.F16)          # 16 tiles of 64 x 64
+    big = al.problem(al.OP_GEMM, 8192, 8192, 8192, al.BF16, al.BF16)
+    conv = al.problem(al.OP_CONV2D, 6272, 256, 2304, al.F16, al.F16, conv_C=256)
+    for p in (rn50, big, conv, al.problem(al.OP_GEMM, 512, 512, 512, al.BF16, al.F32, transB=True)):
+        assert len(al.alcop_splitk_space(p)) >= 4
+    s, split, us = al.alcop_splitk_auto(rn50)
+    assert split >= 4
+    assert us < al.alcop_model_predict(rn50, al.alcop_sched_auto(rn50), 0)[0]
+    assert al.alcop_splitk_auto(big)[1] == 1          # plenty of tiles: slicing only adds a pass
+    assert al.alcop_splitk_auto(conv)[1] > 1
+    # more slices than k-tiles are clamped by the launch, not by the query; the query is monotone
+    # in nothing in particular, but every answer is a built variant
+    keys = {v.key() for v in al.alcop_splitk_space(rn50)}
+    for k in (1, 2, 8, 64):
+        assert al.alcop_splitk_auto(rn50, k)[0].key() in keys
+    assert al.alcop_splitk_workspace_bytes(2, 128, 64, 3) == 4 * 3 * 2 * 128 * 64
+    assert al.alcop_splitk_workspace_bytes(1, 128, 64, 0) == 0
+    fake = ctypes.c_void_p(0x10000)
+    call = lambda tA, split, ws, nbytes: L.alcop_gemm_splitk(
+        fake, fake, fake, 1, 128, 64, 512, 512, 64, 64, 0, 0, 0, tA, 0, 0, 0, None, None, split,
+        ws, nbytes, None)
+    assert call(1, 2, fake, 1 << 20) == al.ERR_UNSUPPORTED
+    assert call(0, 2, None, 1 << 20) == al.ERR_NULL
+    assert call(0, 2, ctypes.c_void_p(0x10004), 1 << 20) == al.ERR_ALIGN
+    assert call(0, -1, fake, 1 << 20) == al.ERR_SHAPE
+    assert call(0, 2, fake, 4 * 2 * 128 * 64 - 1) == al.ERR_SIZE
