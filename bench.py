@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--copy-calib", type=int, default=0, metavar="MiB",
                     help="run a plain device-to-device copy of this many MiB --steps times and exit "
                          "(calibrates the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
+    ap.add_argument("--splitk-report", action="store_true",
+                    help="time the split-K entry points against the best unsplit schedule on the "
+                         "configurations with fewer output tiles than compute units; prints one JSON object")
     ap.add_argument("--sched", default=None,
                     help="bm,bn,bk,wm,wn,S,R,F[,raster]: time this schedule only, no tuning (for profiling)")
     a = ap.parse_args()
@@ -65,6 +68,10 @@ def main():
 
     if a.tune_report:
         print(json.dumps(tune_report(al, wl, torch, dev)))
+        return
+
+    if a.splitk_report:
+        print(json.dumps(splitk_report(al, wl, torch, dev, stream)))
         return
 
     if a.sched:
@@ -261,6 +268,49 @@ def tune_report(al, wl, torch, dev):
                      "best_in_top_k_pct": curves,
                      "top5": [[repr(s), round(us, 2)] for s, us in top],
                      "all": [[list(s.key()), round(us, 3)] for s, us in meas]}
+    return rep
+
+
+def splitk_report(al, wl, torch, dev, stream):
+    """Best unsplit schedule (model's top 10, timed) against split-K (the model's schedule, every
+    slice count timed) on the shapes whose tile count leaves compute units idle."""
+    rep = {}
+
+    def timed(fn, iters=200):
+        for _ in range(10):
+            fn()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(iters):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / iters
+
+    for name in ("mm_rn50_fc", "conv14", "ffn2"):
+        prob, Ad, Bd, Cd, conv, flops, byts = _setup(al, wl, torch, dev, name)
+        base = al.alcop_tune(prob, Ad, Bd, Cd, top_k=10, model=0, iters=50, conv=conv)
+        M, N = prob.M, prob.N
+        s, pick, pred = al.alcop_splitk_auto(prob)
+        ws = torch.empty(al.alcop_splitk_workspace_bytes(1, M, N, 32) // 4, dtype=torch.float32, device=dev)
+        by_split = {}
+        for k in (1, 2, 3, 4, 6, 8, 12, 16, 24, 32):
+            if k > (prob.K + s.bk - 1) // s.bk:
+                continue
+            if conv is None:
+                fn = lambda k=k: al.alcop_gemm_splitk(Ad, Bd, Cd, k, ws, s, stream=stream)
+            else:
+                fn = lambda k=k: al.alcop_conv2d_igemm_splitk(Ad, Bd, Cd, k, ws, (1, 1), (1, 1), s, stream=stream)
+            by_split[k] = round(timed(fn), 2)
+        best_k = min(by_split, key=by_split.get)
+        rep[name] = {"unsplit_best_us": round(base.best_us, 2), "unsplit_schedule": repr(base.best),
+                     "splitk_schedule": repr(s), "model_split": pick, "model_predicted_us": round(pred, 2),
+                     "us_by_split": by_split, "best_split": best_k,
+                     "speedup_best_split": round(base.best_us / by_split[best_k], 3),
+                     "speedup_model_split": round(base.best_us / by_split.get(pick, float("nan")), 3),
+                     "tflops_best_split": round(flops / by_split[best_k] / 1e6, 1)}
     return rep
 
 
