@@ -295,6 +295,7 @@ def splitk_report(al, wl, torch, dev, stream):
         M, N = prob.M, prob.N
         s, pick, pred = al.alcop_splitk_auto(prob)
         ws = torch.empty(al.alcop_splitk_workspace_bytes(1, M, N, 32) // 4, dtype=torch.float32, device=dev)
+        tuned, tuned_split = al.alcop_tune_splitk(prob, Ad, Bd, Cd, ws, top_k=10, iters=50, conv=conv)
         by_split = {}
         for k in (1, 2, 3, 4, 6, 8, 12, 16, 24, 32):
             if k > (prob.K + s.bk - 1) // s.bk:
@@ -307,6 +308,9 @@ def splitk_report(al, wl, torch, dev, stream):
         best_k = min(by_split, key=by_split.get)
         rep[name] = {"unsplit_best_us": round(base.best_us, 2), "unsplit_schedule": repr(base.best),
                      "splitk_schedule": repr(s), "model_split": pick, "model_predicted_us": round(pred, 2),
+                     "tuned_top10": {"schedule": repr(tuned.best), "split": tuned_split,
+                                     "us": round(tuned.best_us, 2), "space": tuned.space,
+                                     "speedup_vs_unsplit": round(base.best_us / tuned.best_us, 3)},
                      "us_by_split": by_split, "best_split": best_k,
                      "speedup_best_split": round(base.best_us / by_split[best_k], 3),
                      "speedup_model_split": round(base.best_us / by_split.get(pick, float("nan")), 3),

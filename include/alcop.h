@@ -187,6 +187,24 @@ int alcop_conv2d_igemm_splitk(const void* x, const void* w, void* y, int N, int 
                               void* workspace /* device */, size_t workspace_bytes,
                               void* hip_stream);
 
+/*
+ * Model-ranked tuning over (split-K variant, number of slices): candidates whose partial tiles
+ * do not fit the workspace are pruned, the rest are ranked by the model of alcop_splitk_auto and
+ * the first top_k (0 = all) are timed with HIP events, `iters` launches of both kernels each.
+ * Operands as for alcop_tune (C and the workspace are overwritten); best / best_split / best_us
+ * receive the fastest measured pair; the optional log arrays (host, log_cap entries) the trials
+ * in rank order, log_split holding the number of slices actually launched.  Synchronises.
+ */
+int alcop_tune_splitk(const alcop_problem* prob /* host */, const void* A, const void* B, void* C,
+                      long lda, long ldb, long ldc, long strideA, long strideB, long strideC,
+                      const int* conv /* host, 11 ints, conv only */, void* workspace /* device */,
+                      size_t workspace_bytes, int top_k, int iters, alcop_sched* best /* host */,
+                      int* best_split /* host */, double* best_us /* host */,
+                      int* trials_run /* host */, int* space_size /* host */,
+                      alcop_sched* log_sched /* host */, int* log_split /* host */,
+                      double* log_pred_us /* host */, double* log_meas_us /* host */, int log_cap,
+                      void* hip_stream);
+
 /* The split-K variants built into the library for the problem's dtype / layout / operator
  * (same conventions as alcop_sched_space). */
 int alcop_splitk_space(const alcop_problem* prob /* host */, alcop_sched* out /* host */, int cap);

@@ -25,7 +25,7 @@ EXPORTS = [
     "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
-    "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space",
+    "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk",
 ]
 
 
@@ -111,6 +111,9 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
                                     vp, sz, vp]
     L.alcop_conv2d_igemm_splitk.restype = i
     L.alcop_conv2d_igemm_splitk.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, i, vp, sz, vp]
+    L.alcop_tune_splitk.restype = i
+    L.alcop_tune_splitk.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, vp, sz, i, i, sp, ip, dp, ip, ip,
+                                    sp, ip, dp, dp, i, vp]
     L.alcop_splitk_space.restype = i
     L.alcop_splitk_space.argtypes = [pp, sp, i]
     L.alcop_splitk_auto.restype = i
@@ -366,6 +369,25 @@ def alcop_tune(prob: Problem, A, B, C, top_k=10, model=0, iters=20, conv=None, s
     _check(rc, "alcop_tune")
     log = [(Sched(*ls[i].key()), lp[i], lm[i]) for i in range(trials.value)]
     return TuneResult(Sched(*best.key()), best_us.value, trials.value, space.value, log)
+
+
+def alcop_tune_splitk(prob: Problem, A, B, C, workspace, top_k=10, iters=20, conv=None, stream=None):
+    """Model-ranked tuning over (split-K variant, slices).  Returns (TuneResult, best_split); the
+    log entries are (Sched, slices, predicted_us, measured_us)."""
+    cv, ld = _operands(prob, A, B, C, conv)
+    cap = 16 * max(1, lib().alcop_splitk_space(ctypes.byref(prob), None, 0))
+    best, best_us, best_split = Sched(), ctypes.c_double(), ctypes.c_int()
+    trials, space = ctypes.c_int(), ctypes.c_int()
+    ls, lk = (Sched * cap)(), (ctypes.c_int * cap)()
+    lp, lm = (ctypes.c_double * cap)(), (ctypes.c_double * cap)()
+    rc = lib().alcop_tune_splitk(ctypes.byref(prob), _ptr(A), _ptr(B), _ptr(C), *ld, cv, _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), top_k, iters,
+                                 ctypes.byref(best), ctypes.byref(best_split), ctypes.byref(best_us),
+                                 ctypes.byref(trials), ctypes.byref(space), ls, lk, lp, lm, cap,
+                                 _stream(stream))
+    _check(rc, "alcop_tune_splitk")
+    log = [(Sched(*ls[i].key()), lk[i], lp[i], lm[i]) for i in range(trials.value)]
+    return TuneResult(Sched(*best.key()), best_us.value, trials.value, space.value, log), best_split.value
 
 
 def alcop_time(prob: Problem, A, B, C, s: Sched, warmup=3, iters=20, conv=None, stream=None) -> float:

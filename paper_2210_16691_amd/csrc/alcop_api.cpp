@@ -523,10 +523,10 @@ int call_of_problem(const alcop_problem* prob, const void* A, const void* B, voi
 
 // Mean microseconds per launch over `iters` back-to-back launches (HIP events on `st`).
 int time_sched(const Call& c, const alcop_sched& s, const KernelEntry* e, int warmup, int iters,
-               hipStream_t st, double* us)
+               hipStream_t st, double* us, const Split* split = nullptr)
 {
   for (int i = 0; i < warmup; i++) {
-    int rc = launch_call(c, s, e, st);
+    int rc = launch_call(c, s, e, st, split);
     if (rc) return rc;
   }
   hipEvent_t e0, e1;
@@ -537,7 +537,7 @@ int time_sched(const Call& c, const alcop_sched& s, const KernelEntry* e, int wa
   }
   int rc = ALCOP_OK;
   (void)hipEventRecord(e0, st);
-  for (int i = 0; i < iters && rc == ALCOP_OK; i++) rc = launch_call(c, s, e, st);
+  for (int i = 0; i < iters && rc == ALCOP_OK; i++) rc = launch_call(c, s, e, st, split);
   (void)hipEventRecord(e1, st);
   if (hipEventSynchronize(e1) != hipSuccess) rc = ALCOP_ERR_LAUNCH;
   float ms = 0.f;
@@ -642,6 +642,71 @@ int alcop_conv2d_igemm_splitk(const void* x, const void* w, void* y, int N, int 
   int rc = conv_call(&c, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, in, out);
   if (rc) return rc;
   return run_splitk(c, sched, split, workspace, workspace_bytes, hip_stream);
+}
+
+int alcop_tune_splitk(const alcop_problem* prob, const void* A, const void* B, void* C, long lda,
+                      long ldb, long ldc, long strideA, long strideB, long strideC, const int* conv,
+                      void* workspace, size_t workspace_bytes, int top_k, int iters,
+                      alcop_sched* best, int* best_split, double* best_us, int* trials_run,
+                      int* space_size, alcop_sched* log_sched, int* log_split, double* log_pred_us,
+                      double* log_meas_us, int log_cap, void* hip_stream)
+{
+  if (!best || !best_split || !best_us) return ALCOP_ERR_NULL;
+  if (!workspace) return ALCOP_ERR_NULL;
+  if (!aligned16(workspace)) return ALCOP_ERR_ALIGN;
+  if (top_k < 0 || iters <= 0) return ALCOP_ERR_SHAPE;
+  Call c;
+  int rc = call_of_problem(prob, A, B, C, lda, ldb, ldc, strideA, strideB, strideC, conv, &c);
+  if (rc) return rc;
+  if (c.transA) return ALCOP_ERR_UNSUPPORTED;
+  rc = check_call(c);
+  if (rc) return rc;
+  const alcop_problem p = problem_of(c);
+  struct Cand {
+    alcop_sched s;
+    const KernelEntry* e;
+    Split sp;
+    double pred;
+  };
+  std::vector<Cand> cands;
+  const Device dev;
+  for (const alcop_sched& s : space_of(p, 1)) {
+    const KernelEntry* e = nullptr;
+    if (check_sched(p, s, &e, 1) != ALCOP_OK || span_check(c, s) != ALCOP_OK) continue;
+    int last_nz = 0;
+    for (int k : kSplitChoices) {
+      const Split sp = make_split(c.K, s.bk, k, workspace);
+      if (sp.nz == last_nz) continue;                       // same slicing as a smaller request
+      last_nz = sp.nz;
+      if (4.0 * sp.nz * c.batch * c.M * c.N > (double)workspace_bytes) continue;   // pruned
+      cands.push_back(Cand{s, e, sp, predict_splitk(p, s, k, dev)});
+    }
+  }
+  if (space_size) *space_size = (int)cands.size();
+  if (cands.empty()) return ALCOP_ERR_SCHED;
+  std::stable_sort(cands.begin(), cands.end(),
+                   [](const Cand& a, const Cand& b) { return a.pred < b.pred; });
+  const int n = top_k == 0 ? (int)cands.size() : std::min(top_k, (int)cands.size());
+  bool have = false;
+  for (int t = 0; t < n; t++) {
+    double us = 0;
+    rc = time_sched(c, cands[t].s, cands[t].e, 3, iters, (hipStream_t)hip_stream, &us, &cands[t].sp);
+    if (rc) return rc;
+    if (t < log_cap) {
+      if (log_sched) log_sched[t] = cands[t].s;
+      if (log_split) log_split[t] = cands[t].sp.nz;
+      if (log_pred_us) log_pred_us[t] = cands[t].pred;
+      if (log_meas_us) log_meas_us[t] = us;
+    }
+    if (!have || us < *best_us) {
+      *best_us = us;
+      *best = cands[t].s;
+      *best_split = cands[t].sp.nz;
+      have = true;
+    }
+  }
+  if (trials_run) *trials_run = n;
+  return ALCOP_OK;
 }
 
 int alcop_splitk_space(const alcop_problem* prob, alcop_sched* out, int cap)

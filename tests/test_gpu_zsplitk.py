@@ -129,3 +129,26 @@ def test_bad_arguments_are_refused():
     with pytest.raises(al.AlcopError) as e:      # not a split-K variant
         al.alcop_gemm_splitk(A, B, C, 2, _ws(1, 128, 64, 2), al.sched(256, 256, 32, 128, 64, 2, 2, 1))
     assert e.value.code == al.ERR_SCHED
+
+
+def test_tuner_over_variants_and_slices():
+    cfg, A, B = wl.make_inputs("mm_rn50_fc")
+    M, N, K = cfg["M"], cfg["N"], cfg["K"]
+    Ad, Bd = A.to(DEV), B.to(DEV)
+    C = torch.empty(M, N, dtype=torch.float16, device=DEV)
+    prob = al.problem(al.OP_GEMM, M, N, K, al.F16, al.F16)
+    ws = _ws(1, M, N, 32)
+    r, split = al.alcop_tune_splitk(prob, Ad, Bd, C, ws, top_k=8, iters=20)
+    assert r.trials == 8 and len(r.log) == 8 and r.space > 8
+    preds = [p for _, _, p, _ in r.log]
+    assert preds == sorted(preds)                      # trials come in the model's order
+    assert r.best_us == min(m for _, _, _, m in r.log)
+    assert (r.best.key(), split) in [(s.key(), k) for s, k, _, _ in r.log]
+    # a small workspace prunes the large slice counts
+    tiny = _ws(1, M, N, 2)
+    r2, split2 = al.alcop_tune_splitk(prob, Ad, Bd, C, tiny, top_k=0, iters=5)
+    assert split2 <= 2 and all(k <= 2 for _, k, _, _ in r2.log) and r2.space < r.space
+    # the tuned pair computes the right thing
+    al.alcop_gemm_splitk(Ad, Bd, C, split, ws, r.best)
+    torch.cuda.synchronize()
+    assert_close(to_f64(C), oracle.gemm(wl.bits(A), wl.bits(B), ODT[cfg["dtype"]]), "tuned split-K")

@@ -223,3 +223,9 @@ def test_splitk_space_model_pick_and_argument_checks():
     assert call(0, 2, ctypes.c_void_p(0x10004), 1 << 20) == al.ERR_ALIGN
     assert call(0, -1, fake, 1 << 20) == al.ERR_SHAPE
     assert call(0, 2, fake, 4 * 2 * 128 * 64 - 1) == al.ERR_SIZE
+    best, k, us = al.Sched(), ctypes.c_int(), ctypes.c_double()
+    tune = lambda ws, top_k: L.alcop_tune_splitk(
+        ctypes.byref(rn50), fake, fake, fake, 2048, 64, 64, 0, 0, 0, None, ws, 1 << 20, top_k, 5,
+        ctypes.byref(best), ctypes.byref(k), ctypes.byref(us), None, None, None, None, None, None, 0, None)
+    assert tune(None, 5) == al.ERR_NULL
+    assert tune(fake, -1) == al.ERR_SHAPE
