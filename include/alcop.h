@@ -153,6 +153,17 @@ int alcop_conv2d_igemm(const void* x, const void* w, void* y, int N, int H, int 
                        void* hip_stream);
 
 /*
+ * The same convolution with the weights stored KRSC, [K][R][S][C]: the filter index outermost,
+ * i.e. B of the GEMM view stored N x (R*S*C) with the reduction axis contiguous (both operand
+ * tiles are then read from LDS with plain 16-byte reads).  In an alcop_problem this layout is
+ * op = ALCOP_OP_CONV2D with transB = 1.  Everything else as for alcop_conv2d_igemm.
+ */
+int alcop_conv2d_igemm_krsc(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                            int K, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
+                            alcop_dtype in, alcop_dtype out, const alcop_sched* sched /* host */,
+                            void* hip_stream);
+
+/*
  * Split-K: the reduction axis is cut into `split` slices of whole k-tiles, every slice is a block
  * of its own (grid.z), and a second kernel adds the slices' fp32 partial tiles in ascending
  * order, applies f(.) and converts to the output type.  For outputs with few tiles and a long

@@ -25,7 +25,7 @@ EXPORTS = [
     "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
-    "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk",
+    "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc",
 ]
 
 
@@ -86,6 +86,8 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
     L.alcop_bmm_fused.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, ep, sp, vp]
     L.alcop_conv2d_igemm.restype = i
     L.alcop_conv2d_igemm.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, vp]
+    L.alcop_conv2d_igemm_krsc.restype = i
+    L.alcop_conv2d_igemm_krsc.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, vp]
     L.alcop_sched_supported.restype = i
     L.alcop_sched_supported.argtypes = [pp, sp]
     L.alcop_sched_space.restype = i
@@ -289,6 +291,17 @@ def alcop_splitk_auto(prob: "Problem", split: int = 0):
     _check(lib().alcop_splitk_auto(ctypes.byref(prob), int(split), ctypes.byref(s), ctypes.byref(n),
                                    ctypes.byref(us)), "alcop_splitk_auto")
     return s, n.value, us.value
+
+
+def alcop_conv2d_igemm_krsc(x, w, y, stride=(1, 1), pad=(0, 0), sched=None, stream=None):
+    """x NHWC [N,H,W,C], w KRSC [K,R,S,C], y NPQK [N,P,Q,K]; all contiguous."""
+    N, H, W, Cc = x.shape
+    K, R, S, _ = w.shape
+    rc = lib().alcop_conv2d_igemm_krsc(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cc, K, R, S,
+                                       stride[0], stride[1], pad[0], pad[1],
+                                       _dtype_code(x), _dtype_code(y), _sp(sched), _stream(stream))
+    _check(rc, "alcop_conv2d_igemm_krsc")
+    return y
 
 
 def problem(op, M, N, K, in_dtype, out_dtype, batch=1, transB=False, conv_C=0, transA=False) -> Problem:

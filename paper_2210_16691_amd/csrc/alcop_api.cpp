@@ -28,6 +28,7 @@ const std::vector<KernelEntry>& registry()
     register_nk(t);
     register_conv(t);
     register_ta(t);
+    register_conv_krsc(t);
     register_splitk_gemm(t);
     register_splitk_conv(t);
     return t;
@@ -92,7 +93,8 @@ int check_problem(const alcop_problem& p)
   if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.batch <= 0 || p.batch > 65535) return ALCOP_ERR_SHAPE;
   if (p.N % 8 != 0 || p.K % 8 != 0) return ALCOP_ERR_SHAPE;
   if (p.transA && p.M % 8 != 0) return ALCOP_ERR_SHAPE;
-  if (p.op == ALCOP_OP_CONV2D && (p.transA || p.transB || p.conv_C <= 0 || p.K % p.conv_C != 0))
+  // convolution: transB selects the weight layout (0: RSCK = B stored K x N, 1: KRSC = N x K)
+  if (p.op == ALCOP_OP_CONV2D && (p.transA || p.conv_C <= 0 || p.K % p.conv_C != 0))
     return ALCOP_ERR_SHAPE;
   return ALCOP_OK;
 }
@@ -208,10 +210,6 @@ int check_call(const Call& c)
 
 int span_check(const Call& c, const alcop_sched& s)
 {
-  if (c.op == ALCOP_OP_CONV2D) {
-    if (2.0 * ((double)(c.K - 1) * c.N + c.N) >= 2147483648.0) return ALCOP_ERR_SIZE;
-    return ALCOP_OK;
-  }
   // The loaders form 32-bit byte offsets from a tile's origin.  For an operand whose rows run
   // along k (A stored K x M, B stored K x N) the rows of a partial last k-tile lie past the
   // descriptor and must stay below 2^31 as offsets, so that neither they nor the out-of-range
@@ -219,7 +217,8 @@ int span_check(const Call& c, const alcop_sched& s)
   // to whole k-tiles there.
   const double rows = std::min(s.bm, c.M), cols = std::min(s.bn, c.N);
   const double kceil = (double)((c.K + s.bk - 1) / s.bk) * s.bk;
-  const double a = c.transA ? 2.0 * ((kceil - 1) * c.lda + rows) : 2.0 * ((rows - 1) * c.lda + c.K);
+  const double a = c.op == ALCOP_OP_CONV2D ? 0.0   // x is checked as a whole with the call
+                   : c.transA ? 2.0 * ((kceil - 1) * c.lda + rows) : 2.0 * ((rows - 1) * c.lda + c.K);
   const double b = c.transB ? 2.0 * ((cols - 1) * c.ldb + c.K) : 2.0 * ((kceil - 1) * c.ldb + cols);
   if (a >= 2147483648.0 || b >= 2147483648.0) return ALCOP_ERR_SIZE;
   return ALCOP_OK;
@@ -462,7 +461,8 @@ Call gemm_call(alcop_op op, const void* A, const void* B, void* C, int batch, in
 }
 
 int conv_call(Call* c, const void* x, const void* w, void* y, int N, int H, int W, int Cc, int K,
-              int R, int S, int sh, int sw, int ph, int pw, alcop_dtype in, alcop_dtype out)
+              int R, int S, int sh, int sw, int ph, int pw, alcop_dtype in, alcop_dtype out,
+              int krsc = 0)
 {
   std::memset(c, 0, sizeof(*c));
   if (N <= 0 || H <= 0 || W <= 0 || Cc <= 0 || K <= 0 || R <= 0 || S <= 0 || sh <= 0 || sw <= 0 ||
@@ -481,9 +481,9 @@ int conv_call(Call* c, const void* x, const void* w, void* y, int N, int H, int 
   c->N = K;
   c->K = (int)Kg;
   c->lda = Kg;
-  c->ldb = K;
+  c->ldb = krsc ? Kg : K;
   c->ldc = K;
-  c->transB = 0;
+  c->transB = krsc ? 1 : 0;
   c->in = in;
   c->out = out;
   c->cN = N;
@@ -511,7 +511,7 @@ int call_of_problem(const alcop_problem* prob, const void* A, const void* B, voi
   if (prob->op == ALCOP_OP_CONV2D) {
     if (!conv) return ALCOP_ERR_NULL;
     int rc = conv_call(out, A, B, C, conv[0], conv[1], conv[2], conv[3], conv[4], conv[5], conv[6],
-                       conv[7], conv[8], conv[9], conv[10], prob->in, prob->out);
+                       conv[7], conv[8], conv[9], conv[10], prob->in, prob->out, prob->transB);
     if (rc) return rc;
     if (out->M != prob->M || out->N != prob->N || out->K != prob->K) return ALCOP_ERR_SHAPE;
     return ALCOP_OK;
@@ -732,6 +732,17 @@ int alcop_splitk_auto(const alcop_problem* prob, int split, alcop_sched* sched_o
   if (rc) return rc;
   if (predicted_us) *predicted_us = predict_splitk(*prob, *sched_out, *split_out, Device());
   return ALCOP_OK;
+}
+
+int alcop_conv2d_igemm_krsc(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                            int K, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
+                            alcop_dtype in, alcop_dtype out, const alcop_sched* sched,
+                            void* hip_stream)
+{
+  Call c;
+  int rc = conv_call(&c, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, in, out, 1);
+  if (rc) return rc;
+  return run(c, sched, hip_stream);
 }
 
 int alcop_sched_supported(const alcop_problem* prob, const alcop_sched* sched)

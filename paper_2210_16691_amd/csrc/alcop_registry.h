@@ -23,6 +23,7 @@ void register_bf16_kn(std::vector<KernelEntry>&);
 void register_nk(std::vector<KernelEntry>&);
 void register_conv(std::vector<KernelEntry>&);
 void register_ta(std::vector<KernelEntry>&);
+void register_conv_krsc(std::vector<KernelEntry>&);
 void register_splitk_gemm(std::vector<KernelEntry>&);
 void register_splitk_conv(std::vector<KernelEntry>&);
 

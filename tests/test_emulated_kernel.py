@@ -296,3 +296,28 @@ def test_splitk_conv_exact_and_in_bounds():
                             reads=[x, w], writes=[y, ws], policy=emu.POLICIES[(n + split) % 4])
             assert not errs, (repr(s), split, errs[:4])
             assert _exact(y, ref), (repr(s), split)
+
+
+# ---- convolution with KRSC weights -------------------------------------------------------------
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=9, W=7, C=64, K=72, R=3, S=3, stride=(1, 1), pad=(1, 1)),
+    dict(N=1, H=12, W=10, C=32, K=64, R=3, S=2, stride=(2, 1), pad=(1, 0)),
+])
+def test_conv_krsc_weights_exact_and_in_bounds(geom):
+    g = geom
+    x = wl.small_ints((g["N"], g["H"], g["W"], g["C"]), "f16", 71)
+    w = wl.small_ints((g["R"], g["S"], g["C"], g["K"]), "f16", 72)
+    wk = w.permute(3, 0, 1, 2).contiguous()                  # [K][R][S][C]
+    P = (g["H"] + 2 * g["pad"][0] - g["R"]) // g["stride"][0] + 1
+    Q = (g["W"] + 2 * g["pad"][1] - g["S"]) // g["stride"][1] + 1
+    ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, g["stride"], g["pad"])
+    prob = al.problem(al.OP_CONV2D, g["N"] * P * Q, g["K"], g["R"] * g["S"] * g["C"], al.F16, al.F16,
+                      conv_C=g["C"], transB=True)
+    scheds = emu.space(prob)
+    assert scheds
+    for n, s in enumerate(scheds):
+        y = torch.full((g["N"], P, Q, g["K"]), float("nan"), dtype=torch.float16)
+        errs = emu.call(al.alcop_conv2d_igemm_krsc, x, wk, y, g["stride"], g["pad"], s,
+                        reads=[x, wk], writes=[y], policy=emu.POLICIES[n % 4])
+        assert not errs, (repr(s), errs[:4])
+        assert _exact(y, ref), repr(s)
