@@ -298,6 +298,8 @@ int alcop_sched_auto(const alcop_problem* prob /* host */, alcop_sched* out /* h
  * alcop_cache_save writes every cached entry and returns their number; alcop_cache_load merges
  * the file's entries into the cache (entries that name a schedule this library cannot run for
  * that problem are skipped) and returns the number accepted.  Negative return = alcop_status.
+ * If the environment variable ALCOP_TUNE_CACHE names a file, it is merged in once, before the
+ * first time a NULL / zero schedule is resolved (a missing or unreadable file is ignored).
  */
 int alcop_cache_save(const char* path /* host */);
 int alcop_cache_load(const char* path /* host */);

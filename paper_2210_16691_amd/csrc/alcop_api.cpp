@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -154,9 +155,17 @@ CacheKey key_of(const alcop_problem& p)
                   p.transA};
 }
 
+int load_cache_file(const char* path);
+
 // Model's top-1 among the feasible schedules (used when the caller passes no schedule).
 int auto_sched(const alcop_problem& p, alcop_sched* out)
 {
+  // a tuning cache named by the environment is merged in once, before the first lookup
+  static std::once_flag env_once;
+  std::call_once(env_once, [] {
+    const char* path = std::getenv("ALCOP_TUNE_CACHE");
+    if (path && *path) (void)load_cache_file(path);
+  });
   {
     std::lock_guard<std::mutex> lk(g_cache_mu);
     auto it = g_cache.find(key_of(p));
@@ -925,6 +934,15 @@ int alcop_cache_save(const char* path)
 int alcop_cache_load(const char* path)
 {
   if (!path) return ALCOP_ERR_NULL;
+  return load_cache_file(path);
+}
+
+}  // extern "C"
+
+namespace alcop {
+namespace {
+int load_cache_file(const char* path)
+{
   std::FILE* f = std::fopen(path, "r");
   if (!f) return ALCOP_ERR_IO;
   int n = 0;
@@ -955,6 +973,10 @@ int alcop_cache_load(const char* path)
   std::fclose(f);
   return n;
 }
+}  // namespace
+}  // namespace alcop
+
+extern "C" {
 
 const char* alcop_strerror(int code)
 {

@@ -229,3 +229,19 @@ def test_splitk_space_model_pick_and_argument_checks():
         ctypes.byref(best), ctypes.byref(k), ctypes.byref(us), None, None, None, None, None, None, 0, None)
     assert tune(None, 5) == al.ERR_NULL
     assert tune(fake, -1) == al.ERR_SHAPE
+
+
+def test_tuning_cache_named_by_the_environment(tmp_path):
+    import subprocess
+    import sys
+    f = tmp_path / "cache.txt"
+    f.write_text("0 1 1536 1024 768 0 0 1 1 0 : 64 64 32 32 32 2 2 1 1 0\n")
+    code = ("import paper_2210_16691_amd as al\n"
+            "p = al.problem(al.OP_GEMM, 1536, 1024, 768, al.BF16, al.BF16)\n"
+            "print(al.alcop_sched_auto(p).key())\n")
+    env = dict(os.environ, ALCOP_TUNE_CACHE=str(f), PYTHONPATH=ROOT)
+    out = subprocess.check_output([sys.executable, "-c", code], env=env, cwd=ROOT).decode()
+    assert out.strip() == "(64, 64, 32, 32, 32, 2, 2, 1, 1, 0)"
+    env["ALCOP_TUNE_CACHE"] = str(tmp_path / "missing.txt")          # ignored, the model decides
+    out = subprocess.check_output([sys.executable, "-c", code], env=env, cwd=ROOT).decode()
+    assert out.strip() != "(64, 64, 32, 32, 32, 2, 2, 1, 1, 0)"
