@@ -321,3 +321,36 @@ def test_conv_krsc_weights_exact_and_in_bounds(geom):
                         reads=[x, wk], writes=[y], policy=emu.POLICIES[n % 4])
         assert not errs, (repr(s), errs[:4])
         assert _exact(y, ref), repr(s)
+
+
+# ---- block -> tile mapping, batched transposed layouts, bf16 convolution -------------------------
+@pytest.mark.parametrize("ntm,ntn,raster", [(4, 4, 1), (10, 4, 1), (9, 3, 1), (3, 8, 1), (5, 4, 0), (16, 1, 1)])
+def test_every_tile_is_computed_exactly_once(ntm, ntn, raster):
+    # tile counts that are / are not a multiple of 8 (the XCD-aware renumbering), more row tiles
+    # than one group of 8, a ragged last group; C starts as NaN, so a tile nobody computes shows
+    s = al.sched(64, 64, 32, 32, 32, 2, 1, 0, raster)
+    M, N, K = ntm * 64 - 8, ntn * 64 - 16, 64
+    errs, ok = _gemm_case("bf16", 0, 0, s, M, N, K, (0, 0), out="f32", seed=ntm * 10 + ntn)
+    assert not errs and ok, errs[:4]
+
+
+def test_batched_with_a_stored_k_by_m_and_b_stored_n_by_k():
+    b, M, N, K = 2, 136, 72, 96
+    A = wl.small_ints((b, K, M), "f16", 81)
+    B = wl.small_ints((b, N, K), "f16", 82)
+    C = torch.full((b, M, N), float("nan"), dtype=torch.float16)
+    s = al.sched(128, 128, 64, 64, 64, 3, 2, 1)
+    errs = emu.call(al.alcop_bmm, A, B, C, s, transB=True, transA=True, reads=[A, B], writes=[C], policy=(1, 1))
+    assert not errs, errs[:4]
+    ref = oracle.bmm(wl.bits(A.transpose(1, 2).contiguous()), wl.bits(B.transpose(1, 2).contiguous()), oracle.F16)
+    assert _exact(C, ref)
+
+
+def test_bf16_convolution_with_fp32_output():
+    x = wl.small_ints((2, 6, 5, 64), "bf16", 91)
+    w = wl.small_ints((3, 3, 64, 64), "bf16", 92)
+    y = torch.full((2, 6, 5, 64), float("nan"), dtype=torch.float32)
+    errs = emu.call(al.alcop_conv2d_igemm, x, w, y, (1, 1), (1, 1), al.sched(128, 64, 64, 64, 32, 3, 2, 1),
+                    reads=[x, w], writes=[y], policy=(1, 0))
+    assert not errs, errs[:4]
+    assert _exact(y, oracle.conv2d(wl.bits(x), wl.bits(w), oracle.BF16, (1, 1), (1, 1)))
