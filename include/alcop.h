@@ -33,7 +33,7 @@
  *   - Alignment: every tensor base pointer is 16-byte aligned; leading dimensions and batch
  *     strides are multiples of 8 elements.
  *   - Shapes: K and N must be multiples of 8; M is free.  Edge tiles in M, N and K are loaded
- *     with zero fill and stored under a mask (convolution: C must be a multiple of bk).  Each
+ *     with zero fill and stored under a mask (convolution: C must be a multiple of 8).  Each
  *     operand of one GEMM (one batch entry) must span less than 2 GiB.
  */
 #ifndef ALCOP_H
@@ -145,7 +145,10 @@ int alcop_bmm_fused(const void* A, const void* B, void* C, int batch, int M, int
  *   x: NHWC  [N][H][W][C];  w: RSCK [R][S][C][K];  y: NPQK [N][P][Q][K],
  *   P = (H + 2*pad_h - R)/stride_h + 1, Q likewise.  Cross-correlation, zero padding,
  *   dilation 1, one group.  GEMM view: M = N*P*Q, N = K, reduction = R*S*C in (r,s,c) order.
- *   C must be a multiple of the schedule's bk; K a multiple of 8; x must span < 2 GiB.
+ *   C and K must be multiples of 8; x must span < 2 GiB.  When the schedule's bk divides C a
+ *   k-tile lies inside one filter tap and the tap is tracked once per wave; otherwise (C = 8, 24,
+ *   40, ... or bk = 64 with C = 96) every lane tracks the tap of its own 8-channel chunk.  The
+ *   library holds kernels of both kinds; which one a schedule means follows from C and bk.
  */
 int alcop_conv2d_igemm(const void* x, const void* w, void* y, int N, int H, int W, int C,
                        int K, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
@@ -235,7 +238,8 @@ int alcop_splitk_auto(const alcop_problem* prob /* host */, int split,
  * schedule rules and "compile fail" marks stand for, Sec. 3.1 and Fig. 9): a kernel with
  * these parameters is built; the LDS ring fits 160 KB; the outstanding-load count
  * (S-2)*loads_per_stage fits the 6-bit vector-memory counter; fuse_inner implies R=2, S>=2;
- * bk divides C for conv.  Returns ALCOP_OK or the error a launch would return.
+ * for conv a kernel with the gather that C and bk call for.  Returns ALCOP_OK or the error a
+ * launch would return.
  */
 int alcop_sched_supported(const alcop_problem* prob /* host */, const alcop_sched* sched /* host */);
 

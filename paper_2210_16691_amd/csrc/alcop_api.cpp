@@ -30,6 +30,7 @@ const std::vector<KernelEntry>& registry()
     register_conv(t);
     register_ta(t);
     register_conv_krsc(t);
+    register_conv_anyc(t);
     register_splitk_gemm(t);
     register_splitk_conv(t);
     return t;
@@ -73,9 +74,18 @@ alcop_problem problem_of(const Call& c)
   return p;
 }
 
+// Loader of the A operand a problem needs with k-tile bk: 0 = matrix; 1 = convolution gather
+// whose k-tiles lie inside one filter tap (bk divides the channel count); 2 = gather for any
+// channel count that is a multiple of 8.
+int a_mode(const alcop_problem& p, int bk)
+{
+  if (p.op != ALCOP_OP_CONV2D) return 0;
+  return (bk > 0 && p.conv_C % bk == 0) ? 1 : 2;
+}
+
 const KernelEntry* find_entry(const alcop_problem& p, const alcop_sched& s, int sk)
 {
-  const int am = p.op == ALCOP_OP_CONV2D ? 1 : 0;
+  const int am = a_mode(p, s.bk);
   for (const KernelEntry& e : registry())
     if (e.sk == sk && e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.al == (p.transA ? 1 : 0) &&
         e.am == am && e.bm == s.bm &&
@@ -95,7 +105,8 @@ int check_problem(const alcop_problem& p)
   if (p.N % 8 != 0 || p.K % 8 != 0) return ALCOP_ERR_SHAPE;
   if (p.transA && p.M % 8 != 0) return ALCOP_ERR_SHAPE;
   // convolution: transB selects the weight layout (0: RSCK = B stored K x N, 1: KRSC = N x K)
-  if (p.op == ALCOP_OP_CONV2D && (p.transA || p.conv_C <= 0 || p.K % p.conv_C != 0))
+  if (p.op == ALCOP_OP_CONV2D &&
+      (p.transA || p.conv_C <= 0 || p.conv_C % 8 != 0 || p.K % p.conv_C != 0))
     return ALCOP_ERR_SHAPE;
   return ALCOP_OK;
 }
@@ -115,9 +126,9 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
   if (!e) return ALCOP_ERR_SCHED;
   if (e->lds_bytes > 160 * 1024) return ALCOP_ERR_SCHED;
   if (e->stages >= 2 && (e->stages - 2) * e->loads_per_stage > 63) return ALCOP_ERR_SCHED;
-  // GEMM / BMM: a partial last k-tile is zero-filled by the loader (K % 8 == 0 is checked with
-  // the problem).  Convolution: a k-tile must stay inside one filter tap.
-  if (p.op == ALCOP_OP_CONV2D && p.conv_C % s.bk != 0) return ALCOP_ERR_SHAPE;
+  // A partial last k-tile is zero-filled by the loader (K % 8 == 0 is checked with the problem).
+  // Convolution: the channel count is a multiple of 8 (checked with the problem); which gather
+  // a schedule gets follows from whether its k-tile divides the channel count.
   const long ntm = (p.M + s.bm - 1) / s.bm, ntn = (p.N + s.bn - 1) / s.bn;
   if (ntm * ntn > 0x7fffffffL) return ALCOP_ERR_SHAPE;
   if (out) *out = e;
@@ -131,10 +142,9 @@ int default_l2_prefetch(int bk) { return 256 / bk; }
 std::vector<alcop_sched> space_of(const alcop_problem& p, int sk = 0)
 {
   std::vector<alcop_sched> v;
-  const int am = p.op == ALCOP_OP_CONV2D ? 1 : 0;
   for (const KernelEntry& e : registry())
     if (e.sk == sk && e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) &&
-        e.al == (p.transA ? 1 : 0) && e.am == am)
+        e.al == (p.transA ? 1 : 0) && e.am == a_mode(p, e.bk))
     {
       v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1, 0});
       // the fused multi-level kernels are also offered with the third (HBM -> L2) level on
@@ -985,7 +995,7 @@ const char* alcop_strerror(int code)
     case ALCOP_ERR_NULL: return "null pointer";
     case ALCOP_ERR_DTYPE: return "unsupported element type";
     case ALCOP_ERR_ALIGN: return "pointer, leading dimension or stride not aligned";
-    case ALCOP_ERR_SHAPE: return "bad shape (size <= 0, K or N not a multiple of 8, conv C not a multiple of bk)";
+    case ALCOP_ERR_SHAPE: return "bad shape (size <= 0, K or N not a multiple of 8, conv C not a multiple of 8)";
     case ALCOP_ERR_SCHED: return "schedule not built or infeasible";
     case ALCOP_ERR_LAUNCH: return "HIP launch failed";
     case ALCOP_ERR_UNSUPPORTED: return "not supported";

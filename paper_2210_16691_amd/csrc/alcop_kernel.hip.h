@@ -55,7 +55,7 @@ struct Params {
   int out_dtype;               // 0 f16, 1 bf16, 2 f32
   int ntm, ntn;                // tile counts
   int raster, group_m;         // block -> tile order
-  // convolution geometry (AM == 1): x is NHWC, A rows are (img, p, q)
+  // convolution geometry (AM != 0): x is NHWC, A rows are (img, p, q)
   int cH, cW, cC, cP, cQ, cS, csh, csw, cph, cpw;
   unsigned a_span, b_span;     // conv: bytes of x; unused otherwise
   // third pipeline level (HBM -> L2): every wave touches lines of k-tile kt + pf_dist when it
@@ -139,7 +139,10 @@ struct KCfg {
   static_assert(BK == 32 || BK == 64, "bk");
   static_assert(S >= 1 && S <= 4 && (R == 1 || R == 2), "stages");
   static_assert(!FUSE || (R == 2 && S >= 2), "fusion needs a register double buffer and S>=2");
-  static_assert(!(AM == 1 && AL == 1), "the convolution gather produces a K-contiguous A tile");
+  // AM: 0 = A is a matrix; 1 = A is gathered from an NHWC image and a k-tile lies inside one
+  // filter tap (bk divides the channel count: the tap is the same for all lanes); 2 = gathered,
+  // any channel count that is a multiple of 8 (every lane tracks the tap of its own chunk)
+  static_assert(!(AM != 0 && AL == 1), "the convolution gather produces a K-contiguous A tile");
   static_assert(WAIT <= 63, "vmcnt is a 6-bit counter");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
 };
@@ -307,6 +310,8 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   int ih0[NLA], iw0[NLA];
   uint32_t coff[NLA];
   int cr = 0, cs = 0, cc0 = 0;                // (r, s, c0) of the next k-tile to issue
+  bool a_in_k = true;                         // AM == 2: this lane's chunk lies below K
+  int a_k8 = 0;                               // AM == 2: k of this lane's chunk within a k-tile
   if constexpr (C::SK && C::AM == 1) {        // the slice starts at tap k0 / C, channel k0 % C
     const int tap = k0 / p.cC;
     cc0 = k0 - tap * p.cC;
@@ -322,6 +327,17 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     la.voff = la.voff_t = la.step = la.kstep = 0;
     const int r = q0 / OA::CPR, ph = q0 % OA::CPR;
     const int c = ph ^ OA::swz(r);
+    if constexpr (C::AM == 2) {
+      // C is any multiple of 8: a chunk of 8 channels still lies inside one tap, but the chunks
+      // of a k-tile may belong to different taps, so (r, s, c0) are per lane and start at the
+      // lane's own k
+      a_k8 = c * 8;
+      const int kc = k0 + a_k8;
+      const int tap = kc / p.cC;
+      cc0 = kc - tap * p.cC;
+      cr = tap / p.cS;
+      cs = tap - cr * p.cS;
+    }
 #pragma unroll
     for (int i = 0; i < NLA; i++) {
       const int m = tm * BM + r + i * OA::RSTEP;
@@ -331,7 +347,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       ih0[i] = (m < p.M) ? pp * p.csh - p.cph : -0x40000000;
       iw0[i] = qq * p.csw - p.cpw;
       coff[i] = (uint32_t)((((img * p.cH + (pp * p.csh - p.cph)) * p.cW) + iw0[i]) * p.cC * 2 +
-                           c * 16);
+                           (C::AM == 2 ? 0 : c * 16));
     }
   }
   lb = setup_loader<OB, HW>(Bbatch, tn, p.N, p.ldb, Kb, nko, q0);
@@ -378,6 +394,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       st_ka = st_live ? (uint32_t)kt * la.kstep : 0x80000000u;
     else
       st_tap = (uint32_t)(((cr * p.cW + cs) * p.cC + cc0) * 2);
+    if constexpr (C::AM == 2) a_in_k = kt * BK + a_k8 < Kb;
     st_kb = st_live ? (uint32_t)kt * lb.kstep : 0x80000000u;
   };
   auto issue_one = [&](int idx) {
@@ -386,8 +403,9 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       if constexpr (C::AM == 0) {
         HW::dma16(la.rsrc, st_voffA + st_ka + (uint32_t)i * la.step, st_dst + i * (NWAVES * 1024));
       } else {
-        const bool ok = st_live && (unsigned)(ih0[i] + cr) < (unsigned)p.cH &&
-                        (unsigned)(iw0[i] + cs) < (unsigned)p.cW;
+        bool ok = st_live && (unsigned)(ih0[i] + cr) < (unsigned)p.cH &&
+                  (unsigned)(iw0[i] + cs) < (unsigned)p.cW;
+        if constexpr (C::AM == 2) ok = ok && a_in_k;
         HW::dma16(la.rsrc, ok ? coff[i] + st_tap : 0x80000000u, st_dst + i * (NWAVES * 1024));
       }
     } else if (idx < NLA + NLB) {
@@ -403,6 +421,10 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     if constexpr (C::AM == 1) {
       cc0 += BK;
       if (cc0 == p.cC) { cc0 = 0; cs++; if (cs == p.cS) { cs = 0; cr++; } }
+    }
+    if constexpr (C::AM == 2) {
+      cc0 += BK;
+      while (cc0 >= p.cC) { cc0 -= p.cC; cs++; if (cs == p.cS) { cs = 0; cr++; } }
     }
   };
   auto issue = [&](int kt, int slot) {

@@ -24,6 +24,7 @@ void register_nk(std::vector<KernelEntry>&);
 void register_conv(std::vector<KernelEntry>&);
 void register_ta(std::vector<KernelEntry>&);
 void register_conv_krsc(std::vector<KernelEntry>&);
+void register_conv_anyc(std::vector<KernelEntry>&);
 void register_splitk_gemm(std::vector<KernelEntry>&);
 void register_splitk_conv(std::vector<KernelEntry>&);
 

@@ -98,6 +98,11 @@ void emu_part_3(std::vector<KernelEntry>& t)
   add<0, 128, 64, 64, 64, 32, 3, 2, 1, 1, 1>(t);       // KRSC weights
   add<0, 64, 64, 32, 32, 32, 1, 1, 0, 1, 1>(t);
   add<0, 128, 128, 64, 64, 64, 4, 2, 1, 1, 1>(t);
+  add<0, 128, 64, 64, 64, 32, 3, 2, 1, 0, 2>(t);       // gather for any channel count (x8)
+  add<0, 128, 64, 32, 64, 32, 2, 1, 0, 0, 2>(t);
+  add<0, 64, 64, 32, 32, 32, 4, 2, 1, 0, 2>(t);
+  add<0, 64, 64, 64, 32, 32, 1, 1, 0, 0, 2>(t);
+  add<0, 64, 64, 32, 32, 32, 3, 2, 1, 1, 2>(t);        // ... with KRSC weights
 }
 #else
 // the part that is compiled once: the product's sub-table hooks and the test controls
@@ -117,6 +122,7 @@ void register_f16_kn_mid(std::vector<KernelEntry>& t)
 void register_splitk_gemm(std::vector<KernelEntry>&) {}
 void register_splitk_conv(std::vector<KernelEntry>&) {}
 void register_conv_krsc(std::vector<KernelEntry>&) {}
+void register_conv_anyc(std::vector<KernelEntry>&) {}
 
 static void reduce_entry(const void* p)
 {

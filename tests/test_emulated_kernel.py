@@ -354,3 +354,36 @@ def test_bf16_convolution_with_fp32_output():
                     reads=[x, w], writes=[y], policy=(1, 0))
     assert not errs, errs[:4]
     assert _exact(y, oracle.conv2d(wl.bits(x), wl.bits(w), oracle.BF16, (1, 1), (1, 1)))
+
+
+# ---- convolution with channel counts the k-tile does not divide -----------------------------------
+@pytest.mark.parametrize("geom", [
+    dict(N=1, H=14, W=12, C=8, K=64, R=7, S=7, stride=(2, 2), pad=(3, 3)),     # padded RGB stem
+    dict(N=2, H=7, W=6, C=24, K=72, R=3, S=3, stride=(1, 1), pad=(1, 1)),
+    dict(N=1, H=6, W=9, C=40, K=64, R=3, S=2, stride=(1, 2), pad=(0, 1)),
+    dict(N=1, H=5, W=5, C=96, K=64, R=1, S=1, stride=(1, 1), pad=(0, 0)),      # bk = 64 does not divide 96
+    dict(N=1, H=6, W=6, C=16, K=64, R=5, S=5, stride=(1, 1), pad=(2, 2)),
+])
+def test_conv_any_channel_multiple_of_8(geom):
+    g = geom
+    x = wl.small_ints((g["N"], g["H"], g["W"], g["C"]), "f16", 95)
+    w = wl.small_ints((g["R"], g["S"], g["C"], g["K"]), "f16", 96)
+    P = (g["H"] + 2 * g["pad"][0] - g["R"]) // g["stride"][0] + 1
+    Q = (g["W"] + 2 * g["pad"][1] - g["S"]) // g["stride"][1] + 1
+    ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, g["stride"], g["pad"])
+    ran = 0
+    for krsc in (False, True):
+        prob = al.problem(al.OP_CONV2D, g["N"] * P * Q, g["K"], g["R"] * g["S"] * g["C"], al.F16, al.F16,
+                          conv_C=g["C"], transB=krsc)
+        wt = w.permute(3, 0, 1, 2).contiguous() if krsc else w
+        fn = al.alcop_conv2d_igemm_krsc if krsc else al.alcop_conv2d_igemm
+        for n, s in enumerate(emu.space(prob)):
+            if g["C"] % s.bk == 0:
+                continue                                   # served by the one-tap gather, tested above
+            y = torch.full((g["N"], P, Q, g["K"]), float("nan"), dtype=torch.float16)
+            errs = emu.call(fn, x, wt, y, g["stride"], g["pad"], s, reads=[x, wt], writes=[y],
+                            policy=emu.POLICIES[n % 4])
+            assert not errs, (repr(s), krsc, errs[:4])
+            assert _exact(y, ref), (repr(s), krsc)
+            ran += 1
+    assert ran >= 2

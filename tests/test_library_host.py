@@ -101,8 +101,15 @@ def test_feasibility_rules():
     pc = al.problem(al.OP_CONV2D, 32 * 56 * 56, 64, 576, al.F16, al.F16, conv_C=64)
     assert al.alcop_sched_supported(pc, al.sched(128, 64, 64, 64, 32, 3, 2, 1)) == al.OK
     pc32 = al.problem(al.OP_CONV2D, 1024, 64, 9 * 32, al.F16, al.F16, conv_C=32)
-    assert al.alcop_sched_supported(pc32, al.sched(128, 64, 64, 64, 32, 3, 2, 1)) == al.ERR_SHAPE
+    # C = 32 with bk = 64: a k-tile spans two filter taps -> the per-lane gather kernels serve it
+    assert al.alcop_sched_supported(pc32, al.sched(128, 64, 64, 64, 32, 3, 2, 1)) == al.OK
     assert al.alcop_sched_supported(pc32, al.sched(128, 64, 32, 64, 32, 3, 2, 1)) == al.OK
+    # ... for fewer tiles than the one-tap gather is built for
+    assert al.alcop_sched_supported(pc32, al.sched(64, 128, 64, 32, 64, 3, 2, 1)) == al.ERR_SCHED
+    pc8 = al.problem(al.OP_CONV2D, 12544, 64, 49 * 8, al.F16, al.F16, conv_C=8)     # a padded RGB stem
+    assert len([s for s in al.alcop_sched_space(pc8) if al.alcop_sched_supported(pc8, s) == al.OK]) >= 12
+    assert al.alcop_sched_supported(al.problem(al.OP_CONV2D, 1024, 64, 9 * 12, al.F16, al.F16, conv_C=12),
+                                    al.sched(128, 64, 32, 64, 32, 3, 2, 1)) == al.ERR_SHAPE
 
 
 def test_sweep_of_the_motivating_example_is_built():
