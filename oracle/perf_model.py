@@ -136,3 +136,19 @@ def bottleneck(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, dev: Device = Devi
     t_lds = n_blocks * steps * n_warp * (wm + wn) * 16 * 2 / (dev.num_cu * dev.bw_lds_cu)
     t_mem = (n_blocks * math.ceil(K / bk) * (bm + bn) * bk * 2 + n_blocks * bm * bn * out_bytes) / dev.bw_dram
     return max(t_cmp, t_lds, t_mem)
+
+
+def predict_splitk(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, split,
+                   dev: Device = Device(), transB: bool = False):
+    """Split-K schedule (not in the paper; its model applied to the sliced problem): the
+    reduction axis is cut into slices of whole k-tiles, each slice is a block of its own writing
+    an fp32 partial tile, and a second pass adds the slices.  `split` slices are requested; the
+    k-tiles are dealt evenly, so fewer may result.  Returns (microseconds, slices)."""
+    n_tiles_k = math.ceil(K / bk)
+    per = math.ceil(n_tiles_k / split)
+    slices = math.ceil(n_tiles_k / per)
+    t = predict(M, N, per * bk, batch * slices, 4, bm, bn, bk, wm, wn, S, R, fuse, dev,
+                transB=transB)["t_kernel"]
+    if slices > 1:
+        t += dev.lat_dram + dev.lat_dram_write + batch * M * N * (4.0 * slices + out_bytes) / dev.bw_dram
+    return t, slices

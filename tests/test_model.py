@@ -112,3 +112,23 @@ def test_library_model_matches_oracle(P):
         us1, _ = al.alcop_model_predict(prob, s, 1)
         assert us1 == pytest.approx(
             pm.bottleneck(P["M"], P["N"], P["K"], P["batch"], ob, s.bm, s.bn, s.bk, s.wm, s.wn), rel=1e-12)
+
+
+@pytest.mark.parametrize("shape", [(1, 1024, 64, 2048), (1, 4096, 768, 3072), (3, 136, 72, 1000), (1, 2048, 2048, 2048)])
+def test_library_splitk_model_matches_oracle(shape):
+    b, M, N, K = shape
+    prob = al.problem(al.OP_BMM if b > 1 else al.OP_GEMM, M, N, K, al.F16, al.F16, batch=b)
+    for split in (1, 2, 5, 16, 64):
+        s, k, us = al.alcop_splitk_auto(prob, split)
+        assert k == split
+        want, slices = pm.predict_splitk(M, N, K, b, 2, s.bm, s.bn, s.bk, s.wm, s.wn, s.stages,
+                                         s.reg_stages, bool(s.fuse_inner), split)
+        assert us == pytest.approx(want, rel=1e-12)
+        # the pick is the arg-min of the same formula over the variants built for this problem
+        best = min(pm.predict_splitk(M, N, K, b, 2, v.bm, v.bn, v.bk, v.wm, v.wn, v.stages, v.reg_stages,
+                                     bool(v.fuse_inner), split)[0] for v in al.alcop_splitk_space(prob))
+        assert us == pytest.approx(best, rel=1e-12)
+    # hand-checked slicing: 33 k-tiles of 64 over 4 requested slices -> 9 per slice -> 4 slices;
+    # over 16 requested -> 3 per slice -> 11 slices
+    assert pm.predict_splitk(128, 128, 33 * 64, 1, 2, 128, 128, 64, 64, 64, 3, 2, True, 4)[1] == 4
+    assert pm.predict_splitk(128, 128, 33 * 64, 1, 2, 128, 128, 64, 64, 64, 3, 2, True, 16)[1] == 11
