@@ -167,6 +167,17 @@ int alcop_conv2d_igemm_krsc(const void* x, const void* w, void* y, int N, int H,
                             void* hip_stream);
 
 /*
+ * Convolution with the consumer-side elementwise function of alcop_gemm_fused on the
+ * accumulators: y[n][p][q][k] = act(alpha * conv(x, w) + bias[k]) - the convolution + bias + ReLU
+ * layer of the paper's ResNet / VGG models in one kernel.  krsc = 0: weights RSCK, 1: KRSC.
+ * ep == NULL means alpha = 1, no bias, identity.
+ */
+int alcop_conv2d_igemm_fused(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                             int K, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
+                             alcop_dtype in, alcop_dtype out, const alcop_epilogue* ep /* host */,
+                             int krsc, const alcop_sched* sched /* host */, void* hip_stream);
+
+/*
  * Split-K: the reduction axis is cut into `split` slices of whole k-tiles, every slice is a block
  * of its own (grid.z), and a second kernel adds the slices' fp32 partial tiles in ascending
  * order, applies f(.) and converts to the output type.  For outputs with few tiles and a long

@@ -25,7 +25,7 @@ EXPORTS = [
     "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
-    "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc",
+    "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused",
 ]
 
 
@@ -88,6 +88,8 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
     L.alcop_conv2d_igemm.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, vp]
     L.alcop_conv2d_igemm_krsc.restype = i
     L.alcop_conv2d_igemm_krsc.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, vp]
+    L.alcop_conv2d_igemm_fused.restype = i
+    L.alcop_conv2d_igemm_fused.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, ep, i, sp, vp]
     L.alcop_sched_supported.restype = i
     L.alcop_sched_supported.argtypes = [pp, sp]
     L.alcop_sched_space.restype = i
@@ -291,6 +293,23 @@ def alcop_splitk_auto(prob: "Problem", split: int = 0):
     _check(lib().alcop_splitk_auto(ctypes.byref(prob), int(split), ctypes.byref(s), ctypes.byref(n),
                                    ctypes.byref(us)), "alcop_splitk_auto")
     return s, n.value, us.value
+
+
+def alcop_conv2d_igemm_fused(x, w, y, stride=(1, 1), pad=(0, 0), alpha=1.0, bias=None, act=0,
+                             krsc=False, sched=None, stream=None):
+    """y = act(alpha * conv(x, w) + bias[k]); w is RSCK [R,S,C,K], or KRSC [K,R,S,C] if krsc."""
+    N, H, W, Cc = x.shape
+    if krsc:
+        K, R, S, _ = w.shape
+    else:
+        R, S, _, K = w.shape
+    e = _epilogue(alpha, bias, act)
+    rc = lib().alcop_conv2d_igemm_fused(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cc, K, R, S,
+                                        stride[0], stride[1], pad[0], pad[1], _dtype_code(x),
+                                        _dtype_code(y), ctypes.byref(e), int(krsc), _sp(sched),
+                                        _stream(stream))
+    _check(rc, "alcop_conv2d_igemm_fused")
+    return y
 
 
 def alcop_conv2d_igemm_krsc(x, w, y, stride=(1, 1), pad=(0, 0), sched=None, stream=None):

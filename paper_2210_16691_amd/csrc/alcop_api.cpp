@@ -764,6 +764,23 @@ int alcop_conv2d_igemm_krsc(const void* x, const void* w, void* y, int N, int H,
   return run(c, sched, hip_stream);
 }
 
+int alcop_conv2d_igemm_fused(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                             int K, int R, int S, int stride_h, int stride_w, int pad_h, int pad_w,
+                             alcop_dtype in, alcop_dtype out, const alcop_epilogue* ep, int krsc,
+                             const alcop_sched* sched, void* hip_stream)
+{
+  Call c;
+  int rc = conv_call(&c, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, in, out,
+                     krsc ? 1 : 0);
+  if (rc) return rc;
+  if (ep) {
+    c.alpha = ep->alpha;
+    c.bias = ep->bias;
+    c.act = ep->act;
+  }
+  return run(c, sched, hip_stream);
+}
+
 int alcop_sched_supported(const alcop_problem* prob, const alcop_sched* sched)
 {
   if (!prob || !sched) return ALCOP_ERR_NULL;

@@ -387,3 +387,18 @@ def test_conv_any_channel_multiple_of_8(geom):
             assert _exact(y, ref), (repr(s), krsc)
             ran += 1
     assert ran >= 2
+
+
+def test_conv_bias_relu_in_the_epilogue():
+    x = wl.small_ints((2, 6, 5, 64), "f16", 97)
+    w = wl.small_ints((3, 3, 64, 72), "f16", 98)
+    bias = (torch.arange(72, dtype=torch.float32) % 9) - 4
+    ref = oracle.epilogue(oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, (1, 1), (1, 1)).reshape(-1, 72),
+                          0.5, bias.double().numpy(), 1).reshape(2, 6, 5, 72)
+    for krsc in (False, True):
+        wt = w.permute(3, 0, 1, 2).contiguous() if krsc else w
+        y = torch.full((2, 6, 5, 72), float("nan"), dtype=torch.float32)
+        errs = emu.call(al.alcop_conv2d_igemm_fused, x, wt, y, (1, 1), (1, 1), 0.5, bias, 1, krsc,
+                        al.sched(128, 64, 64, 64, 32, 3, 2, 1), reads=[x, wt, bias], writes=[y])
+        assert not errs, errs[:4]
+        assert _exact(y, ref), krsc

@@ -45,3 +45,18 @@ def test_config_conv14_equals_the_rsck_result_within_tolerance():
     assert_close(to_f64(y), ref, "conv14 KRSC")
     scale = float(np.sqrt(np.mean(ref ** 2)))
     assert np.max(np.abs(to_f64(y) - ref)) < 2e-2 * scale
+
+
+def test_conv_bias_relu_in_the_epilogue():
+    x = wl.small_ints((2, 12, 10, 64), "f16", 831)
+    w = wl.small_ints((3, 3, 64, 72), "f16", 832)
+    bias = (torch.arange(72, dtype=torch.float32) % 9) - 4
+    ref = oracle.epilogue(oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, (1, 1), (1, 1)).reshape(-1, 72),
+                          0.5, bias.double().numpy(), 1).reshape(2, 12, 10, 72)
+    for krsc in (False, True):
+        wt = (w.permute(3, 0, 1, 2).contiguous() if krsc else w).to(DEV)
+        y = torch.full((2, 12, 10, 72), float("nan"), dtype=torch.float32, device=DEV)
+        al.alcop_conv2d_igemm_fused(x.to(DEV), wt, y, (1, 1), (1, 1), 0.5, bias.to(DEV), 1, krsc,
+                                    al.sched(128, 64, 64, 64, 32, 3, 2, 1))
+        torch.cuda.synchronize()
+        assert np.array_equal(to_f64(y), ref), krsc
