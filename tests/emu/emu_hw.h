@@ -23,6 +23,10 @@
 //     landing it delivers at once.  A read that the kernel's waits and barriers do not order
 //     after the landing, or before the refill, then returns poison (NaN patterns) or the wrong
 //     k-tile, and the result differs from the oracle's;
+//   * the release of a ring slot: an LDS read counts as in flight from its issue until the
+//     lane's next s_waitcnt lgkmcnt(0) (the compiler's own waits before a register is used are
+//     not visible here, so this is the conservative reading); a direct-to-LDS load issued onto
+//     bytes that any lane may still be reading is an error;
 //   * no load is in flight and no lane is waiting when the kernel returns.
 //
 // The semantics modelled here were established by probing an MI355X:
@@ -109,6 +113,7 @@ struct Lane {
   int mma_par = 0, tr_par = 0;
   long n_rsrc = 0, n_dma = 0;      // per-lane operation counters for the uniformity checks
   std::deque<Pending> pending;
+  std::vector<std::pair<uint32_t, uint32_t>> reads;   // LDS reads since the last lgkmcnt(0) wait
 };
 struct Wave {
   int arrived = 0, runnable = 0;
@@ -121,6 +126,7 @@ struct Block {
   int nt = 0, nwaves = 0;
   uint32_t bx = 0, by = 0, bz = 0;
   std::vector<unsigned char> lds;  // LDS_BASE + lds_bytes
+  std::vector<uint16_t> reading;   // per LDS byte: reads that may still be in flight
   uint32_t lds_bytes = 0;
   std::vector<Lane> lanes;
   std::vector<Wave> waves;
@@ -190,6 +196,20 @@ inline unsigned char* lds_ptr(uint32_t addr, uint32_t n, uint32_t align, const c
     return nullptr;
   }
   return b.lds.data() + addr;
+}
+// An LDS read of [addr, addr + n) by the current lane stays "in flight" until its next wait.
+inline void note_read(uint32_t addr, uint32_t n)
+{
+  Block& b = *blk();
+  for (uint32_t i = 0; i < n; i++) b.reading[addr + i]++;
+  b.lanes[b.cur].reads.emplace_back(addr, n);
+}
+inline void reads_done()
+{
+  Block& b = *blk();
+  for (const auto& r : b.lanes[b.cur].reads)
+    for (uint32_t i = 0; i < r.second; i++) b.reading[r.first + i]--;
+  b.lanes[b.cur].reads.clear();
 }
 inline void land(const Pending& p)
 {
@@ -289,6 +309,14 @@ struct Emu {
     p.dst = dst;
     p.bytes = n;
     memcpy(p.data, data, n);
+    if (lds_ptr(dst, n, 4, "direct-to-LDS destination"))
+      for (uint32_t i = 0; i < n; i++)
+        if (b.reading[dst + i]) {
+          fail("direct-to-LDS load onto LDS bytes %u.. that a read issued before the last "
+               "lgkmcnt(0) wait may still be fetching (block %u,%u thread %d)",
+               dst + i - LDS_BASE, b.bx, b.by, b.cur);
+          break;
+        }
     if (!cfg().late_landing) {
       land(p);
       return;
@@ -356,7 +384,11 @@ struct Emu {
       q.pop_front();
     }
   }
-  static void wait_lds() {}        // LDS reads of this model complete at once
+  static void wait_lds()           // reads deliver at once here; the wait ends their "in flight" mark
+  {
+    if (cfg().mutation == 4) return;
+    reads_done();
+  }
   static void block_barrier()
   {
     if (cfg().mutation == 2) return;
@@ -401,7 +433,10 @@ struct Emu {
   {
     wave_sync();
     u32x4 v = {0, 0, 0, 0};
-    if (const unsigned char* p = lds_ptr(addr, 16, 16, "ds_read_b128")) memcpy(&v, p, 16);
+    if (const unsigned char* p = lds_ptr(addr, 16, 16, "ds_read_b128")) {
+      memcpy(&v, p, 16);
+      note_read(addr, 16);
+    }
     return v;
   }
   static u32x2 lds_read_tr8(uint32_t addr)
@@ -418,7 +453,10 @@ struct Emu {
     uint16_t out[4] = {0, 0, 0, 0};
     for (int e = 0; e < 4; e++) {
       const uint32_t a = W.T[par][g + 4 * e + i / 4];
-      if (const unsigned char* p = lds_ptr(a, 8, 8, "ds_read_b64_tr_b16")) memcpy(&out[e], p + 2 * (i % 4), 2);
+      if (const unsigned char* p = lds_ptr(a, 8, 8, "ds_read_b64_tr_b16")) {
+        memcpy(&out[e], p + 2 * (i % 4), 2);
+        note_read(a + 2 * (i % 4), 2);
+      }
     }
     u32x2 v;
     memcpy(&v, out, 8);
@@ -539,6 +577,7 @@ inline long run_grid(void (*entry)(const void*), const void* params, int threads
         b.bz = bz;
         b.lds_bytes = lds_bytes;
         b.lds.assign(LDS_BASE + lds_bytes, 0);
+        b.reading.assign(LDS_BASE + lds_bytes, 0);
         for (size_t i = 0; i + 1 < b.lds.size(); i += 2) memcpy(b.lds.data() + i, &POISON16, 2);
         b.lanes.resize(threads);
         b.waves.resize(threads / 64);

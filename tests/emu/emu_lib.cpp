@@ -168,7 +168,8 @@ void emu_register_buffer(const void* ptr, size_t bytes, int writable)
 // Plants a mistake in the model's synchronisation, to show that the checks notice it:
 // 1 = every vmcnt wait lets two more loads stay in flight than asked (one more would be
 // harmless: the last load of every stage is the L2 touch, which nobody reads); 2 = the block
-// barrier does not wait; 3 = vmcnt waits are ignored (loads land only at the final wait).
+// barrier does not wait; 3 = vmcnt waits are ignored (loads land only at the final wait);
+// 4 = lgkmcnt waits are ignored (LDS reads stay in flight).
 void emu_set_mutation(int m) { emu::cfg().mutation = m; }
 
 long emu_error_count(void) { return emu::cfg().n_errors; }

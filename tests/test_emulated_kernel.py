@@ -200,6 +200,11 @@ def test_planted_synchronisation_mistakes_are_noticed():
     # waits ignored altogether
     errs, ok = _gemm_case("f16", 0, 0, s4, M, N, K, (1, 0), mutation=3)
     assert not ok
+    # no wait for the LDS reads before the barrier that releases a slot: the refill may overtake
+    # a read (the data path of the model cannot show this, the in-flight bookkeeping does)
+    for s in (s4, s3u, al.sched(128, 128, 64, 64, 64, 1, 1, 0)):
+        errs, ok = _gemm_case("f16", 0, 0, s, M, N, K, (1, 0), mutation=4)
+        assert errs and "may still be fetching" in " ".join(errs), repr(s)
 
 
 def test_out_of_bounds_accesses_are_noticed():
