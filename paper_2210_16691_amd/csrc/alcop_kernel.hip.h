@@ -114,6 +114,11 @@ struct Opnd {
   }
 };
 
+// One kernel = one KCfg.  DT: 0 fp16, 1 bf16 operands.  BM x BN x BK: block tile; WM x WN: wave
+// tile.  S: stages of the LDS ring (1 = unpipelined); R: register slots for fragments (2 = the
+// inner, LDS -> register pipeline); FUSE: the inner pipeline runs across k-tiles (Fig. 3(d)).
+// BL / AL: operand layouts; AM: how the A tile is produced (matrix or convolution gather);
+// SK: split-K variant (grid.z slices of the reduction axis, fp32 partial tiles).
 template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int S_, int R_, int FUSE_,
           int BL_, int AM_, int AL_ = 0, int SK_ = 0>
 struct KCfg {
