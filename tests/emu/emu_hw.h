@@ -68,6 +68,7 @@ struct Config {
   bool late_landing = true;    // direct-to-LDS data lands only when a wait forces it
   bool last_wave_first = false;
   int mutation = 0;            // a planted synchronisation mistake (see emu_set_mutation)
+  bool any_address = false;    // no operand ranges declared: global accesses are not checked
   std::vector<std::string> errors;
   long n_errors = 0;
 };
@@ -92,6 +93,7 @@ inline void fail(const char* fmt, ...)
 inline bool in_buffer(const void* p, size_t n, bool write)
 {
   const char* a = (const char*)p;
+  if (cfg().any_address) return true;
   for (const Buffer& b : cfg().buffers)
     if (a >= b.ptr && a + n <= b.ptr + b.bytes && (!write || b.writable)) return true;
   return false;

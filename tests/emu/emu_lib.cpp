@@ -155,6 +155,7 @@ void emu_reset(int late_landing, int last_wave_first)
   c.buffers.clear();
   c.errors.clear();
   c.n_errors = 0;
+  c.any_address = false;
   c.late_landing = late_landing != 0;
   c.last_wave_first = last_wave_first != 0;
 }
@@ -171,6 +172,10 @@ void emu_register_buffer(const void* ptr, size_t bytes, int writable)
 // barrier does not wait; 3 = vmcnt waits are ignored (loads land only at the final wait);
 // 4 = lgkmcnt waits are ignored (LDS reads stay in flight).
 void emu_set_mutation(int m) { emu::cfg().mutation = m; }
+
+// any != 0: global accesses are not checked against declared operands (for running code that
+// does not declare them); LDS, uniformity and synchronisation checks stay on.
+void emu_allow_any_address(int any) { emu::cfg().any_address = any != 0; }
 
 long emu_error_count(void) { return emu::cfg().n_errors; }
 
