@@ -256,7 +256,8 @@ int alcop_sched_supported(const alcop_problem* prob /* host */, const alcop_sche
 
 /*
  * The schedule space: every kernel built into the library that matches the problem's
- * dtype / layout / operator, whether or not it is feasible for the shape.
+ * dtype / layout / operator (for a convolution: with the gather that the channel count and the
+ * kernel's bk call for), whether or not it is feasible for the shape.
  * Writes at most `cap` entries to out (host) and returns the total count, or a negative
  * alcop_status if the problem itself is invalid.
  */
