@@ -76,6 +76,12 @@ typedef struct {
   int raster;         /* block -> tile order: 0 row-major, 1 XCD-grouped panels             */
   int l2_prefetch;    /* third buffer level (HBM -> L2): lines of k-tile kt+l2_prefetch are  */
                       /* touched when k-tile kt is issued; 0 = off; needs raster = 1         */
+  int variant;        /* 0 = the default kernel.  Convolution only, 1 = input patch resident */
+                      /* in LDS: the block loads its output tile's input pixels plus halo    */
+                      /* once and forms the filter taps by shifted LDS reads, so only the    */
+                      /* weights stream through the ring.  Needs stride 1, RSCK weights,     */
+                      /* bk equal to the channel count, and a patch that fits the LDS;       */
+                      /* a call that does not meet this returns ALCOP_ERR_SCHED              */
 } alcop_sched;
 
 /* Problem description used by the model / tuner / feasibility entry points. */
@@ -264,6 +270,15 @@ int alcop_sched_supported(const alcop_problem* prob /* host */, const alcop_sche
 int alcop_sched_space(const alcop_problem* prob /* host */, alcop_sched* out /* host */, int cap);
 
 /*
+ * The schedule variants (alcop_sched.variant != 0) built for the problem: kernels whose
+ * feasibility depends on more than the problem description - for a convolution the variant with
+ * the input patch resident in LDS, which also needs stride 1 and a patch that fits the LDS.
+ * alcop_sched_supported only checks that such a kernel exists; the launch (or the tuner) checks
+ * the rest.  A NULL / zero schedule never resolves to a variant unless the tuner chose it.
+ */
+int alcop_sched_variants(const alcop_problem* prob /* host */, alcop_sched* out /* host */, int cap);
+
+/*
  * Static latency model (paper Sec. 5, Table 1): predicted kernel time in microseconds and,
  * optionally, its terms.  terms (host, may be NULL) receives 8 doubles:
  *   [0] T_kernel  [1] T_threadblk  [2] T_init  [3] T_main_loop  [4] T_epilogue
@@ -285,6 +300,9 @@ int alcop_model_predict(const alcop_problem* prob /* host */, const alcop_sched*
  *              is model 0 and which is refitted after every timed trial; the next trial is the
  *              untried schedule with the lowest corrected prediction;
  *          3 = no model: schedules in table order (the paper's grid search baseline).
+ *   variants: 0 = candidates are the default kernels (alcop_sched_space); 1 = also the schedule
+ *          variants that depend on the call's geometry (alcop_sched_variants), those that this
+ *          call cannot use being pruned.
  *   For conv problems pass x as A, w as B, y as C and the geometry in `conv` (host; 11 ints:
  *   N,H,W,C,K,R,S,stride_h,stride_w,pad_h,pad_w), else conv = NULL and lda/ldb/ldc/strides
  *   as for alcop_bmm (batch 1 for GEMM).
@@ -294,7 +312,7 @@ int alcop_model_predict(const alcop_problem* prob /* host */, const alcop_sched*
  */
 int alcop_tune(const alcop_problem* prob /* host */, const void* A, const void* B, void* C,
                long lda, long ldb, long ldc, long strideA, long strideB, long strideC,
-               const int* conv /* host */, int top_k, int model, int iters,
+               const int* conv /* host */, int top_k, int model, int variants, int iters,
                alcop_sched* best /* host */, double* best_us /* host */,
                int* trials_run /* host */, int* space_size /* host */,
                alcop_sched* log_sched /* host */, double* log_pred_us /* host */,
@@ -310,7 +328,8 @@ int alcop_sched_auto(const alcop_problem* prob /* host */, alcop_sched* out /* h
 /*
  * Tuning cache on disk (the tuner's trial outcome per problem, so that a later process skips the
  * timing).  Text file, one line per problem:
- *   op batch M N K transA transB in out conv_C : bm bn bk wm wn stages reg_stages fuse raster l2
+ *   op batch M N K transA transB in out conv_C : bm bn bk wm wn stages reg_stages fuse raster l2 variant
+ * (the last number may be missing in files written before the field existed: 0)
  * alcop_cache_save writes every cached entry and returns their number; alcop_cache_load merges
  * the file's entries into the cache (entries that name a schedule this library cannot run for
  * that problem are skipped) and returns the number accepted.  Negative return = alcop_status.

@@ -65,22 +65,29 @@ def pipeline_latency_caption_form(t_load, t_use, n_loop, n_pipe, n_mplx):
 
 
 def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Device = Device(),
-            transB: bool = False, transA: bool = False):
-    """Returns a dict of the Table 1 quantities (microseconds)."""
+            transB: bool = False, transA: bool = False, patch_taps: int = 0):
+    """Returns a dict of the Table 1 quantities (microseconds).
+
+    patch_taps > 0 (not in the paper): a convolution whose input patch stays in LDS; the A rows
+    of a tile are fetched once per block instead of once per filter tap, so one k-tile accounts
+    for bm / patch_taps of them, and the patch (reading: 1.5 tiles) occupies LDS beside the
+    ring of B tiles."""
     ntm, ntn = math.ceil(M / bm), math.ceil(N / bn)
     tiles = ntm * ntn
     n_blocks = tiles * batch
     n_warp = (bm // wm) * (bn // wn)
     n_smem_loop = math.ceil(K / bk)
     n_reg_loop = bk // 16
-    bytes_one_smem_loop = (bm + bn) * bk * 2
+    a_rows = bm / patch_taps if patch_taps > 0 else bm
+    bytes_one_smem_loop = (a_rows + bn) * bk * 2
+    lds_use = (S * bn * bk * 2 + 1.5 * bm * bk * 2) if patch_taps > 0 else S * bytes_one_smem_loop
     bytes_one_reg_loop = n_warp * (wm + wn) * 16 * 2
     flops_one_reg_loop = 2 * bm * bn * 16
 
     # simulated scheduler
     regs = wm * wn / 64 + R * (wm / 32 + wn / 32) * 4 + 48
     waves_per_simd = max(1, min(8, math.floor(dev.regs_per_lane / regs)))
-    n_blk_per_cu = min(math.floor(dev.lds_bytes / (S * bytes_one_smem_loop)),
+    n_blk_per_cu = min(math.floor(dev.lds_bytes / lds_use),
                        math.floor(waves_per_simd * dev.simd_per_cu / n_warp))
     n_blk_per_cu = max(1, n_blk_per_cu)
     n_blk_per_cu = min(n_blk_per_cu, math.ceil(n_blocks / dev.num_cu))
@@ -110,7 +117,7 @@ def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Devi
     mats = math.ceil(n_blk_per_batch / tiles)
     rows_u = min(ntm, math.ceil(math.sqrt(per_mat)))
     cols_u = min(ntn, math.ceil(per_mat / rows_u))
-    workset = (rows_u * bm + cols_u * bn) * bk * 2 * mats
+    workset = (rows_u * a_rows + cols_u * bn) * bk * 2 * mats
     t_dram_load = dev.lat_dram + workset / dev.bw_dram
     t_smem_load = max(t_llc_load, t_dram_load)
 

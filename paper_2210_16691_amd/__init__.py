@@ -25,7 +25,7 @@ EXPORTS = [
     "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
-    "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused",
+    "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_sched_variants",
 ]
 
 
@@ -39,17 +39,19 @@ class Sched(ctypes.Structure):
     """Mirror of ``alcop_sched``."""
     _fields_ = [(n, ctypes.c_int) for n in
                 ("bm", "bn", "bk", "wm", "wn", "stages", "reg_stages", "fuse_inner", "raster",
-                 "l2_prefetch")]
+                 "l2_prefetch", "variant")]
 
     def key(self):
         return tuple(getattr(self, n) for n, _ in self._fields_)
 
     def __repr__(self):
-        return "Sched(%dx%dx%d w%dx%d S%d R%d F%d r%d pf%d)" % self.key()
+        return "Sched(%dx%dx%d w%dx%d S%d R%d F%d r%d pf%d)" % self.key()[:10] + (
+            "" if self.variant == 0 else "[v%d]" % self.variant)
 
 
-def sched(bm, bn, bk, wm, wn, stages=1, reg_stages=1, fuse_inner=0, raster=1, l2_prefetch=0) -> Sched:
-    return Sched(bm, bn, bk, wm, wn, stages, reg_stages, fuse_inner, raster, l2_prefetch)
+def sched(bm, bn, bk, wm, wn, stages=1, reg_stages=1, fuse_inner=0, raster=1, l2_prefetch=0,
+          variant=0) -> Sched:
+    return Sched(bm, bn, bk, wm, wn, stages, reg_stages, fuse_inner, raster, l2_prefetch, variant)
 
 
 class Epilogue(ctypes.Structure):
@@ -97,8 +99,10 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
     L.alcop_model_predict.restype = i
     L.alcop_model_predict.argtypes = [pp, sp, i, dp, dp]
     L.alcop_tune.restype = i
-    L.alcop_tune.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, i, i, i, sp, dp, ip, ip,
+    L.alcop_tune.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, i, i, i, i, sp, dp, ip, ip,
                              sp, dp, dp, i, vp]
+    L.alcop_sched_variants.restype = i
+    L.alcop_sched_variants.argtypes = [pp, sp, i]
     L.alcop_time.restype = i
     L.alcop_time.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, sp, i, i, dp, vp]
     L.alcop_sched_auto.restype = i
@@ -340,6 +344,16 @@ def alcop_sched_space(prob: Problem):
     return [Sched(*arr[i].key()) for i in range(n)]
 
 
+def alcop_sched_variants(prob: Problem):
+    """Schedule variants whose feasibility depends on the call (see alcop_sched.variant)."""
+    n = lib().alcop_sched_variants(ctypes.byref(prob), None, 0)
+    if n < 0:
+        raise AlcopError(n, "alcop_sched_variants")
+    arr = (Sched * max(n, 1))()
+    lib().alcop_sched_variants(ctypes.byref(prob), arr, n)
+    return [Sched(*arr[i].key()) for i in range(n)]
+
+
 def alcop_sched_auto(prob: Problem) -> Sched:
     """The schedule a None schedule resolves to (tuning cache, else the model's top-1)."""
     s = Sched()
@@ -388,14 +402,18 @@ def _operands(prob, A, B, C, conv):
     return None, (A.stride(0), B.stride(0), C.stride(0), 0, 0, 0)
 
 
-def alcop_tune(prob: Problem, A, B, C, top_k=10, model=0, iters=20, conv=None, stream=None) -> TuneResult:
-    """Model-ranked tuning on the caller's tensors (C is overwritten). top_k=0: exhaustive."""
+def alcop_tune(prob: Problem, A, B, C, top_k=10, model=0, iters=20, conv=None, stream=None,
+               variants=False) -> TuneResult:
+    """Model-ranked tuning on the caller's tensors (C is overwritten). top_k=0: exhaustive.
+    variants=True also considers the schedule variants that depend on the call's geometry."""
     cv, ld = _operands(prob, A, B, C, conv)
-    cap = max(1, lib().alcop_sched_space(ctypes.byref(prob), None, 0))
+    cap = max(1, lib().alcop_sched_space(ctypes.byref(prob), None, 0) +
+              lib().alcop_sched_variants(ctypes.byref(prob), None, 0))
     best, best_us = Sched(), ctypes.c_double()
     trials, space = ctypes.c_int(), ctypes.c_int()
     ls, lp, lm = (Sched * cap)(), (ctypes.c_double * cap)(), (ctypes.c_double * cap)()
-    rc = lib().alcop_tune(ctypes.byref(prob), _ptr(A), _ptr(B), _ptr(C), *ld, cv, top_k, model, iters,
+    rc = lib().alcop_tune(ctypes.byref(prob), _ptr(A), _ptr(B), _ptr(C), *ld, cv, top_k, model,
+                          int(variants), iters,
                           ctypes.byref(best), ctypes.byref(best_us), ctypes.byref(trials),
                           ctypes.byref(space), ls, lp, lm, cap, _stream(stream))
     _check(rc, "alcop_tune")

@@ -31,6 +31,7 @@ const std::vector<KernelEntry>& registry()
     register_ta(t);
     register_conv_krsc(t);
     register_conv_anyc(t);
+    register_conv_patch(t);
     register_splitk_gemm(t);
     register_splitk_conv(t);
     return t;
@@ -77,15 +78,17 @@ alcop_problem problem_of(const Call& c)
 // Loader of the A operand a problem needs with k-tile bk: 0 = matrix; 1 = convolution gather
 // whose k-tiles lie inside one filter tap (bk divides the channel count); 2 = gather for any
 // channel count that is a multiple of 8.
-int a_mode(const alcop_problem& p, int bk)
+// 3 = schedule variant 1 of a convolution: the input patch stays in LDS (bk equals the channel count).
+int a_mode(const alcop_problem& p, int bk, int variant)
 {
   if (p.op != ALCOP_OP_CONV2D) return 0;
+  if (variant == 1) return 3;
   return (bk > 0 && p.conv_C % bk == 0) ? 1 : 2;
 }
 
 const KernelEntry* find_entry(const alcop_problem& p, const alcop_sched& s, int sk)
 {
-  const int am = a_mode(p, s.bk);
+  const int am = a_mode(p, s.bk, s.variant);
   for (const KernelEntry& e : registry())
     if (e.sk == sk && e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.al == (p.transA ? 1 : 0) &&
         e.am == am && e.bm == s.bm &&
@@ -122,6 +125,9 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
   if (s.raster != 0 && s.raster != 1) return ALCOP_ERR_SCHED;
   if (s.l2_prefetch < 0 || s.l2_prefetch > 64 || (s.l2_prefetch > 0 && s.raster != 1))
     return ALCOP_ERR_SCHED;
+  if (s.variant != 0 &&
+      !(s.variant == 1 && p.op == ALCOP_OP_CONV2D && !p.transB && p.conv_C == s.bk && sk == 0))
+    return ALCOP_ERR_SCHED;
   const KernelEntry* e = find_entry(p, s, sk);
   if (!e) return ALCOP_ERR_SCHED;
   if (e->lds_bytes > 160 * 1024) return ALCOP_ERR_SCHED;
@@ -139,14 +145,19 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
 // latencies of matrix work at any tile size).
 int default_l2_prefetch(int bk) { return 256 / bk; }
 
-std::vector<alcop_sched> space_of(const alcop_problem& p, int sk = 0)
+// variants: 0 = the default kernels; 1 = also the schedule variants whose feasibility depends
+// on the call, not only on the problem description (the patch convolution); 2 = only those.
+std::vector<alcop_sched> space_of(const alcop_problem& p, int sk = 0, int variants = 0)
 {
   std::vector<alcop_sched> v;
   for (const KernelEntry& e : registry())
     if (e.sk == sk && e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) &&
-        e.al == (p.transA ? 1 : 0) && e.am == a_mode(p, e.bk))
+        e.al == (p.transA ? 1 : 0) &&
+        ((variants != 2 && e.am == a_mode(p, e.bk, 0)) ||
+         (variants != 0 && e.am == 3 && p.op == ALCOP_OP_CONV2D && p.conv_C == e.bk)))
     {
-      v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1, 0});
+      v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1, 0,
+                              e.am == 3 ? 1 : 0});
       // the fused multi-level kernels are also offered with the third (HBM -> L2) level on
       if (e.fuse && e.am == 0 && sk == 0)
         v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1,
@@ -167,7 +178,26 @@ CacheKey key_of(const alcop_problem& p)
 
 int load_cache_file(const char* path);
 
-// Model's top-1 among the feasible schedules (used when the caller passes no schedule).
+// The static model's top-1 among the feasible default-variant schedules (variants that depend on
+// more than the problem description, such as the patch convolution, are left to the tuner).
+int model_pick(const alcop_problem& p, alcop_sched* out)
+{
+  const Device dev;
+  double best = 0;
+  bool have = false;
+  for (const alcop_sched& s : space_of(p)) {
+    if (check_sched(p, s, nullptr) != ALCOP_OK) continue;
+    const double t = predict(p, s, 0, dev, nullptr);
+    if (!have || t < best) {
+      best = t;
+      *out = s;
+      have = true;
+    }
+  }
+  return have ? ALCOP_OK : ALCOP_ERR_SCHED;
+}
+
+// What a NULL / zero schedule resolves to: the tuning cache, else the model's pick.
 int auto_sched(const alcop_problem& p, alcop_sched* out)
 {
   // a tuning cache named by the environment is merged in once, before the first lookup
@@ -184,19 +214,8 @@ int auto_sched(const alcop_problem& p, alcop_sched* out)
       return ALCOP_OK;
     }
   }
-  const Device dev;
-  double best = 0;
-  bool have = false;
-  for (const alcop_sched& s : space_of(p)) {
-    if (check_sched(p, s, nullptr) != ALCOP_OK) continue;
-    const double t = predict(p, s, 0, dev, nullptr);
-    if (!have || t < best) {
-      best = t;
-      *out = s;
-      have = true;
-    }
-  }
-  if (!have) return ALCOP_ERR_SCHED;
+  const int rc = model_pick(p, out);
+  if (rc) return rc;
   std::lock_guard<std::mutex> lk(g_cache_mu);
   g_cache[key_of(p)] = *out;
   return ALCOP_OK;
@@ -240,6 +259,35 @@ int span_check(const Call& c, const alcop_sched& s)
                    : c.transA ? 2.0 * ((kceil - 1) * c.lda + rows) : 2.0 * ((rows - 1) * c.lda + c.K);
   const double b = c.transB ? 2.0 * ((cols - 1) * c.ldb + c.K) : 2.0 * ((kceil - 1) * c.ldb + cols);
   if (a >= 2147483648.0 || b >= 2147483648.0) return ALCOP_ERR_SIZE;
+  return ALCOP_OK;
+}
+
+// Geometry of the patch variant of a convolution (schedule variant 1) for one call, or an error:
+// stride 1; the patch (tile rows + halo, rounded up to whole block-wide loads) must fit the LDS.
+struct Patch {
+  int wp = 0, ntj = 0, loads = 0;
+};
+int patch_of(const Call& c, const alcop_sched& s, const KernelEntry* e, Patch* out)
+{
+  if (c.op != ALCOP_OP_CONV2D || c.csh != 1 || c.csw != 1) return ALCOP_ERR_SCHED;
+  Patch pt;
+  pt.wp = c.cW + 2 * c.cpw;                                    // row length of the padded image
+  const long positions = (long)(c.cP - 1) * pt.wp + c.cQ;      // output positions per image
+  pt.ntj = (int)((positions + s.bm - 1) / s.bm);
+  const long rows = s.bm + (long)(c.cR - 1) * pt.wp + (c.cS - 1);
+  const long slots = rows * (s.bk / 8);                        // 16-byte slots of the patch
+  const long loads = (slots + e->threads - 1) / e->threads;
+  if (e->patch_off + loads * e->threads * 16 > 160 * 1024) return ALCOP_ERR_SCHED;
+  if ((long)pt.ntj * c.cN > 0x7fffffffL / std::max(1, (c.N + s.bn - 1) / s.bn)) return ALCOP_ERR_SHAPE;
+  pt.loads = (int)loads;
+  if (out) *out = pt;
+  return ALCOP_OK;
+}
+
+// What a schedule needs from the call beyond the problem description.
+int call_feasible(const Call& c, const alcop_sched& s, const KernelEntry* e)
+{
+  if (e->am == 3) return patch_of(c, s, e, nullptr);
   return ALCOP_OK;
 }
 
@@ -307,6 +355,16 @@ int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipSt
     p.cph = c.cph;
     p.cpw = c.cpw;
     p.a_span = (unsigned)(2L * c.cN * c.cH * c.cW * c.cC);
+    if (e->am == 3) {
+      Patch pt;
+      if (patch_of(c, s, e, &pt) != ALCOP_OK) return ALCOP_ERR_SCHED;
+      p.cR = c.cR;
+      p.cWp = pt.wp;
+      p.ntj = pt.ntj;
+      p.patch_loads = pt.loads;
+      p.ntm = pt.ntj * c.cN;                 // tiles of padded output positions, per image
+      p.group_m = std::min(8, p.ntm);
+    }
   }
   dim3 grid((unsigned)(p.ntm * p.ntn), (unsigned)c.batch, 1);
   if (split) {
@@ -356,7 +414,8 @@ int run(const Call& c, const alcop_sched* sched, void* stream)
   if (rc) return rc;
   const alcop_problem prob = problem_of(c);
   alcop_sched s;
-  if (!sched || sched->bm == 0) {
+  const bool automatic = !sched || sched->bm == 0;
+  if (automatic) {
     rc = auto_sched(prob, &s);
     if (rc) return rc;
   } else {
@@ -366,6 +425,19 @@ int run(const Call& c, const alcop_sched* sched, void* stream)
   rc = check_sched(prob, s, &e);
   if (rc) return rc;
   rc = span_check(c, s);
+  if (rc) return rc;
+  rc = call_feasible(c, s, e);
+  if (rc && automatic && s.variant != 0) {
+    // the cached schedule was tuned on a call with another geometry (the cache key is the
+    // problem description): fall back to the model's pick for this call
+    rc = model_pick(prob, &s);
+    if (rc) return rc;
+    rc = check_sched(prob, s, &e);
+    if (rc) return rc;
+    rc = span_check(c, s);
+    if (rc) return rc;
+    rc = call_feasible(c, s, e);
+  }
   if (rc) return rc;
   return launch_call(c, s, e, (hipStream_t)stream);
 }
@@ -839,12 +911,14 @@ int alcop_time(const alcop_problem* prob, const void* A, const void* B, void* C,
   if (rc) return rc;
   rc = span_check(c, *sched);
   if (rc) return rc;
+  rc = call_feasible(c, *sched, e);
+  if (rc) return rc;
   return time_sched(c, *sched, e, warmup, iters, (hipStream_t)hip_stream, mean_us);
 }
 
 int alcop_tune(const alcop_problem* prob, const void* A, const void* B, void* C, long lda, long ldb,
                long ldc, long strideA, long strideB, long strideC, const int* conv, int top_k,
-               int model, int iters, alcop_sched* best, double* best_us, int* trials_run,
+               int model, int variants, int iters, alcop_sched* best, double* best_us, int* trials_run,
                int* space_size, alcop_sched* log_sched, double* log_pred_us, double* log_meas_us,
                int log_cap, void* hip_stream)
 {
@@ -865,9 +939,11 @@ int alcop_tune(const alcop_problem* prob, const void* A, const void* B, void* C,
   };
   std::vector<Cand> cands;
   const Device dev;
-  for (const alcop_sched& s : space_of(p)) {
+  for (const alcop_sched& s : space_of(p, 0, variants ? 1 : 0)) {
     const KernelEntry* e = nullptr;
-    if (check_sched(p, s, &e) != ALCOP_OK || span_check(c, s) != ALCOP_OK) continue;   // pruned
+    if (check_sched(p, s, &e) != ALCOP_OK || span_check(c, s) != ALCOP_OK ||
+        call_feasible(c, s, e) != ALCOP_OK)
+      continue;   // pruned
     Cand cd;
     cd.s = s;
     cd.e = e;
@@ -927,6 +1003,17 @@ int alcop_tune(const alcop_problem* prob, const void* A, const void* B, void* C,
   return ALCOP_OK;
 }
 
+int alcop_sched_variants(const alcop_problem* prob, alcop_sched* out, int cap)
+{
+  if (!prob) return ALCOP_ERR_NULL;
+  const int rc = check_problem(*prob);
+  if (rc) return rc;
+  const std::vector<alcop_sched> v = space_of(*prob, 0, 2);
+  if (out)
+    for (int i = 0; i < (int)v.size() && i < cap; i++) out[i] = v[i];
+  return (int)v.size();
+}
+
 int alcop_sched_auto(const alcop_problem* prob, alcop_sched* out)
 {
   if (!prob || !out) return ALCOP_ERR_NULL;
@@ -947,10 +1034,10 @@ int alcop_cache_save(const char* path)
       const CacheKey& k = kv.first;
       const alcop_sched& s = kv.second;
       // key order: op batch M N K transB in out conv_C transA
-      std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d : %d %d %d %d %d %d %d %d %d %d\n", std::get<0>(k),
+      std::fprintf(f, "%d %d %d %d %d %d %d %d %d %d : %d %d %d %d %d %d %d %d %d %d %d\n", std::get<0>(k),
                    std::get<1>(k), std::get<2>(k), std::get<3>(k), std::get<4>(k), std::get<9>(k),
                    std::get<5>(k), std::get<6>(k), std::get<7>(k), std::get<8>(k), s.bm, s.bn, s.bk,
-                   s.wm, s.wn, s.stages, s.reg_stages, s.fuse_inner, s.raster, s.l2_prefetch);
+                   s.wm, s.wn, s.stages, s.reg_stages, s.fuse_inner, s.raster, s.l2_prefetch, s.variant);
       n++;
     }
   }
@@ -977,9 +1064,11 @@ int load_cache_file(const char* path)
   while (std::fgets(line, sizeof(line), f)) {
     int op, batch, M, N, K, tA, tB, in, out, cc;
     alcop_sched s;
-    if (std::sscanf(line, "%d %d %d %d %d %d %d %d %d %d : %d %d %d %d %d %d %d %d %d %d", &op, &batch,
+    s.variant = 0;   // absent in files written before the field existed
+    if (std::sscanf(line, "%d %d %d %d %d %d %d %d %d %d : %d %d %d %d %d %d %d %d %d %d %d", &op, &batch,
                     &M, &N, &K, &tA, &tB, &in, &out, &cc, &s.bm, &s.bn, &s.bk, &s.wm, &s.wn,
-                    &s.stages, &s.reg_stages, &s.fuse_inner, &s.raster, &s.l2_prefetch) != 20)
+                    &s.stages, &s.reg_stages, &s.fuse_inner, &s.raster, &s.l2_prefetch,
+                    &s.variant) < 20)
       continue;
     alcop_problem p;
     p.op = (alcop_op)op;

@@ -10,13 +10,15 @@ hipError_t launch_instance(const Params& p, dim3 grid, hipStream_t st)
 {
   static bool attr_set = false;
   if (!attr_set) {
-    // LDS rings above the default 64 KB per-block limit need an explicit opt-in.
+    // LDS rings above the default 64 KB per-block limit need an explicit opt-in (the patch
+    // convolution sizes its LDS per call, up to the 160 KB a block can have).
     hipError_t e = hipFuncSetAttribute((const void*)alcop_mainloop<C, Gfx950>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       C::AM == 3 ? 160 * 1024 : C::LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  alcop_mainloop<C, Gfx950><<<grid, dim3(C::NT), C::LDS_BYTES, st>>>(p);
+  alcop_mainloop<C, Gfx950><<<grid, dim3(C::NT), dynamic_lds_bytes<C>(p), st>>>(p);
   return hipGetLastError();
 }
 
@@ -39,7 +41,7 @@ void add_instance(std::vector<KernelEntry>& t)
   if constexpr (instance_feasible(BM, BN, BK, WM, WN, S, R, F)) {
     using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK>;
     t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, C::LDS_BYTES, C::NT,
-                            C::L, &launch_instance<C>});
+                            C::L, C::PATCH_OFF, &launch_instance<C>});
   }
 }
 

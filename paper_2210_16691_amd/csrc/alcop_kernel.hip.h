@@ -70,6 +70,9 @@ struct Params {
   // C + z * zstrideC elements (C is then the caller's workspace)
   int ksplit_len;
   long zstrideC;
+  // convolution with an LDS-resident input patch (AM == 3): filter height, row length of the
+  // zero-padded image, tiles per image, direct-to-LDS loads per thread that bring in the patch
+  int cR, cWp, ntj, patch_loads;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -130,14 +133,18 @@ struct KCfg {
   using OA = Opnd<AL ? LAY_MN : LAY_K, BM, WM, BK, NT>;
   using OB = Opnd<BL ? LAY_K : LAY_MN, BN, WN, BK, NT>;
   static constexpr int TM = WM / 32, TN = WN / 32, NKI = BK / 16;
-  static constexpr int A_BYTES = OA::BYTES, B_BYTES = OB::BYTES;
+  // AM == 3 keeps its A operand in a patch outside the ring: a stage holds the B tile only
+  static constexpr int A_BYTES = AM == 3 ? 0 : OA::BYTES, B_BYTES = OB::BYTES;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int RING_BYTES = S * STAGE_BYTES;
   static constexpr int EPI_WAVE_BYTES = 32 * (WN * 4 + 16);     // epilogue band, fp32 worst case
   static constexpr int MAIN_BYTES = RING_BYTES + NWAVES * 256;  // + landing pad of the L2 touches
   static constexpr int LDS_BYTES =
       MAIN_BYTES > NWAVES * EPI_WAVE_BYTES ? MAIN_BYTES : NWAVES * EPI_WAVE_BYTES;
-  static constexpr int NLA = OA::NL, NLB = OB::NL;
+  static constexpr int NLA = AM == 3 ? 0 : OA::NL, NLB = OB::NL;
+  // AM == 3: the patch follows the ring and the landing pad, 1024-byte aligned; its size depends
+  // on the convolution's geometry and is added to the dynamic LDS size at launch
+  static constexpr int PATCH_OFF = (MAIN_BYTES + 1023) / 1024 * 1024;
   static constexpr int L = NLA + NLB + 1;   // per wave and k-tile: tile loads + one L2 touch
   static constexpr int WAIT = (S >= 2 ? (S - 2) * L : 0);    // loads allowed in flight at a wait
   static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "wave tile");
@@ -146,11 +153,26 @@ struct KCfg {
   static_assert(!FUSE || (R == 2 && S >= 2), "fusion needs a register double buffer and S>=2");
   // AM: 0 = A is a matrix; 1 = A is gathered from an NHWC image and a k-tile lies inside one
   // filter tap (bk divides the channel count: the tap is the same for all lanes); 2 = gathered,
-  // any channel count that is a multiple of 8 (every lane tracks the tap of its own chunk)
+  // any channel count that is a multiple of 8 (every lane tracks the tap of its own chunk);
+  // 3 = stride-1 convolution with C = BK whose input patch (tile + halo) is loaded into LDS once
+  // and whose filter taps are formed by shifted LDS reads: only the weights stream through the ring
+  static_assert(AM != 3 || (SK == 0 && BL == 0), "patch convolution: RSCK weights, no split-K");
   static_assert(!(AM != 0 && AL == 1), "the convolution gather produces a K-contiguous A tile");
   static_assert(WAIT <= 63, "vmcnt is a 6-bit counter");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
 };
+
+// Dynamic LDS bytes a launch of configuration C needs (host side).
+template <class C>
+inline int dynamic_lds_bytes(const Params& p)
+{
+  if constexpr (C::AM == 3) {
+    const int need = C::PATCH_OFF + p.patch_loads * C::NT * 16;
+    return need > C::LDS_BYTES ? need : C::LDS_BYTES;
+  } else {
+    return C::LDS_BYTES;
+  }
+}
 
 // Per-lane state of the producer side of one operand.
 template <class HW>
@@ -312,8 +334,8 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   }
   LoadState<HW> la, lb;
   // convolution: per-load row geometry of the gathered A tile
-  int ih0[NLA], iw0[NLA];
-  uint32_t coff[NLA];
+  int ih0[NLA > 0 ? NLA : 1], iw0[NLA > 0 ? NLA : 1];
+  uint32_t coff[NLA > 0 ? NLA : 1];
   int cr = 0, cs = 0, cc0 = 0;                // (r, s, c0) of the next k-tile to issue
   bool a_in_k = true;                         // AM == 2: this lane's chunk lies below K
   int a_k8 = 0;                               // AM == 2: k of this lane's chunk within a k-tile
@@ -323,8 +345,32 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     cr = tap / p.cS;
     cs = tap - cr * p.cS;
   }
+  // AM == 3: the tile is BM consecutive positions j of one image's output space laid out with
+  // the padded row length Wp (positions with column >= Q are computed and not stored); for
+  // filter tap (r, s) the A operand is the same patch shifted by r * Wp + s rows
+  int p_img = 0, p_j0 = 0;
+  const uint32_t patch_base = lds0 + C::PATCH_OFF;
   if constexpr (C::AM == 0) {
     la = setup_loader<OA, HW>(Abatch, tm, p.M, p.lda, Kb, nko, q0);
+  } else if constexpr (C::AM == 3) {
+    p_img = tm / p.ntj;
+    p_j0 = (tm - p_img * p.ntj) * BM;
+    la.rsrc = HW::make_rsrc(p.A, (int)p.a_span);
+    la.voff = la.voff_t = la.step = la.kstep = 0;
+    const int rows = BM + (p.cR - 1) * p.cWp + (p.cS - 1);       // patch rows = tile + halo
+    for (int i = 0; i < p.patch_loads; i++) {
+      // 16-byte slot q of the patch: row q / CPR, physical chunk q % CPR (swizzled like any
+      // k-contiguous tile); rows are positions of the padded image, zero outside the image
+      const int q = q0 + i * C::NT;
+      const int row = q / OA::CPR;
+      const int c = (q % OA::CPR) ^ OA::swz(row);
+      const int jj = p_j0 + row;
+      const int ihp = jj / p.cWp;
+      const int ih = ihp - p.cph, iw = jj - ihp * p.cWp - p.cpw;
+      const bool ok = row < rows && (unsigned)ih < (unsigned)p.cH && (unsigned)iw < (unsigned)p.cW;
+      const uint32_t off = (uint32_t)((((p_img * p.cH + ih) * p.cW) + iw) * p.cC * 2 + c * 16);
+      HW::dma16(la.rsrc, ok ? off : 0x80000000u, patch_base + (uint32_t)(i * C::NT + wave * 64) * 16u);
+    }
   } else {
     // implicit GEMM: row m of A is output pixel (img, p, q); a k-tile lies inside one filter tap
     // (r, s) because bk divides C, so a lane's chunk is 16 contiguous bytes of x or padding.
@@ -397,7 +443,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     st_dst = lds0 + (uint32_t)slot * STAGE_BYTES + (uint32_t)wave * 1024u;
     if constexpr (C::AM == 0)
       st_ka = st_live ? (uint32_t)kt * la.kstep : 0x80000000u;
-    else
+    else if constexpr (C::AM != 3)
       st_tap = (uint32_t)(((cr * p.cW + cs) * p.cC + cc0) * 2);
     if constexpr (C::AM == 2) a_in_k = kt * BK + a_k8 < Kb;
     st_kb = st_live ? (uint32_t)kt * lb.kstep : 0x80000000u;
@@ -447,9 +493,22 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   setup_reader<OA>(lane, wm, 0, rdA);
   setup_reader<OB>(lane, wn, A_BYTES, rdB);
   uint32_t curA[OA::NRD], curB[OB::NRD];
+  int tap_r = 0, tap_s = 0, tap_n = 0;        // AM == 3: filter tap of the k-tile read next
   auto set_read_slot = [&](uint32_t sbase) {
+    if constexpr (C::AM == 3) {
+      // one k-tile per tap (C = BK): the fragment rows are the wave's rows shifted by the tap;
+      // the read past the last k-tile (fused pipeline) is pointed at the unshifted rows
+      const int shift = tap_n < nko ? tap_r * p.cWp + tap_s : 0;
+      const int row = wm * WM + (lane & 31) + shift;
 #pragma unroll
-    for (int i = 0; i < OA::NRD; i++) curA[i] = sbase + rdA[i];
+      for (int ki = 0; ki < OA::NRD; ki++)
+        curA[ki] = patch_base + (uint32_t)(row * (BK * 2) + (((2 * ki + (lane >> 5)) ^ OA::swz(row)) * 16));
+      tap_n++;
+      if (++tap_s == p.cS) { tap_s = 0; tap_r++; }
+    } else {
+#pragma unroll
+      for (int i = 0; i < OA::NRD; i++) curA[i] = sbase + rdA[i];
+    }
 #pragma unroll
     for (int i = 0; i < OB::NRD; i++) curB[i] = sbase + rdB[i];
   };
@@ -628,8 +687,17 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       for (int t = 0; t < 32 / RPI; t++) {
         const int r = t * RPI + lane / LPR, c16 = lane % LPR;
         const u32x4 v = HW::lds_read16(ebase + r * RS + c16 * 16);
-        const int m = m0 + j * 32 + r, n = n0 + c16 * (16 / OB);
-        if (m < p.M && n < p.N)
+        int m = m0 + j * 32 + r;
+        const int n = n0 + c16 * (16 / OB);
+        bool row_ok = m < p.M;
+        if constexpr (C::AM == 3) {
+          // position of the padded output space -> output pixel; columns >= Q are not stored
+          const int jj = p_j0 + wm * WM + j * 32 + r;
+          const int pp = jj / p.cWp, qq = jj - pp * p.cWp;
+          row_ok = pp < p.cP && qq < p.cQ;
+          m = (p_img * p.cP + pp) * p.cQ + qq;
+        }
+        if (row_ok && n < p.N)
           HW::global_store16(Cb + ((long)m * p.ldc + n) * OB, v);
       }
     }

@@ -31,7 +31,14 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   const double n_warp = (bm / wm) * (bn / wn);              // N_warp_per_threadblk
   const double n_smem_loop = std::ceil(prob.K / bk);        // N_smem_loop (a partial tile counts)
   const double n_reg_loop = bk / 16.0;                       // N_reg_loop (MFMA k = 16)
-  const double stage_bytes = (bm + bn) * bk * 2.0;          // Bytes_one_smem_loop
+  // Schedule variant 1 of a convolution keeps the input patch of the tile in LDS: the A rows are
+  // loaded once per block, not once per filter tap, so a k-tile brings in 1/taps of them, and
+  // the patch (reading: tile plus half a tile of halo) occupies LDS beside the ring of B tiles.
+  const bool patch = prob.op == ALCOP_OP_CONV2D && s.variant == 1 && prob.conv_C > 0;
+  const double taps = patch ? std::max(1.0, (double)prob.K / prob.conv_C) : 1.0;
+  const double a_rows = bm / taps;                           // A rows fetched per k-tile
+  const double stage_bytes = (a_rows + bn) * bk * 2.0;      // Bytes_one_smem_loop
+  const double lds_use = patch ? S * bn * bk * 2.0 + 1.5 * bm * bk * 2.0 : S * stage_bytes;
   const double frag_bytes = n_warp * (wm + wn) * 16.0 * 2.0; // Bytes_one_reg_loop (LDS reads)
   const double flops_reg_loop = 2.0 * bm * bn * 16.0;        // FLOPs_one_reg_loop
 
@@ -52,7 +59,7 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   // registers).  Reading: registers per lane = accumulators + R fragment sets + 48.
   const double regs = wm * wn / 64.0 + R * (wm / 32.0 + wn / 32.0) * 4.0 + 48.0;
   const double waves_per_simd = std::max(1.0, std::min(8.0, std::floor(dev.regs_per_lane / regs)));
-  double blk_per_cu = std::min(std::floor(dev.lds_bytes / (S * stage_bytes)),
+  double blk_per_cu = std::min(std::floor(dev.lds_bytes / lds_use),
                                std::floor(waves_per_simd * dev.simd_per_cu / n_warp));
   blk_per_cu = std::max(1.0, blk_per_cu);
   blk_per_cu = std::min(blk_per_cu, ceil_div(n_blocks, dev.num_cu));   // no more than exist
@@ -96,7 +103,7 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   const double mats = ceil_div(n_in_batch, tiles);
   const double rows_u = std::min(ntm, std::ceil(std::sqrt(per_mat)));
   const double cols_u = std::min(ntn, ceil_div(per_mat, rows_u));
-  const double workset = (rows_u * bm + cols_u * bn) * bk * 2.0 * mats;
+  const double workset = (rows_u * a_rows + cols_u * bn) * bk * 2.0 * mats;
   const double t_dram = dev.lat_dram + workset / dev.bw_dram;
   const double t_smem_load = std::max(t_llc, t_dram);
 

@@ -12,6 +12,7 @@ struct KernelEntry {
   int dt, bm, bn, bk, wm, wn, stages, reg_stages, fuse, bl, am, al;
   int sk;   // 1: split-K variant (grid.z slices of the reduction axis, fp32 partial tiles)
   int lds_bytes, threads, loads_per_stage;
+  int patch_off;   // am == 3: LDS offset of the input patch (its size is per call)
   hipError_t (*launch)(const Params&, dim3, hipStream_t);
 };
 
@@ -25,6 +26,7 @@ void register_conv(std::vector<KernelEntry>&);
 void register_ta(std::vector<KernelEntry>&);
 void register_conv_krsc(std::vector<KernelEntry>&);
 void register_conv_anyc(std::vector<KernelEntry>&);
+void register_conv_patch(std::vector<KernelEntry>&);
 void register_splitk_gemm(std::vector<KernelEntry>&);
 void register_splitk_conv(std::vector<KernelEntry>&);
 

@@ -14,7 +14,7 @@ namespace alcop {
 template <class C>
 hipError_t launch_emulated(const Params& p, dim3 grid, hipStream_t)
 {
-  emu::run_grid(&emu::mainloop_entry<C>, &p, C::NT, C::LDS_BYTES, grid.x, grid.y, grid.z);
+  emu::run_grid(&emu::mainloop_entry<C>, &p, C::NT, dynamic_lds_bytes<C>(p), grid.x, grid.y, grid.z);
   return hipSuccess;
 }
 
@@ -24,7 +24,7 @@ void add(std::vector<KernelEntry>& t)
 {
   using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK>;
   t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, C::LDS_BYTES, C::NT, C::L,
-                          &launch_emulated<C>});
+                          C::PATCH_OFF, &launch_emulated<C>});
 }
 
 #if EMU_PART == 0
@@ -103,6 +103,12 @@ void emu_part_3(std::vector<KernelEntry>& t)
   add<0, 64, 64, 32, 32, 32, 4, 2, 1, 0, 2>(t);
   add<0, 64, 64, 64, 32, 32, 1, 1, 0, 0, 2>(t);
   add<0, 64, 64, 32, 32, 32, 3, 2, 1, 1, 2>(t);        // ... with KRSC weights
+  add<0, 256, 64, 64, 64, 64, 3, 2, 1, 0, 3>(t);       // input patch resident in LDS
+  add<0, 256, 64, 64, 64, 64, 1, 1, 0, 0, 3>(t);
+  add<0, 128, 64, 64, 64, 32, 2, 2, 0, 0, 3>(t);
+  add<0, 128, 64, 32, 64, 32, 4, 2, 1, 0, 3>(t);
+  add<0, 64, 64, 32, 32, 32, 2, 1, 0, 0, 3>(t);
+  add<1, 128, 64, 64, 64, 32, 3, 2, 1, 0, 3>(t);
 }
 #else
 // the part that is compiled once: the product's sub-table hooks and the test controls
@@ -123,6 +129,7 @@ void register_splitk_gemm(std::vector<KernelEntry>&) {}
 void register_splitk_conv(std::vector<KernelEntry>&) {}
 void register_conv_krsc(std::vector<KernelEntry>&) {}
 void register_conv_anyc(std::vector<KernelEntry>&) {}
+void register_conv_patch(std::vector<KernelEntry>&) {}
 
 static void reduce_entry(const void* p)
 {

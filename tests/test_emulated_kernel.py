@@ -407,3 +407,54 @@ def test_conv_bias_relu_in_the_epilogue():
                         al.sched(128, 64, 64, 64, 32, 3, 2, 1), reads=[x, wt, bias], writes=[y])
         assert not errs, errs[:4]
         assert _exact(y, ref), krsc
+
+
+# ---- convolution with the input patch resident in LDS (schedule variant 1) ---------------------------
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=9, W=7, C=64, K=64, R=3, S=3, pad=(1, 1)),
+    dict(N=1, H=20, W=18, C=64, K=72, R=3, S=3, pad=(1, 1)),      # several tiles per image
+    dict(N=2, H=6, W=10, C=32, K=64, R=5, S=3, pad=(2, 0)),
+    dict(N=1, H=8, W=8, C=64, K=64, R=1, S=1, pad=(0, 0)),
+    dict(N=3, H=5, W=6, C=32, K=64, R=2, S=4, pad=(1, 2)),
+])
+def test_conv_patch_variant_exact_and_in_bounds(geom):
+    g = geom
+    dt = "f16"
+    x = wl.small_ints((g["N"], g["H"], g["W"], g["C"]), dt, 101)
+    w = wl.small_ints((g["R"], g["S"], g["C"], g["K"]), dt, 102)
+    P = g["H"] + 2 * g["pad"][0] - g["R"] + 1
+    Q = g["W"] + 2 * g["pad"][1] - g["S"] + 1
+    ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, (1, 1), g["pad"])
+    prob = al.problem(al.OP_CONV2D, g["N"] * P * Q, g["K"], g["R"] * g["S"] * g["C"], al.F16, al.F16,
+                      conv_C=g["C"])
+    with emu._swapped():
+        scheds = al.alcop_sched_variants(prob)
+        assert scheds and all(s.variant == 1 and al.alcop_sched_supported(prob, s) == al.OK for s in scheds)
+        assert all(s.variant == 0 for s in al.alcop_sched_space(prob))
+    for n, s in enumerate(scheds):
+        for policy in (emu.POLICIES[n % 4], emu.POLICIES[(n + 2) % 4]):
+            y = torch.full((g["N"], P, Q, g["K"]), float("nan"), dtype=torch.float16)
+            errs = emu.call(al.alcop_conv2d_igemm, x, w, y, (1, 1), g["pad"], s,
+                            reads=[x, w], writes=[y], policy=policy)
+            assert not errs, (repr(s), policy, errs[:4])
+            assert _exact(y, ref), (repr(s), policy)
+
+
+def test_conv_patch_variant_is_refused_where_it_does_not_apply():
+    x = wl.small_ints((1, 12, 12, 64), "f16", 103)
+    w = wl.small_ints((3, 3, 64, 64), "f16", 104)
+    s = al.sched(128, 64, 64, 64, 32, 2, 2, 0, variant=1)
+    y = torch.zeros(1, 6, 6, 64, dtype=torch.float16)
+    with pytest.raises(al.AlcopError) as e:                        # stride 2
+        emu.call(al.alcop_conv2d_igemm, x, w, y, (2, 2), (1, 1), s, reads=[x, w], writes=[y])
+    assert e.value.code == al.ERR_SCHED
+    big = wl.small_ints((1, 4, 700, 64), "f16", 105)               # a halo of two 702-pixel rows: too much LDS
+    yb = torch.zeros(1, 4, 700, 64, dtype=torch.float16)
+    with pytest.raises(al.AlcopError) as e:
+        emu.call(al.alcop_conv2d_igemm, big, w, yb, (1, 1), (1, 1), s, reads=[big, w], writes=[yb])
+    assert e.value.code == al.ERR_SCHED
+    with emu._swapped():
+        gemm = al.problem(al.OP_GEMM, 128, 64, 64, al.F16, al.F16)
+        assert al.alcop_sched_supported(gemm, al.sched(128, 64, 64, 64, 32, 2, 2, 0, variant=1)) == al.ERR_SCHED
+        c32 = al.problem(al.OP_CONV2D, 144, 64, 9 * 32, al.F16, al.F16, conv_C=32)
+        assert al.alcop_sched_supported(c32, s) == al.ERR_SCHED     # bk must equal the channel count

@@ -150,7 +150,7 @@ int main(void) {
   printf("%zu %zu %zu\n", sizeof(alcop_sched), sizeof(alcop_problem), sizeof(alcop_epilogue));
   printf("%zu %zu %zu\n", offsetof(alcop_sched, l2_prefetch), offsetof(alcop_problem, transA),
          offsetof(alcop_epilogue, act));
-  printf("%zu %zu\n", offsetof(alcop_problem, conv_C), offsetof(alcop_epilogue, bias));
+  printf("%zu %zu %zu\n", offsetof(alcop_problem, conv_C), offsetof(alcop_epilogue, bias), offsetof(alcop_sched, variant));
   return 0;
 }''')
     exe = tmp_path / "layout"
@@ -159,7 +159,7 @@ int main(void) {
     got = [int(v) for v in out]
     want = [ctypes.sizeof(al.Sched), ctypes.sizeof(al.Problem), ctypes.sizeof(al.Epilogue),
             al.Sched.l2_prefetch.offset, al.Problem.transA.offset, al.Epilogue.act.offset,
-            al.Problem.conv_C.offset, al.Epilogue.bias.offset]
+            al.Problem.conv_C.offset, al.Epilogue.bias.offset, al.Sched.variant.offset]
     assert got == want
 
 
@@ -192,7 +192,7 @@ def test_auto_schedule_is_the_models_top_one_and_cache_round_trip(tmp_path):
         "0 1 1000 1001 768 0 0 1 1 0 : 64 64 32 32 32 2 2 1 1 0\n"      # N % 8 != 0
         "garbage\n")
     assert al.alcop_cache_load(str(f)) == 1
-    assert al.alcop_sched_auto(p).key() == (64, 64, 32, 32, 32, 2, 2, 1, 1, 0)
+    assert al.alcop_sched_auto(p).key() == (64, 64, 32, 32, 32, 2, 2, 1, 1, 0, 0)
     out = tmp_path / "saved.txt"
     n = al.alcop_cache_save(str(out))
     assert n >= 1
@@ -248,7 +248,7 @@ def test_tuning_cache_named_by_the_environment(tmp_path):
             "print(al.alcop_sched_auto(p).key())\n")
     env = dict(os.environ, ALCOP_TUNE_CACHE=str(f), PYTHONPATH=ROOT)
     out = subprocess.check_output([sys.executable, "-c", code], env=env, cwd=ROOT).decode()
-    assert out.strip() == "(64, 64, 32, 32, 32, 2, 2, 1, 1, 0)"
+    assert out.strip() == "(64, 64, 32, 32, 32, 2, 2, 1, 1, 0, 0)"
     env["ALCOP_TUNE_CACHE"] = str(tmp_path / "missing.txt")          # ignored, the model decides
     out = subprocess.check_output([sys.executable, "-c", code], env=env, cwd=ROOT).decode()
-    assert out.strip() != "(64, 64, 32, 32, 32, 2, 2, 1, 1, 0)"
+    assert out.strip() != "(64, 64, 32, 32, 32, 2, 2, 1, 1, 0, 0)"

@@ -132,3 +132,21 @@ def test_library_splitk_model_matches_oracle(shape):
     # over 16 requested -> 3 per slice -> 11 slices
     assert pm.predict_splitk(128, 128, 33 * 64, 1, 2, 128, 128, 64, 64, 64, 3, 2, True, 4)[1] == 4
     assert pm.predict_splitk(128, 128, 33 * 64, 1, 2, 128, 128, 64, 64, 64, 3, 2, True, 16)[1] == 11
+
+
+def test_library_patch_convolution_model_matches_oracle():
+    # conv 56x56x64 -> 64, 3x3: 9 taps; variant 1 fetches the A rows once per block
+    M, N, K, C = 32 * 56 * 56, 64, 576, 64
+    prob = al.problem(al.OP_CONV2D, M, N, K, al.F16, al.F16, conv_C=C)
+    seen = 0
+    for s in al.alcop_sched_space(prob) + al.alcop_sched_variants(prob):
+        us, terms = al.alcop_model_predict(prob, s, 0)
+        r = pm.predict(M, N, K, 1, 2, s.bm, s.bn, s.bk, s.wm, s.wn, s.stages, s.reg_stages,
+                       bool(s.fuse_inner), patch_taps=9 if s.variant == 1 else 0)
+        assert us == pytest.approx(r["t_kernel"], rel=1e-12)
+        if s.variant == 1:
+            seen += 1
+            # less traffic per k-tile than the default kernel of the same schedule
+            plain = al.sched(s.bm, s.bn, s.bk, s.wm, s.wn, s.stages, s.reg_stages, s.fuse_inner)
+            assert terms[5] < al.alcop_model_predict(prob, plain, 0)[1][5]
+    assert seen >= 6
