@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--splitk-report", action="store_true",
                     help="time the split-K entry points against the best unsplit schedule on the "
                          "configurations with fewer output tiles than compute units; prints one JSON object")
+    ap.add_argument("--conv-patch-report", action="store_true",
+                    help="conv56 / conv14: exhaustive search over the default kernels and over the "
+                         "LDS-resident-patch variants (schedule variant 1); prints one JSON object")
     ap.add_argument("--sched", default=None,
                     help="bm,bn,bk,wm,wn,S,R,F[,raster]: time this schedule only, no tuning (for profiling)")
     a = ap.parse_args()
@@ -72,6 +75,22 @@ def main():
 
     if a.splitk_report:
         print(json.dumps(splitk_report(al, wl, torch, dev, stream)))
+        return
+
+    if a.conv_patch_report:
+        rep = {}
+        for name in ("conv56", "conv14"):
+            prob, Ad, Bd, Cd, conv, flops, byts = _setup(al, wl, torch, dev, name)
+            base = al.alcop_tune(prob, Ad, Bd, Cd, top_k=0, model=0, iters=30, conv=conv)
+            both = al.alcop_tune(prob, Ad, Bd, Cd, top_k=0, model=0, iters=30, conv=conv, variants=True)
+            var = [(s, us) for s, _, us in both.log if s.variant == 1]
+            best_var = min(var, key=lambda t: t[1]) if var else (None, float("nan"))
+            rep[name] = {"default_best_us": round(base.best_us, 2), "default_best": repr(base.best),
+                         "variant_best_us": round(best_var[1], 2), "variant_best": repr(best_var[0]),
+                         "speedup": round(base.best_us / best_var[1], 3),
+                         "tflops_variant": round(flops / best_var[1] / 1e6, 1),
+                         "variants": [[repr(s), round(us, 2)] for s, us in sorted(var, key=lambda t: t[1])[:8]]}
+        print(json.dumps(rep))
         return
 
     if a.sched:
