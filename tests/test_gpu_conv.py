@@ -41,7 +41,9 @@ def test_integers_bit_exact_every_schedule(geom):
     x = wl.small_ints((g["N"], g["H"], g["W"], g["C"]), "f16", 301)
     w = wl.small_ints((g["R"], g["S"], g["C"], g["K"]), "f16", 302)
     ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, g["stride"], g["pad"])
-    scheds = feasible(conv_problem(x, w, g["stride"], g["pad"]))
+    # schedules whose k-tile divides the channel count (one filter tap per k-tile); the others
+    # use the per-lane gather and have their own test file
+    scheds = [s for s in feasible(conv_problem(x, w, g["stride"], g["pad"])) if g["C"] % s.bk == 0]
     assert scheds
     for s in scheds:
         got = to_f64(run_conv(x, w, "f32", s, g["stride"], g["pad"]))
