@@ -458,3 +458,18 @@ def test_conv_patch_variant_is_refused_where_it_does_not_apply():
         assert al.alcop_sched_supported(gemm, al.sched(128, 64, 64, 64, 32, 2, 2, 0, variant=1)) == al.ERR_SCHED
         c32 = al.problem(al.OP_CONV2D, 144, 64, 9 * 32, al.F16, al.F16, conv_C=32)
         assert al.alcop_sched_supported(c32, s) == al.ERR_SCHED     # bk must equal the channel count
+
+
+def test_conv_patch_variant_bf16_bias_relu_several_column_tiles():
+    x = wl.small_ints((2, 7, 9, 64), "bf16", 111)
+    w = wl.small_ints((3, 3, 64, 136), "bf16", 112)
+    bias = (torch.arange(136, dtype=torch.float32) % 5) - 2
+    ref = oracle.epilogue(oracle.conv2d(wl.bits(x), wl.bits(w), oracle.BF16, (1, 1), (1, 1)).reshape(-1, 136),
+                          2.0, bias.double().numpy(), 1).reshape(2, 7, 9, 136)
+    for raster in (1, 0):
+        y = torch.full((2, 7, 9, 136), float("nan"), dtype=torch.float32)
+        s = al.sched(128, 64, 64, 64, 32, 3, 2, 1, raster, 0, 1)
+        errs = emu.call(al.alcop_conv2d_igemm_fused, x, w, y, (1, 1), (1, 1), 2.0, bias, 1, False, s,
+                        reads=[x, w, bias], writes=[y], policy=(1, 1))
+        assert not errs, errs[:4]
+        assert _exact(y, ref), raster
