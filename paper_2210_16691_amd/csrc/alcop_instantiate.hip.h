@@ -8,6 +8,7 @@ namespace alcop {
 template <class C>
 hipError_t launch_instance(const Params& p, dim3 grid, hipStream_t st)
 {
+  // (two threads making the first launch together both set the attribute: harmless)
   static bool attr_set = false;
   if (!attr_set) {
     // LDS rings above the default 64 KB per-block limit need an explicit opt-in (the patch
