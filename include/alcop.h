@@ -198,7 +198,8 @@ int alcop_conv2d_igemm_fused(const void* x, const void* w, void* y, int N, int H
  *     loop through the workspace), or 0 = the model's choice.
  *   sched: one of the split-K variants built into the library (alcop_splitk_auto returns the
  *     model's pick), or NULL / zero = that pick.  l2_prefetch must be 0.
- *   batch = 1 with strides 0 is a plain GEMM.  A stored K x M (transA) is not built: UNSUPPORTED.
+ *   batch = 1 with strides 0 is a plain GEMM.  Layouts as for alcop_gemm (variants are built for
+ *     A stored K x M only together with B stored K x N: the weight-gradient product X^T . dY).
  * Errors as for alcop_gemm; ALCOP_ERR_SIZE also if the workspace is too small.
  */
 size_t alcop_splitk_workspace_bytes(int batch, int M, int N, int split);

@@ -246,23 +246,25 @@ def alcop_splitk_workspace_bytes(batch: int, M: int, N: int, split: int) -> int:
 
 
 def alcop_gemm_splitk(A, B, C, split, workspace, sched=None, alpha=1.0, bias=None, act=0,
-                      transB=False, stream=None):
+                      transB=False, stream=None, transA=False):
     """C = act(alpha * A.B + bias) with the reduction axis cut into `split` slices (0 = the model's
     choice).  A, B, C are 2-D (GEMM) or 3-D (batched) tensors; `workspace` is a tensor of at least
     alcop_splitk_workspace_bytes(batch, M, N, split) bytes that the call overwrites."""
     if A.dim() == 2:
-        b, (M, K), sA, sB, sC = 1, A.shape, 0, 0, 0
+        b, sA, sB, sC = 1, 0, 0, 0
+        K, M = A.shape if transA else A.shape[::-1]
         N = B.shape[0] if transB else B.shape[1]
         lda, ldb, ldc = A.stride(0), B.stride(0), C.stride(0)
     else:
-        b, M, K = A.shape
+        b = A.shape[0]
+        K, M = A.shape[1:] if transA else A.shape[:0:-1]
         N = B.shape[1] if transB else B.shape[2]
         lda, ldb, ldc = A.stride(1), B.stride(1), C.stride(1)
         sA, sB, sC = A.stride(0), B.stride(0), C.stride(0)
     e = _epilogue(alpha, bias, act)
     rc = lib().alcop_gemm_splitk(_ptr(A), _ptr(B), _ptr(C), b, M, N, K, lda, ldb, ldc, sA, sB, sC,
-                                 0, int(transB), _dtype_code(A), _dtype_code(C), ctypes.byref(e),
-                                 _sp(sched), int(split), _ptr(workspace),
+                                 int(transA), int(transB), _dtype_code(A), _dtype_code(C),
+                                 ctypes.byref(e), _sp(sched), int(split), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "alcop_gemm_splitk")
     return C

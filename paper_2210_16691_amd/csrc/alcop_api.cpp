@@ -713,9 +713,8 @@ int alcop_gemm_splitk(const void* A, const void* B, void* C, int batch, int M, i
                       const alcop_epilogue* ep, const alcop_sched* sched, int split,
                       void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-  if (transA) return ALCOP_ERR_UNSUPPORTED;
   Call c = gemm_call(batch > 1 ? ALCOP_OP_BMM : ALCOP_OP_GEMM, A, B, C, batch, M, N, K, lda, ldb, ldc,
-                     strideA, strideB, strideC, 0, transB, in, out);
+                     strideA, strideB, strideC, transA, transB, in, out);
   if (ep) {
     c.alpha = ep->alpha;
     c.bias = ep->bias;
@@ -749,7 +748,6 @@ int alcop_tune_splitk(const alcop_problem* prob, const void* A, const void* B, v
   Call c;
   int rc = call_of_problem(prob, A, B, C, lda, ldb, ldc, strideA, strideB, strideC, conv, &c);
   if (rc) return rc;
-  if (c.transA) return ALCOP_ERR_UNSUPPORTED;
   rc = check_call(c);
   if (rc) return rc;
   const alcop_problem p = problem_of(c);
@@ -817,7 +815,6 @@ int alcop_splitk_auto(const alcop_problem* prob, int split, alcop_sched* sched_o
   if (!prob || !sched_out || !split_out) return ALCOP_ERR_NULL;
   int rc = check_problem(*prob);
   if (rc) return rc;
-  if (prob->transA) return ALCOP_ERR_UNSUPPORTED;
   if (split < 0 || split > 64) return ALCOP_ERR_SHAPE;
   rc = auto_splitk(*prob, split, sched_out, split_out);
   if (rc) return rc;

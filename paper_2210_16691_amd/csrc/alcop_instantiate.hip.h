@@ -88,6 +88,14 @@ void add_instance(std::vector<KernelEntry>& t)
   add_instance<DT, BM, BN, BK, WM, WN, 3, 2, 1, BL, AM, 0, 1>(T);      \
   add_instance<DT, BM, BN, BK, WM, WN, 4, 2, 1, BL, AM, 0, 1>(T);
 
+// The same for A stored K x M (the layout of a weight-gradient product X^T . dY, whose output is
+// small and whose reduction axis is the long batch axis).
+#define ALCOP_SPLITK_PIPES_TA(T, DT, BM, BN, BK, WM, WN, BL)          \
+  add_instance<DT, BM, BN, BK, WM, WN, 1, 1, 0, BL, 0, 1, 1>(T);       \
+  add_instance<DT, BM, BN, BK, WM, WN, 2, 2, 1, BL, 0, 1, 1>(T);       \
+  add_instance<DT, BM, BN, BK, WM, WN, 3, 2, 1, BL, 0, 1, 1>(T);       \
+  add_instance<DT, BM, BN, BK, WM, WN, 4, 2, 1, BL, 0, 1, 1>(T);
+
 #define ALCOP_BOTH_BK(MACRO, T, DT, BM, BN, WM, WN, BL, AM) \
   MACRO(T, DT, BM, BN, 32, WM, WN, BL, AM)                  \
   MACRO(T, DT, BM, BN, 64, WM, WN, BL, AM)

@@ -83,6 +83,8 @@ void emu_part_4(std::vector<KernelEntry>& t)
   add<0, 128, 64, 64, 64, 32, 3, 2, 1, 0, 1, 0, 1>(t);    // convolution
   add<0, 64, 64, 64, 32, 32, 1, 1, 0, 0, 1, 0, 1>(t);
   add<0, 64, 128, 64, 32, 64, 4, 2, 1, 0, 1, 0, 1>(t);
+  add<0, 128, 128, 64, 64, 64, 3, 2, 1, 0, 0, 1, 1>(t);   // A stored K x M
+  add<1, 64, 64, 64, 32, 32, 2, 2, 1, 0, 0, 1, 1>(t);
 }
 #elif EMU_PART == 3
 void emu_part_3(std::vector<KernelEntry>& t)

@@ -473,3 +473,18 @@ def test_conv_patch_variant_bf16_bias_relu_several_column_tiles():
                         reads=[x, w, bias], writes=[y], policy=(1, 1))
         assert not errs, errs[:4]
         assert _exact(y, ref), raster
+
+
+def test_splitk_weight_gradient_layout_a_stored_k_by_m():
+    # dW = X^T . dY: X is [tokens, in], dY is [tokens, out]; small output, long reduction axis
+    tokens, fin, fout = 8 * 64 + 40, 136, 72
+    X = wl.small_ints((tokens, fin), "f16", 121)
+    dY = wl.small_ints((tokens, fout), "f16", 122)
+    ref = oracle.gemm(wl.bits(X.t().contiguous()), wl.bits(dY), oracle.F16)
+    for split in (3, 9):
+        dW = torch.full((fin, fout), float("nan"), dtype=torch.float32)
+        ws = _ws(1, fin, fout, split)
+        errs = emu.call(al.alcop_gemm_splitk, X, dY, dW, split, ws, al.sched(128, 128, 64, 64, 64, 3, 2, 1),
+                        transA=True, reads=[X, dY], writes=[dW, ws], policy=emu.POLICIES[split % 4])
+        assert not errs, errs[:4]
+        assert _exact(dW, ref), split

@@ -152,3 +152,22 @@ def test_tuner_over_variants_and_slices():
     al.alcop_gemm_splitk(Ad, Bd, C, split, ws, r.best)
     torch.cuda.synchronize()
     assert_close(to_f64(C), oracle.gemm(wl.bits(A), wl.bits(B), ODT[cfg["dtype"]]), "tuned split-K")
+
+
+def test_weight_gradient_layout_a_stored_k_by_m():
+    # dW = X^T . dY with X [tokens, in] and dY [tokens, out]: A stored K x M, B stored K x N
+    tokens, fin, fout = 8 * 64 + 40, 136, 72
+    for dt in ("f16", "bf16"):
+        X = wl.small_ints((tokens, fin), dt, 741)
+        dY = wl.small_ints((tokens, fout), dt, 742)
+        ref = oracle.gemm(wl.bits(X.t().contiguous()), wl.bits(dY), ODT[dt])
+        prob = al.problem(al.OP_GEMM, fin, fout, tokens, al.F16 if dt == "f16" else al.BF16, al.F32, transA=True)
+        scheds = al.alcop_splitk_space(prob)
+        assert len(scheds) >= 6
+        Xd, Yd = X.to(DEV), dY.to(DEV)
+        for s in scheds:
+            for split in (3, 9):
+                dW = torch.full((fin, fout), float("nan"), dtype=torch.float32, device=DEV)
+                al.alcop_gemm_splitk(Xd, Yd, dW, split, _ws(1, fin, fout, split), s, transA=True)
+                torch.cuda.synchronize()
+                assert np.array_equal(to_f64(dW), ref), (dt, repr(s), split)

@@ -225,7 +225,9 @@ def test_splitk_space_model_pick_and_argument_checks():
     call = lambda tA, split, ws, nbytes: L.alcop_gemm_splitk(
         fake, fake, fake, 1, 128, 64, 512, 512, 64, 64, 0, 0, 0, tA, 0, 0, 0, None, None, split,
         ws, nbytes, None)
-    assert call(1, 2, fake, 1 << 20) == al.ERR_UNSUPPORTED
+    # A stored K x M together with B stored N x K: no split-K variant is built for that pair
+    assert L.alcop_gemm_splitk(fake, fake, fake, 1, 128, 64, 512, 128, 512, 64, 0, 0, 0, 1, 1, 0, 0,
+                               None, None, 2, fake, 1 << 20, None) == al.ERR_SCHED
     assert call(0, 2, None, 1 << 20) == al.ERR_NULL
     assert call(0, 2, ctypes.c_void_p(0x10004), 1 << 20) == al.ERR_ALIGN
     assert call(0, -1, fake, 1 << 20) == al.ERR_SHAPE
