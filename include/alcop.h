@@ -271,11 +271,15 @@ int alcop_sched_supported(const alcop_problem* prob /* host */, const alcop_sche
 int alcop_sched_space(const alcop_problem* prob /* host */, alcop_sched* out /* host */, int cap);
 
 /*
- * The schedule variants (alcop_sched.variant != 0) built for the problem: kernels whose
- * feasibility depends on more than the problem description - for a convolution the variant with
- * the input patch resident in LDS, which also needs stride 1 and a patch that fits the LDS.
- * alcop_sched_supported only checks that such a kernel exists; the launch (or the tuner) checks
- * the rest.  A NULL / zero schedule never resolves to a variant unless the tuner chose it.
+ * The kernels outside the default space built for the problem.  They run when a caller names
+ * them or asks the tuner for them (alcop_tune with variants = 1); a NULL / zero schedule never
+ * resolves to one unless the tuner chose it.  They are
+ *   - the schedule variants (alcop_sched.variant != 0), whose feasibility depends on more than the
+ *     problem description: for a convolution the variant with the input patch resident in LDS,
+ *     which also needs stride 1 and a patch that fits the LDS (alcop_sched_supported only checks
+ *     that such a kernel exists; the launch or the tuner checks the rest);
+ *   - the kernels with bk = 128: half as many block-wide synchronisations per unit of work, but
+ *     two stages of a 128 x 128 tile already fill 128 KB of LDS.
  */
 int alcop_sched_variants(const alcop_problem* prob /* host */, alcop_sched* out /* host */, int cap);
 
@@ -301,9 +305,9 @@ int alcop_model_predict(const alcop_problem* prob /* host */, const alcop_sched*
  *              is model 0 and which is refitted after every timed trial; the next trial is the
  *              untried schedule with the lowest corrected prediction;
  *          3 = no model: schedules in table order (the paper's grid search baseline).
- *   variants: 0 = candidates are the default kernels (alcop_sched_space); 1 = also the schedule
- *          variants that depend on the call's geometry (alcop_sched_variants), those that this
- *          call cannot use being pruned.
+ *   variants: 0 = candidates are the default kernels (alcop_sched_space); 1 = also the kernels
+ *          outside the default space (alcop_sched_variants), those that this call cannot use
+ *          being pruned.
  *   For conv problems pass x as A, w as B, y as C and the geometry in `conv` (host; 11 ints:
  *   N,H,W,C,K,R,S,stride_h,stride_w,pad_h,pad_w), else conv = NULL and lda/ldb/ldc/strides
  *   as for alcop_bmm (batch 1 for GEMM).

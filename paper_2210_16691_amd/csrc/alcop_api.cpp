@@ -32,6 +32,7 @@ const std::vector<KernelEntry>& registry()
     register_conv_krsc(t);
     register_conv_anyc(t);
     register_conv_patch(t);
+    register_bk128(t);
     register_splitk_gemm(t);
     register_splitk_conv(t);
     return t;
@@ -145,16 +146,21 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
 // latencies of matrix work at any tile size).
 int default_l2_prefetch(int bk) { return 256 / bk; }
 
-// variants: 0 = the default kernels; 1 = also the schedule variants whose feasibility depends
-// on the call, not only on the problem description (the patch convolution); 2 = only those.
+// Kernels outside the default schedule space: offered to a caller who names them or asks the
+// tuner for them, never picked by the model on its own.  These are the patch convolution (its
+// feasibility depends on the call, not only on the problem description) and the kernels with a
+// k-tile of 128 (two stages of a 128 x 128 tile fill the LDS: a trade the tuner should measure).
+bool opt_in(const KernelEntry& e) { return e.am == 3 || e.bk == 128; }
+
+// variants: 0 = the default kernels; 1 = also the opt-in kernels; 2 = only those.
 std::vector<alcop_sched> space_of(const alcop_problem& p, int sk = 0, int variants = 0)
 {
   std::vector<alcop_sched> v;
   for (const KernelEntry& e : registry())
     if (e.sk == sk && e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) &&
         e.al == (p.transA ? 1 : 0) &&
-        ((variants != 2 && e.am == a_mode(p, e.bk, 0)) ||
-         (variants != 0 && e.am == 3 && p.op == ALCOP_OP_CONV2D && p.conv_C == e.bk)))
+        (e.am == 3 ? (p.op == ALCOP_OP_CONV2D && p.conv_C == e.bk) : e.am == a_mode(p, e.bk, 0)) &&
+        (variants == 1 || (variants == 2) == opt_in(e)))
     {
       v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1, 0,
                               e.am == 3 ? 1 : 0});

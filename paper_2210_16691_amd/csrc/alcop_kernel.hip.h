@@ -21,7 +21,8 @@
 // applied on the source side by choosing which 16-byte chunk of the global tile each lane
 // fetches (the paper applies shared-memory swizzling to all its kernels, Sec. 6.1).
 //   K-contiguous tile (A stored M x K, B stored N x K): rows of BK halves, CPR = BK/8 chunks per
-//     row, physical chunk = logical chunk XOR ((row/2) mod CPR); read with ds_read_b128.
+//     row, physical chunk = logical chunk XOR ((row/2) mod CPR) (XOR (row mod CPR) for the
+//     256-byte rows of BK = 128); read with ds_read_b128.
 //   M/N-contiguous tile (A stored K x M, B stored K x N): one row per k, physical chunk =
 //     logical chunk XOR (((k/RPB) mod min(4,BX/32)) << 2); read with ds_read_b64_tr_b16,
 //     which hands each lane 4 consecutive k of one column (and runs at ~2x the LDS bandwidth
@@ -108,11 +109,15 @@ struct Opnd {
   // 128-byte lines (or parts of lines) in the k-slice of one tile, for the L2 touches
   static constexpr int LINES = LAY == LAY_K ? BX : BK * ((BX * 2) / 128);
   static_assert(BYTES % (NT * 16) == 0, "loads per thread");
-  static_assert(LAY == LAY_K ? (RSTEP % 2 == 0 && (RSTEP / 2) % CPR == 0)
+  // a k-contiguous row of 16 chunks (BK = 128) spans all 64 banks, so consecutive rows must
+  // differ; shorter rows share a 256-byte bank line in pairs and differ per pair
+  static constexpr bool WIDE = LAY == LAY_K && CPR >= 16;
+  static_assert(LAY == LAY_K ? (WIDE ? RSTEP % CPR == 0 : (RSTEP % 2 == 0 && (RSTEP / 2) % CPR == 0))
                              : (RSTEP % (4 * RPB) == 0), "swizzle period");
   // logical 16-byte chunk -> physical chunk within LDS row `row`
   __device__ static __forceinline__ int swz(int row)
   {
+    if constexpr (WIDE) return row % CPR;
     return LAY == LAY_K ? ((row >> 1) % CPR) : (((row / RPB) % GM) << 2);
   }
 };
@@ -148,7 +153,7 @@ struct KCfg {
   static constexpr int L = NLA + NLB + 1;   // per wave and k-tile: tile loads + one L2 touch
   static constexpr int WAIT = (S >= 2 ? (S - 2) * L : 0);    // loads allowed in flight at a wait
   static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "wave tile");
-  static_assert(BK == 32 || BK == 64, "bk");
+  static_assert(BK == 32 || BK == 64 || BK == 128, "bk");
   static_assert(S >= 1 && S <= 4 && (R == 1 || R == 2), "stages");
   static_assert(!FUSE || (R == 2 && S >= 2), "fusion needs a register double buffer and S>=2");
   // AM: 0 = A is a matrix; 1 = A is gathered from an NHWC image and a k-tile lies inside one

@@ -27,6 +27,7 @@ void register_ta(std::vector<KernelEntry>&);
 void register_conv_krsc(std::vector<KernelEntry>&);
 void register_conv_anyc(std::vector<KernelEntry>&);
 void register_conv_patch(std::vector<KernelEntry>&);
+void register_bk128(std::vector<KernelEntry>&);
 void register_splitk_gemm(std::vector<KernelEntry>&);
 void register_splitk_conv(std::vector<KernelEntry>&);
 

@@ -54,6 +54,12 @@ void emu_part_1(std::vector<KernelEntry>& t)
   add<0, 64, 128, 64, 32, 64, 3, 2, 1, 0, 0>(t);
   add<1, 128, 128, 64, 64, 64, 3, 2, 1, 0, 0>(t);      // bf16
   add<1, 64, 64, 32, 32, 32, 2, 1, 0, 0, 0>(t);
+  add<0, 128, 128, 128, 64, 64, 2, 2, 1, 0, 0>(t);     // k-tile of 128
+  add<0, 128, 128, 128, 64, 64, 1, 1, 0, 0, 0>(t);
+  add<0, 64, 64, 128, 32, 32, 4, 2, 1, 0, 0>(t);
+  add<0, 128, 64, 128, 64, 32, 2, 1, 0, 0, 0>(t);
+  add<1, 128, 128, 128, 64, 64, 2, 2, 0, 1, 0>(t);     // ... B stored N x K, bf16
+  add<0, 64, 64, 128, 32, 32, 3, 2, 1, 1, 0>(t);
 }
 #elif EMU_PART == 2
 void emu_part_2(std::vector<KernelEntry>& t)
@@ -132,6 +138,7 @@ void register_splitk_conv(std::vector<KernelEntry>&) {}
 void register_conv_krsc(std::vector<KernelEntry>&) {}
 void register_conv_anyc(std::vector<KernelEntry>&) {}
 void register_conv_patch(std::vector<KernelEntry>&) {}
+void register_bk128(std::vector<KernelEntry>&) {}
 
 static void reduce_entry(const void* p)
 {

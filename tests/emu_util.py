@@ -88,7 +88,9 @@ def call(fn, *args, reads=(), writes=(), policy=(1, 0), mutation=0, **kw):
     return ["%d errors" % n] + buf.value.decode().splitlines()
 
 
-def space(prob):
-    """Schedules the emulated library holds for a problem (a sample of the product's)."""
+def space(prob, opt_in=False):
+    """Schedules the emulated library holds for a problem (a sample of the product's); with opt_in
+    also the kernels outside the default space."""
     with _swapped():
-        return [s for s in al.alcop_sched_space(prob) if al.alcop_sched_supported(prob, s) == al.OK]
+        found = al.alcop_sched_space(prob) + (al.alcop_sched_variants(prob) if opt_in else [])
+        return [s for s in found if al.alcop_sched_supported(prob, s) == al.OK]

@@ -69,7 +69,7 @@ def _gemm_case(dt, transA, transB, s, M, N, K, policy, out="f16", seed=0, mutati
                                                ("bf16", 0, 0), ("bf16", 0, 1), ("bf16", 1, 1)])
 def test_gemm_exact_and_in_bounds_every_emulated_schedule(dt, transA, transB):
     prob = al.problem(al.OP_GEMM, 512, 512, 512, ADT[dt], ADT[dt], transB=bool(transB), transA=bool(transA))
-    scheds = emu.space(prob)
+    scheds = emu.space(prob, opt_in=True)          # includes the k-tile-128 kernels
     assert scheds
     for n, s in enumerate(scheds):
         # two row tiles (the second ragged), a ragged column tile, three k-tiles and a partial one
@@ -488,3 +488,12 @@ def test_splitk_weight_gradient_layout_a_stored_k_by_m():
                         transA=True, reads=[X, dY], writes=[dW, ws], policy=emu.POLICIES[split % 4])
         assert not errs, errs[:4]
         assert _exact(dW, ref), split
+
+
+def test_k_tile_of_128_all_policies_and_l2_touches():
+    for transB, s in ((0, al.sched(128, 128, 128, 64, 64, 2, 2, 1)), (1, al.sched(64, 64, 128, 32, 32, 3, 2, 1)),
+                      (0, al.sched(64, 64, 128, 32, 32, 4, 2, 1, 1, 2))):
+        for policy in emu.POLICIES:
+            errs, ok = _gemm_case("f16", 0, transB, s, 2 * s.bm - 24, s.bn + 8, 5 * 128 + (0 if s.l2_prefetch else 40),
+                                  policy, out="f32")
+            assert not errs and ok, (repr(s), policy, errs[:4])
