@@ -19,10 +19,11 @@
  *
  * Conventions shared by every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never
- *     allocates, frees or copies device memory.  Host pointers are marked "host".
+ *     allocates, frees or copies device memory (the split-K entry points take their scratch
+ *     memory as a workspace argument).  Host pointers are marked "host".
  *   - Calls enqueue work on the given HIP stream (a hipStream_t passed as void*; NULL is the
- *     default stream) and return without synchronising.  alcop_tune is the one exception:
- *     it synchronises the stream in order to time its trials.
+ *     default stream) and return without synchronising.  alcop_tune, alcop_tune_splitk and
+ *     alcop_time are the exceptions: they synchronise the stream in order to time launches.
  *   - Return value: ALCOP_OK (0) or a negative alcop_status.  Nothing is launched when an
  *     error is returned.  No entry point throws or aborts.
  *   - Element types: inputs are IEEE binary16 (ALCOP_F16) or bfloat16 (ALCOP_BF16); products
@@ -52,20 +53,21 @@ typedef enum {
   ALCOP_ERR_NULL = -1,        /* a required pointer is NULL                                  */
   ALCOP_ERR_DTYPE = -2,       /* unsupported input / output element type                     */
   ALCOP_ERR_ALIGN = -3,       /* pointer, leading dimension or stride not aligned as stated  */
-  ALCOP_ERR_SHAPE = -4,       /* non-positive size, K or N not a multiple of 8, conv C % bk   */
+  ALCOP_ERR_SHAPE = -4,       /* non-positive size, K or N (conv: C) not a multiple of 8     */
   ALCOP_ERR_SCHED = -5,       /* schedule infeasible: no such kernel, LDS or wait-counter    */
                               /* limit exceeded, fuse_inner without reg_stages=2/stages>=2   */
   ALCOP_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch                          */
   ALCOP_ERR_UNSUPPORTED = -7, /* valid request outside what is built (e.g. an unknown act)   */
-  ALCOP_ERR_SIZE = -8,        /* an operand spans 2 GiB or more                              */
+  ALCOP_ERR_SIZE = -8,        /* an operand spans 2 GiB or more; a workspace is too small    */
   ALCOP_ERR_IO = -9           /* a cache file could not be opened, read or written           */
 } alcop_status;
 
 /*
  * Schedule parameters: the knobs the paper's tuner searches (tile sizes and per-buffer
  * stage counts, Sec. 4.1 step 1 and Sec. 6.1).  A NULL schedule pointer, or bm == 0, asks
- * the library to pick: the entry with the lowest predicted latency under the static model
- * among the feasible built kernels.
+ * the library to pick: the schedule a tuning run left in the cache for this problem, else the
+ * entry with the lowest predicted latency under the static model among the feasible kernels
+ * of the default space.
  */
 typedef struct {
   int bm, bn, bk;     /* block tile of C (bm x bn) and reduction step bk                    */
