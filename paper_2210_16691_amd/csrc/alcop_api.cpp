@@ -33,6 +33,8 @@ const std::vector<KernelEntry>& registry()
     register_conv_anyc(t);
     register_conv_patch(t);
     register_bk128(t);
+    register_deep(t);
+    register_pf(t);
     register_splitk_gemm(t);
     register_splitk_conv(t);
     return t;
@@ -94,7 +96,8 @@ const KernelEntry* find_entry(const alcop_problem& p, const alcop_sched& s, int 
     if (e.sk == sk && e.dt == (int)p.in && e.bl == (p.transB ? 1 : 0) && e.al == (p.transA ? 1 : 0) &&
         e.am == am && e.bm == s.bm &&
         e.bn == s.bn && e.bk == s.bk && e.wm == s.wm && e.wn == s.wn && e.stages == s.stages &&
-        e.reg_stages == s.reg_stages && e.fuse == (s.fuse_inner ? 1 : 0))
+        e.reg_stages == s.reg_stages && e.fuse == (s.fuse_inner ? 1 : 0) &&
+        e.pf == (s.l2_prefetch > 0 ? 1 : 0))
       return &e;
   return nullptr;
 }
@@ -121,8 +124,11 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
 {
   int rc = check_problem(p);
   if (rc) return rc;
-  if (s.stages < 1 || s.stages > 4 || s.reg_stages < 1 || s.reg_stages > 2) return ALCOP_ERR_SCHED;
-  if (s.fuse_inner && (s.reg_stages != 2 || s.stages < 2)) return ALCOP_ERR_SCHED;
+  if (s.stages < 1 || s.stages > 4 || s.reg_stages < 1 || s.reg_stages > 4) return ALCOP_ERR_SCHED;
+  if (s.fuse_inner && (s.reg_stages < 2 || s.stages < 2)) return ALCOP_ERR_SCHED;
+  // more than two register stages: only the fused pipeline, and its R-1 fragments in flight
+  // must not reach beyond the next k-tile
+  if (s.reg_stages > 2 && (!s.fuse_inner || (s.reg_stages - 1) * 16 > s.bk)) return ALCOP_ERR_SCHED;
   if (s.raster != 0 && s.raster != 1) return ALCOP_ERR_SCHED;
   if (s.l2_prefetch < 0 || s.l2_prefetch > 64 || (s.l2_prefetch > 0 && s.raster != 1))
     return ALCOP_ERR_SCHED;
@@ -162,12 +168,9 @@ std::vector<alcop_sched> space_of(const alcop_problem& p, int sk = 0, int varian
         (e.am == 3 ? (p.op == ALCOP_OP_CONV2D && p.conv_C == e.bk) : e.am == a_mode(p, e.bk, 0)) &&
         (variants == 1 || (variants == 2) == opt_in(e)))
     {
-      v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1, 0,
-                              e.am == 3 ? 1 : 0});
-      // the fused multi-level kernels are also offered with the third (HBM -> L2) level on
-      if (e.fuse && e.am == 0 && sk == 0)
-        v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1,
-                                default_l2_prefetch(e.bk)});
+      // a kernel with the third (HBM -> L2) level is offered with that level on
+      v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1,
+                              e.pf ? default_l2_prefetch(e.bk) : 0, e.am == 3 ? 1 : 0});
     }
   return v;
 }

@@ -23,25 +23,27 @@ hipError_t launch_instance(const Params& p, dim3 grid, hipStream_t st)
   return hipGetLastError();
 }
 
-constexpr bool instance_feasible(int bm, int bn, int bk, int wm, int wn, int s, int r, int f)
+constexpr bool instance_feasible(int bm, int bn, int bk, int wm, int wn, int s, int r, int f,
+                                 int pf = 0)
 {
   const int nt = (bm / wm) * (bn / wn) * 64;
   const int a = bm * bk * 2, b = bn * bk * 2;
   if (a % (nt * 16) || b % (nt * 16)) return false;
   if (s * (a + b) + (nt / 64) * 256 > 160 * 1024) return false;
-  if (f && (r != 2 || s < 2)) return false;
-  const int l = (a + b) / (nt * 16) + 1;
+  if (f && (r < 2 || s < 2)) return false;
+  if (r > 2 && (!f || (r - 1) * 16 > bk)) return false;
+  const int l = (a + b) / (nt * 16) + pf;
   if (s >= 2 && (s - 2) * l > 63) return false;
   return true;
 }
 
 template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int R, int F, int BL, int AM,
-          int AL = 0, int SK = 0>
+          int AL = 0, int SK = 0, int PF = 0>
 void add_instance(std::vector<KernelEntry>& t)
 {
-  if constexpr (instance_feasible(BM, BN, BK, WM, WN, S, R, F)) {
-    using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK>;
-    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, C::LDS_BYTES, C::NT,
+  if constexpr (instance_feasible(BM, BN, BK, WM, WN, S, R, F, PF)) {
+    using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF>;
+    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF, C::LDS_BYTES, C::NT,
                             C::L, C::PATCH_OFF, &launch_instance<C>});
   }
 }

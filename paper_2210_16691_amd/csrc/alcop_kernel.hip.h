@@ -127,11 +127,13 @@ struct Opnd {
 // inner, LDS -> register pipeline); FUSE: the inner pipeline runs across k-tiles (Fig. 3(d)).
 // BL / AL: operand layouts; AM: how the A tile is produced (matrix or convolution gather);
 // SK: split-K variant (grid.z slices of the reduction axis, fp32 partial tiles).
+// PF: the kernel has the third pipeline level (HBM -> L2 touches, one more load per wave and k-tile).
 template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int S_, int R_, int FUSE_,
-          int BL_, int AM_, int AL_ = 0, int SK_ = 0>
+          int BL_, int AM_, int AL_ = 0, int SK_ = 0, int PF_ = 0>
 struct KCfg {
   static constexpr int DT = DT_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
   static constexpr int S = S_, R = R_, FUSE = FUSE_, BL = BL_, AM = AM_, AL = AL_, SK = SK_;
+  static constexpr int PF = PF_;
   static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, NWAVES = WAVES_M * WAVES_N;
   static constexpr int NT = NWAVES * 64;
   // AL: 0 = A stored M x K, 1 = A stored K x M.  BL: 0 = B stored K x N, 1 = B stored N x K.
@@ -150,18 +152,25 @@ struct KCfg {
   // AM == 3: the patch follows the ring and the landing pad, 1024-byte aligned; its size depends
   // on the convolution's geometry and is added to the dynamic LDS size at launch
   static constexpr int PATCH_OFF = (MAIN_BYTES + 1023) / 1024 * 1024;
-  static constexpr int L = NLA + NLB + 1;   // per wave and k-tile: tile loads + one L2 touch
+  static constexpr int L = NLA + NLB + PF;  // per wave and k-tile: tile loads (+ one L2 touch)
   static constexpr int WAIT = (S >= 2 ? (S - 2) * L : 0);    // loads allowed in flight at a wait
   static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "wave tile");
   static_assert(BK == 32 || BK == 64 || BK == 128, "bk");
-  static_assert(S >= 1 && S <= 4 && (R == 1 || R == 2), "stages");
-  static_assert(!FUSE || (R == 2 && S >= 2), "fusion needs a register double buffer and S>=2");
+  static_assert(S >= 1 && S <= 4 && R >= 1 && R <= 4, "stages");
+  static_assert(!FUSE || (R >= 2 && S >= 2), "fusion needs a register double buffer and S>=2");
+  // R >= 3: R - 1 fragments are in flight ahead of the one the matrix cores consume.  They may
+  // reach into the next k-tile but not beyond it, and only the fused pipeline is built that deep.
+  static_assert(R <= 2 || (FUSE && R - 1 <= BK / 16), "deep register pipeline");
+  // loads allowed in flight when the prologue of the deep pipeline, which primes all S slots,
+  // waits for k-tile 0 (a smaller number than necessary only waits for more)
+  static constexpr int WAIT0 = (S - 1) * L < 63 ? (S - 1) * L : 63;
   // AM: 0 = A is a matrix; 1 = A is gathered from an NHWC image and a k-tile lies inside one
   // filter tap (bk divides the channel count: the tap is the same for all lanes); 2 = gathered,
   // any channel count that is a multiple of 8 (every lane tracks the tap of its own chunk);
   // 3 = stride-1 convolution with C = BK whose input patch (tile + halo) is loaded into LDS once
   // and whose filter taps are formed by shifted LDS reads: only the weights stream through the ring
   static_assert(AM != 3 || (SK == 0 && BL == 0), "patch convolution: RSCK weights, no split-K");
+  static_assert(!PF || (AM == 0 && SK == 0 && FUSE), "L2 touches: fused matrix-operand kernels only");
   static_assert(!(AM != 0 && AL == 1), "the convolution gather produces a K-contiguous A tile");
   static_assert(WAIT <= 63, "vmcnt is a 6-bit counter");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
@@ -413,26 +422,30 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   // or B column-panel (equal tn) at about the same time, so each line misses L2 once and all
   // sharers wait for that miss.  Touching the line pf_dist k-tiles earlier, once, by one of the
   // sharers, turns the tile loads into L2 hits.  Lane x of the block owns one line per k-tile.
-  const int pf_d = p.pf_dist < nko - 1 ? p.pf_dist : nko - 1;   // never past the last k-tile
+  int pf_d = 0;
   const char* pf_ptr = Bbatch;                // a valid address for lanes without a line
   uint32_t pf_step = 0;
-  if (pf_d > 0) {
-    const int na = (C::AM == 0) ? OA::LINES / p.pf_pa : 0;   // lines of A this block touches
-    bool have = false;
-    if constexpr (C::AM == 0)
-      have = touch_line<OA>(Abatch, tm, p.M, p.lda, q0, p.pf_pa, tn % p.pf_pa, &pf_ptr, &pf_step);
-    if (!have && q0 >= na)
-      have = touch_line<OB>(Bbatch, tn, p.N, p.ldb, q0 - na, p.pf_pb, tm % p.pf_pb, &pf_ptr, &pf_step);
-    if (!have) {
-      pf_ptr = Bbatch;
-      pf_step = 0;
+  if constexpr (C::PF) {
+    pf_d = p.pf_dist < nko - 1 ? p.pf_dist : nko - 1;   // never past the last k-tile
+    if (pf_d > 0) {
+      const int na = (C::AM == 0) ? OA::LINES / p.pf_pa : 0;   // lines of A this block touches
+      bool have = false;
+      if constexpr (C::AM == 0)
+        have = touch_line<OA>(Abatch, tm, p.M, p.lda, q0, p.pf_pa, tn % p.pf_pa, &pf_ptr, &pf_step);
+      if (!have && q0 >= na)
+        have = touch_line<OB>(Bbatch, tn, p.N, p.ldb, q0 - na, p.pf_pb, tm % p.pf_pb, &pf_ptr, &pf_step);
+      if (!have) {
+        pf_ptr = Bbatch;
+        pf_step = 0;
+      }
+      pf_ptr += (long)pf_step * pf_d;
     }
-    pf_ptr += (long)pf_step * pf_d;
   }
   const uint32_t pf_dst = lds0 + C::RING_BYTES + (uint32_t)wave * 256u;
 
   // Loads of one k-tile: stage_begin fixes the wave-uniform offsets of k-tile `kt` and ring slot
-  // `slot`; issue_one(i) emits load i of the L loads a wave owns (A loads, B loads, L2 touch);
+  // `slot`; issue_one(i) emits load i of the L loads a wave owns (A loads, B loads, and the L2
+  // touch of the kernels that have that level);
   // stage_end advances the convolution tap.  Always exactly L loads per wave and stage.
   // A partial last k-tile selects the lane offsets that zero-fill chunks at k >= K: one select
   // per operand and k-tile, nothing per load.
@@ -468,7 +481,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       const int i = idx - NLA;
       HW::dma16(lb.rsrc, st_voffB + st_kb + (uint32_t)i * lb.step,
             st_dst + A_BYTES + i * (NWAVES * 1024));
-    } else {
+    } else if constexpr (C::PF) {
       HW::touch4(pf_ptr, pf_dst);
       if (st_pf_live) pf_ptr += pf_step;      // stop at the last k-tile: never run past the operand
     }
@@ -569,7 +582,65 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   u32x4 fa[C::R][TM], fb[C::R][TN];
 
   // ---- the pipelined main loop -----------------------------------------------------------
-  if constexpr (C::FUSE) {
+  if constexpr (C::FUSE && C::R >= 3) {
+    // Deep holistic pipeline (Table 1: the stage count of the register-level pipeline is a free
+    // parameter; Fig. 3(d) fusion).  D = R-1 fragments are being read ahead of the fragment the
+    // matrix cores consume, so that an LDS read has at least D-1 whole steps to return; with one
+    // wave per SIMD nothing else hides that latency.  The loop runs in periods: period p opens
+    // with the block-wide synchronisation after which k-tile p+1 may be read and the slot of
+    // k-tile p may be refilled; its step t reads fragment t of k-tile p+1 and computes fragment
+    // KS+t of k-tile p (continuing into k-tile p+1 when KS+t >= NKI).  The ring is primed with
+    // S k-tiles; k-tile p+S is issued during steps 1..NKI-1 of period p.
+    constexpr int R = C::R, D = R - 1, KS = NKI - D;
+    constexpr int G = (NKI % R == 0) ? R : ((NKI % 2 == 0 && R % 2 == 0) ? 2 : 1);   // gcd(NKI, R)
+    constexpr int U = R / G;                  // periods per unrolled body: register slots are static
+#pragma unroll
+    for (int s = 0; s < S; s++) issue(s, s);
+    HW::template wait_vm<C::WAIT0>();
+    HW::block_barrier();
+    set_read_slot(lds0);
+#pragma unroll
+    for (int d = 0; d < D; d++) load_frags(d, fa[d], fb[d]);
+    HW::sched_fence();
+    // steps 0..KS-1 of k-tile 0: the rest of its fragments are read, nothing is issued
+#pragma unroll
+    for (int ki = 0; ki < KS; ki++)
+      step(fa[ki % R], fb[ki % R], true, ki + D, fa[(ki + D) % R], fb[(ki + D) % R], 0, 0, 0, no_sync);
+    int rslot = 0, wslot = 0;
+    bool done = false;
+    for (int p0 = 0; p0 < nko && !done; p0 += U) {
+#pragma unroll
+      for (int u = 0; u < U; u++) {
+        const int pp = p0 + u;
+        if (U > 1 && pp >= nko) break;
+        const bool last = pp + 1 == nko;
+#pragma unroll
+        for (int t = 0; t < NKI; t++) {
+          // fragment u*NKI + KS + t (counted from the body's first period) is consumed, the one D
+          // later is read; past the last k-tile only the consuming steps t < D remain
+          const int cs = (u * NKI + KS + t) % R, rs = (u * NKI + KS + t + D) % R;
+          if (t >= D && last) { done = true; break; }
+          if (t == 0) {
+            constexpr int FIRST = NMM >= 8 ? NMM / 4 : 1;
+            step(fa[cs], fb[cs], true, 0, fa[rs], fb[rs], 0, 0, FIRST, [&] {
+              HW::template wait_vm<C::WAIT>();   // consumer_wait: k-tile p+1 has landed (this wave)
+              HW::wait_lds();                    // consumer_release: my reads of k-tile p are done
+              HW::block_barrier();               // ... for every wave
+              stage_begin(pp + S, wslot);        // the slot of k-tile p is refilled with k-tile p+S
+              wslot = (wslot + 1 == S) ? 0 : wslot + 1;
+              rslot = (rslot + 1 == S) ? 0 : rslot + 1;
+              set_read_slot(lds0 + rslot * STAGE_BYTES);
+            });
+          } else {
+            step(fa[cs], fb[cs], true, t, fa[rs], fb[rs], (t - 1) * C::L / (NKI - 1),
+                 t * C::L / (NKI - 1), 0, no_sync);
+          }
+        }
+        if (done) break;
+        stage_end();
+      }
+    }
+  } else if constexpr (C::FUSE) {
     // Holistic pipeline over (ko, ki): Fig. 3(d).  The loads of k-tile ko+S-1 are issued during
     // steps 0..NKI-2; the wait for k-tile ko+1 and the barrier open step NKI-1, whose reads
     // already fetch the first fragment of k-tile ko+1.

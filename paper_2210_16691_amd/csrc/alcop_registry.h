@@ -11,6 +11,7 @@ namespace alcop {
 struct KernelEntry {
   int dt, bm, bn, bk, wm, wn, stages, reg_stages, fuse, bl, am, al;
   int sk;   // 1: split-K variant (grid.z slices of the reduction axis, fp32 partial tiles)
+  int pf;   // 1: the kernel has the HBM -> L2 touch level (schedules with l2_prefetch > 0)
   int lds_bytes, threads, loads_per_stage;
   int patch_off;   // am == 3: LDS offset of the input patch (its size is per call)
   hipError_t (*launch)(const Params&, dim3, hipStream_t);
@@ -28,6 +29,8 @@ void register_conv_krsc(std::vector<KernelEntry>&);
 void register_conv_anyc(std::vector<KernelEntry>&);
 void register_conv_patch(std::vector<KernelEntry>&);
 void register_bk128(std::vector<KernelEntry>&);
+void register_deep(std::vector<KernelEntry>&);
+void register_pf(std::vector<KernelEntry>&);
 void register_splitk_gemm(std::vector<KernelEntry>&);
 void register_splitk_conv(std::vector<KernelEntry>&);
 

@@ -19,11 +19,11 @@ hipError_t launch_emulated(const Params& p, dim3 grid, hipStream_t)
 }
 
 template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int R, int F, int BL, int AM,
-          int AL = 0, int SK = 0>
+          int AL = 0, int SK = 0, int PF = 0>
 void add(std::vector<KernelEntry>& t)
 {
-  using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK>;
-  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, C::LDS_BYTES, C::NT, C::L,
+  using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF>;
+  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF, C::LDS_BYTES, C::NT, C::L,
                           C::PATCH_OFF, &launch_emulated<C>});
 }
 
@@ -41,6 +41,12 @@ void emu_part_0(std::vector<KernelEntry>& t)
   add<0, 128, 128, 64, 64, 64, 3, 2, 1, 0, 0>(t);
   add<0, 128, 128, 64, 64, 64, 4, 2, 1, 0, 0>(t);
   add<0, 128, 128, 32, 64, 64, 3, 2, 1, 0, 0>(t);
+  // with the HBM -> L2 touch level
+  add<0, 128, 128, 64, 64, 64, 4, 2, 1, 0, 0, 0, 0, 1>(t);
+  add<0, 128, 128, 64, 64, 64, 4, 2, 1, 1, 0, 0, 0, 1>(t);
+  add<0, 64, 64, 32, 32, 32, 4, 2, 1, 0, 0, 0, 0, 1>(t);
+  add<0, 128, 128, 64, 64, 64, 3, 4, 1, 0, 0, 0, 0, 1>(t);
+  add<1, 128, 128, 64, 64, 64, 3, 2, 1, 0, 0, 1, 0, 1>(t);   // A stored K x M
 }
 #elif EMU_PART == 1
 void emu_part_1(std::vector<KernelEntry>& t)
@@ -57,6 +63,7 @@ void emu_part_1(std::vector<KernelEntry>& t)
   add<0, 128, 128, 128, 64, 64, 2, 2, 1, 0, 0>(t);     // k-tile of 128
   add<0, 128, 128, 128, 64, 64, 1, 1, 0, 0, 0>(t);
   add<0, 64, 64, 128, 32, 32, 4, 2, 1, 0, 0>(t);
+  add<0, 64, 64, 128, 32, 32, 4, 2, 1, 0, 0, 0, 0, 1>(t);   // ... with L2 touches
   add<0, 128, 64, 128, 64, 32, 2, 1, 0, 0, 0>(t);
   add<1, 128, 128, 128, 64, 64, 2, 2, 0, 1, 0>(t);     // ... B stored N x K, bf16
   add<0, 64, 64, 128, 32, 32, 3, 2, 1, 1, 0>(t);
@@ -92,6 +99,27 @@ void emu_part_4(std::vector<KernelEntry>& t)
   add<0, 128, 128, 64, 64, 64, 3, 2, 1, 0, 0, 1, 1>(t);   // A stored K x M
   add<1, 64, 64, 64, 32, 32, 2, 2, 1, 0, 0, 1, 1>(t);
 }
+#elif EMU_PART == 5
+void emu_part_5(std::vector<KernelEntry>& t)
+{
+  // register pipelines deeper than two stages (fused only)
+  add<0, 128, 128, 64, 64, 64, 4, 4, 1, 0, 0>(t);      // D = 3 of 4 fragments: synchronisation in step 1
+  add<0, 128, 128, 64, 64, 64, 2, 3, 1, 0, 0>(t);      // R = 3 with 4 fragments: body of three periods
+  add<0, 128, 128, 32, 64, 64, 3, 3, 1, 0, 0>(t);      // D = all fragments of a k-tile
+  add<0, 64, 64, 64, 32, 32, 3, 4, 1, 0, 0>(t);
+  add<0, 256, 256, 32, 128, 64, 2, 3, 1, 0, 0>(t);     // 8 waves
+  add<0, 128, 128, 128, 64, 64, 2, 4, 1, 0, 0>(t);     // k-tile of 128: 8 fragments
+  add<1, 128, 128, 64, 64, 64, 3, 4, 1, 0, 0>(t);      // bf16
+  add<0, 128, 128, 64, 64, 64, 4, 4, 1, 1, 0>(t);      // B stored N x K
+  add<1, 64, 64, 32, 32, 32, 4, 3, 1, 1, 0>(t);
+  add<0, 128, 128, 64, 64, 64, 3, 4, 1, 0, 0, 1>(t);   // A stored K x M
+  add<0, 128, 128, 64, 64, 64, 3, 3, 1, 1, 0, 1>(t);
+  add<0, 128, 64, 64, 64, 32, 3, 4, 1, 0, 1>(t);       // convolution gather
+  add<0, 128, 64, 32, 64, 32, 4, 3, 1, 0, 2>(t);
+  add<0, 128, 64, 64, 64, 32, 3, 4, 1, 1, 1>(t);       // KRSC weights
+  add<0, 256, 64, 64, 64, 64, 3, 4, 1, 0, 3>(t);       // input patch resident in LDS
+  add<0, 128, 128, 64, 64, 64, 3, 4, 1, 0, 0, 0, 1>(t);   // split-K
+}
 #elif EMU_PART == 3
 void emu_part_3(std::vector<KernelEntry>& t)
 {
@@ -125,6 +153,7 @@ void emu_part_1(std::vector<KernelEntry>&);
 void emu_part_2(std::vector<KernelEntry>&);
 void emu_part_3(std::vector<KernelEntry>&);
 void emu_part_4(std::vector<KernelEntry>&);
+void emu_part_5(std::vector<KernelEntry>&);
 void register_f16_kn_mid(std::vector<KernelEntry>& t)
 {
   emu_part_0(t);
@@ -132,6 +161,7 @@ void register_f16_kn_mid(std::vector<KernelEntry>& t)
   emu_part_2(t);
   emu_part_3(t);
   emu_part_4(t);
+  emu_part_5(t);
 }
 void register_splitk_gemm(std::vector<KernelEntry>&) {}
 void register_splitk_conv(std::vector<KernelEntry>&) {}
@@ -139,6 +169,8 @@ void register_conv_krsc(std::vector<KernelEntry>&) {}
 void register_conv_anyc(std::vector<KernelEntry>&) {}
 void register_conv_patch(std::vector<KernelEntry>&) {}
 void register_bk128(std::vector<KernelEntry>&) {}
+void register_deep(std::vector<KernelEntry>&) {}
+void register_pf(std::vector<KernelEntry>&) {}
 
 static void reduce_entry(const void* p)
 {

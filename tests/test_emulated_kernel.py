@@ -91,6 +91,45 @@ def test_gemm_all_timing_policies_many_k_tiles_and_fp32_output():
             assert not errs and ok, (repr(s), policy, errs[:4])
 
 
+def test_deep_register_pipeline_every_k_tile_count_and_policy():
+    # R - 1 fragments in flight: the reads run up to a whole k-tile ahead of the matrix
+    # instructions and the synchronisation sits in the middle of a k-tile.  One k-tile (the
+    # pipeline never reaches its steady state), two, one more than the ring holds, many; a
+    # partial last k-tile; R = 3 on four fragments (body of three k-tiles) and on two
+    # fragments (all of a k-tile in flight); R = 4 on four and on eight fragments.
+    for s in (al.sched(128, 128, 64, 64, 64, 4, 4, 1), al.sched(128, 128, 64, 64, 64, 2, 3, 1),
+              al.sched(128, 128, 32, 64, 64, 3, 3, 1), al.sched(128, 128, 128, 64, 64, 2, 4, 1),
+              al.sched(64, 64, 64, 32, 32, 3, 4, 1)):
+        for nk, extra in ((1, 0), (2, 0), (s.stages + 1, 8), (7, 0), (11, 16)):
+            for policy in emu.POLICIES:
+                errs, ok = _gemm_case("f16", 0, 0, s, s.bm + 8, s.bn, nk * s.bk + extra, policy, out="f32")
+                assert not errs and ok, (repr(s), nk, extra, policy, errs[:4])
+    errs, ok = _gemm_case("f16", 0, 0, al.sched(128, 128, 64, 64, 64, 4, 4, 1), 8, 8, 8, (1, 1))
+    assert not errs and ok
+
+
+def test_deep_register_pipeline_convolution_and_splitk():
+    x = wl.small_ints((2, 9, 7, 64), "f16", 31)
+    w = wl.small_ints((3, 3, 64, 64), "f16", 32)
+    ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, (1, 1), (1, 1))
+    for s in (al.sched(128, 64, 64, 64, 32, 3, 4, 1), al.sched(256, 64, 64, 64, 64, 3, 4, 1, 1, 0, 1)):
+        for policy in ((1, 0), (0, 1)):
+            y = torch.full((2, 9, 7, 64), float("nan"), dtype=torch.float32)
+            errs = emu.call(al.alcop_conv2d_igemm, x, w, y, (1, 1), (1, 1), s, reads=[x, w], writes=[y],
+                            policy=policy)
+            assert not errs, (repr(s), errs[:4])
+            assert _exact(y, ref), repr(s)
+    A = wl.small_ints((136, 7 * 64), "f16", 33)
+    B = wl.small_ints((7 * 64, 72), "f16", 34)
+    ref = oracle.gemm(wl.bits(A), wl.bits(B), oracle.F16)
+    C = torch.full((136, 72), float("nan"), dtype=torch.float32)
+    ws = torch.empty(al.alcop_splitk_workspace_bytes(1, 136, 72, 3) // 4, dtype=torch.float32)
+    errs = emu.call(al.alcop_gemm_splitk, A, B, C, 3, ws, al.sched(128, 128, 64, 64, 64, 3, 4, 1),
+                    reads=[A, B], writes=[C, ws], policy=(1, 1))
+    assert not errs, errs[:4]
+    assert _exact(C, ref)
+
+
 def test_gemm_tiny_and_single_k_tile():
     s = al.sched(64, 64, 32, 32, 32, 4, 2, 1)
     for (M, N, K) in ((1, 8, 8), (8, 8, 32), (64, 64, 16), (65, 72, 40)):
@@ -182,27 +221,30 @@ def test_conv_gather_exact_and_in_bounds(geom):
 def test_planted_synchronisation_mistakes_are_noticed():
     s4 = al.sched(128, 128, 64, 64, 64, 4, 2, 1)
     s3u = al.sched(128, 128, 64, 64, 64, 3, 1, 0)
+    s4d = al.sched(128, 128, 64, 64, 64, 4, 4, 1)       # three fragments in flight
     M, N, K = 128, 128, 8 * 64
     # sound kernel: clean under every policy (the control)
-    for s in (s4, s3u):
+    for s in (s4, s3u, s4d):
         for policy in emu.POLICIES:
             errs, ok = _gemm_case("f16", 0, 0, s, M, N, K, policy)
             assert not errs and ok
     # a wait that lets too many loads stay in flight: a late-landing load is read too early
-    for s in (s4, s3u):
+    for s in (s4, s3u, s4d):
         errs, ok = _gemm_case("f16", 0, 0, s, M, N, K, (1, 0), mutation=1)
         assert not ok, repr(s)
     # no block barrier: a wave that runs ahead reads tiles the others have not delivered, or
     # refills a slot the others still read
-    for policy in ((0, 0), (0, 1), (1, 0)):
-        errs, ok = _gemm_case("f16", 0, 0, s4, M, N, K, policy, mutation=2)
-        assert not ok, policy
+    for s in (s4, s4d):
+        for policy in ((0, 0), (0, 1), (1, 0)):
+            errs, ok = _gemm_case("f16", 0, 0, s, M, N, K, policy, mutation=2)
+            assert not ok, (repr(s), policy)
     # waits ignored altogether
-    errs, ok = _gemm_case("f16", 0, 0, s4, M, N, K, (1, 0), mutation=3)
-    assert not ok
+    for s in (s4, s4d):
+        errs, ok = _gemm_case("f16", 0, 0, s, M, N, K, (1, 0), mutation=3)
+        assert not ok, repr(s)
     # no wait for the LDS reads before the barrier that releases a slot: the refill may overtake
     # a read (the data path of the model cannot show this, the in-flight bookkeeping does)
-    for s in (s4, s3u, al.sched(128, 128, 64, 64, 64, 1, 1, 0)):
+    for s in (s4, s3u, s4d, al.sched(128, 128, 64, 64, 64, 1, 1, 0)):
         errs, ok = _gemm_case("f16", 0, 0, s, M, N, K, (1, 0), mutation=4)
         assert errs and "may still be fetching" in " ".join(errs), repr(s)
 
