@@ -326,6 +326,25 @@ int alcop_tune(const alcop_problem* prob /* host */, const void* A, const void* 
                double* log_meas_us /* host */, int log_cap, void* hip_stream);
 
 /*
+ * The learner behind alcop_tune(model = 2) on its own, host only (paper Sec. 5.3, "Analytical +
+ * ML": a cost model that starts from the analytical predictions and is corrected by profiled
+ * trials).  It is a ridge regression on log(microseconds) over ALCOP_CORRECTOR_DIM features of a
+ * (problem, schedule) pair whose prior weight vector is (0, 1, 0, ...): with no trials it predicts
+ * exactly the analytical model.
+ *   alcop_corrector_features writes the features of one pair: 1; log of the prediction of model
+ *     0; log of the prediction of model 1; log2(bm * bn) - 14; log2(bk) - 6; stages - 2;
+ *     reg_stages - 1; fuse_inner; log2(waves per block) - 2; 1 if l2_prefetch > 0.
+ *   alcop_corrector_fit takes n trials (x: n rows of features, row-major; measured_us: n times,
+ *     all > 0) and writes the weights w that minimise sum (log t - w.x)^2 + 0.3 |w - prior|^2,
+ *     i.e. the solution of (X'X + 0.3 I) w = X' log t + 0.3 prior; n = 0 gives the prior.
+ */
+#define ALCOP_CORRECTOR_DIM 10
+int alcop_corrector_features(const alcop_problem* prob /* host */, const alcop_sched* sched /* host */,
+                             double* x /* host, ALCOP_CORRECTOR_DIM */);
+int alcop_corrector_fit(const double* x /* host */, const double* measured_us /* host */, int n,
+                        double* weights /* host, ALCOP_CORRECTOR_DIM */);
+
+/*
  * The schedule a NULL / zero schedule argument resolves to for this problem: the entry of the
  * tuning cache if there is one (written by alcop_tune or alcop_cache_load), else the feasible
  * schedule with the lowest predicted latency under model 0.  Host only, launches nothing.

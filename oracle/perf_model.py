@@ -18,7 +18,7 @@ follows:
     state) one fragment load per outer iteration is exposed when R = 2.
   * LDS port occupancy (an addition to Table 1 for this machine): T_smem_use is at least the time
     the single LDS port needs to move the fragment reads of every wave (K-contiguous operand at
-    128 B/clk, N-contiguous operand through the transposing read at ~240 B/clk) plus the
+    256 B/clk, N-contiguous operand through the transposing read at ~170 B/clk) plus the
     direct-to-LDS writes of one k-tile.
   * Clock: rates are taken at the ~1.8 GHz a GEMM sustains under the power cap.
 
@@ -40,10 +40,10 @@ class Device:
     regs_per_lane: float = 512.0
     flop_per_us_cu: float = 4096.0 * 1800.0      # sustained clock under the power cap ~1.8 GHz
     lat_lds: float = 128.0 / 1800.0
-    bw_lds_cu: float = 128.0 * 1800.0            # ds_read_b128 and DMA writes
-    bw_lds_tr_cu: float = 240.0 * 1800.0         # transposing 8-byte read
+    bw_lds_cu: float = 256.0 * 1800.0            # ds_read_b128 and DMA writes (measured)
+    bw_lds_tr_cu: float = 170.0 * 1800.0         # transposing 8-byte read (measured)
     lat_llc: float = 0.6
-    bw_llc: float = 16.0e6
+    bw_llc: float = 40.0 * 256.0 * 1800.0        # 40 B/clk per CU when all CUs stream (measured)
     lat_dram: float = 1.2
     bw_dram: float = 8.0e6
     lat_dram_write: float = 1.0

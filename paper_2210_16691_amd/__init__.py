@@ -25,7 +25,7 @@ EXPORTS = [
     "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
-    "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_sched_variants",
+    "alcop_corrector_features", "alcop_corrector_fit", "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_sched_variants",
 ]
 
 
@@ -111,6 +111,10 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
     L.alcop_cache_save.argtypes = [ctypes.c_char_p]
     L.alcop_cache_load.restype = i
     L.alcop_cache_load.argtypes = [ctypes.c_char_p]
+    L.alcop_corrector_features.restype = i
+    L.alcop_corrector_features.argtypes = [pp, sp, dp]
+    L.alcop_corrector_fit.restype = i
+    L.alcop_corrector_fit.argtypes = [dp, dp, i, dp]
     sz = ctypes.c_size_t
     L.alcop_splitk_workspace_bytes.restype = sz
     L.alcop_splitk_workspace_bytes.argtypes = [i, i, i, i]
@@ -384,6 +388,26 @@ def alcop_model_predict(prob: Problem, s: Sched, model: int = 0):
     rc = lib().alcop_model_predict(ctypes.byref(prob), ctypes.byref(s), model, ctypes.byref(us), terms)
     _check(rc, "alcop_model_predict")
     return us.value, list(terms)
+
+
+CORRECTOR_DIM = 10
+
+
+def alcop_corrector_features(prob: Problem, s: Sched):
+    """Features of a (problem, schedule) pair as the learner of alcop_tune(model=2) sees them."""
+    x = (ctypes.c_double * CORRECTOR_DIM)()
+    _check(lib().alcop_corrector_features(ctypes.byref(prob), ctypes.byref(s), x), "alcop_corrector_features")
+    return list(x)
+
+
+def alcop_corrector_fit(X, measured_us):
+    """Weights of the learner after the given trials (X: rows of CORRECTOR_DIM features)."""
+    n = len(measured_us)
+    flat = (ctypes.c_double * (n * CORRECTOR_DIM))(*[float(v) for row in X for v in row])
+    ys = (ctypes.c_double * max(n, 1))(*[float(v) for v in measured_us])
+    w = (ctypes.c_double * CORRECTOR_DIM)()
+    _check(lib().alcop_corrector_fit(flat, ys, n, w), "alcop_corrector_fit")
+    return list(w)
 
 
 @dataclass

@@ -33,16 +33,25 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
 
 
-def _deps_mtime():
+def _deps_mtime(obj: str) -> float:
+    """Newest modification time among the headers this object was last compiled from (from the
+    compiler's own dependency file; every header if there is none yet)."""
+    dep = obj + ".d"
+    if os.path.exists(dep):
+        words = open(dep).read().replace("\\\n", " ").split()
+        files = [w for w in words[1:] if not w.endswith(":")]
+        try:
+            return max(os.path.getmtime(f) for f in files) if files else 0.0
+        except OSError:
+            return float("inf")          # a header it used is gone: recompile
     hs = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
     return max(os.path.getmtime(h) for h in hs)
 
 
 def _compile(src: str, force: bool) -> str:
     obj = os.path.join(OBJDIR, os.path.basename(src) + ".o")
-    newest = max(os.path.getmtime(src), _deps_mtime())
-    if force or not os.path.exists(obj) or os.path.getmtime(obj) < newest:
-        cmd = [HIPCC] + FLAGS + ["-x", "hip", "-c", src, "-o", obj]
+    if force or not os.path.exists(obj) or os.path.getmtime(obj) < max(os.path.getmtime(src), _deps_mtime(obj)):
+        cmd = [HIPCC] + FLAGS + ["-MD", "-MF", obj + ".d", "-x", "hip", "-c", src, "-o", obj]
         r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:

@@ -901,6 +901,30 @@ int alcop_model_predict(const alcop_problem* prob, const alcop_sched* sched, int
   return ALCOP_OK;
 }
 
+int alcop_corrector_features(const alcop_problem* prob, const alcop_sched* sched, double* x)
+{
+  if (!prob || !sched || !x) return ALCOP_ERR_NULL;
+  int rc = check_problem(*prob);
+  if (rc) return rc;
+  const Device dev;
+  Corrector::features(*prob, *sched, dev, x);
+  return ALCOP_OK;
+}
+
+int alcop_corrector_fit(const double* x, const double* measured_us, int n, double* weights)
+{
+  if (!weights || (n > 0 && (!x || !measured_us))) return ALCOP_ERR_NULL;
+  if (n < 0) return ALCOP_ERR_SHAPE;
+  Corrector corr;
+  for (int t = 0; t < n; t++) {
+    if (!(measured_us[t] > 0.0)) return ALCOP_ERR_SHAPE;
+    corr.add(x + (size_t)t * Corrector::D, measured_us[t]);
+  }
+  if (n > 0) corr.fit();
+  for (int i = 0; i < Corrector::D; i++) weights[i] = corr.weight(i);
+  return ALCOP_OK;
+}
+
 int alcop_time(const alcop_problem* prob, const void* A, const void* B, void* C, long lda, long ldb,
                long ldc, long strideA, long strideB, long strideC, const int* conv,
                const alcop_sched* sched, int warmup, int iters, double* mean_us, void* hip_stream)

@@ -84,7 +84,7 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   if (!s.fuse_inner && s.reg_stages >= 2) t_smem_use += t_reg_load;
   // LDS port occupancy (not in Table 1): the LDS serves the fragment reads of every wave and
   // the direct-to-LDS writes of the incoming k-tile through one port.  The K-contiguous operand
-  // is read at bw_lds, the N-contiguous one through the faster transposing read.  However well
+  // is read at bw_lds, the N-contiguous one through the transposing read at its own rate.  However well
   // latencies are hidden, a k-tile cannot be consumed faster than the port moves its bytes.
   {
     const double a_read = bm * bk * 2.0 * (bn / wn);   // every A row is read by the waves along n

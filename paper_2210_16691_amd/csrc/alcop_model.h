@@ -16,9 +16,14 @@ struct Device {
   double clk_per_us = 1800.0;
   double flop_per_us_cu = 4096.0 * 1800.0;
   double lat_lds = 128.0 / 1800.0;
-  double bw_lds_cu = 128.0 * 1800.0;          // ds_read_b128 / DMA write: 128 B/clk per CU
-  double bw_lds_tr_cu = 240.0 * 1800.0;       // ds_read_b64_tr_b16: ~240 B/clk per CU (measured)
-  double lat_llc = 0.6, bw_llc = 16.0e6;      // L2 / Infinity Cache -> CU, aggregate
+  // LDS read rates measured with enough waves in flight to hide the latency: ds_read_b128
+  // 256 B/clk per CU (4 clk per wave instruction), ds_read_b64_tr_b16 ~170 B/clk (3 clk per wave
+  // instruction of 512 bytes); direct-to-LDS writes are taken at the b128 rate
+  double bw_lds_cu = 256.0 * 1800.0;
+  double bw_lds_tr_cu = 170.0 * 1800.0;
+  // L2 / Infinity Cache -> LDS, aggregate: a CU's direct-to-LDS fill path delivers ~56 B/clk alone
+  // and ~40 B/clk when all 256 stream (8 L2s near their bandwidth, ~20 % of the requests missing)
+  double lat_llc = 0.6, bw_llc = 40.0 * 256.0 * 1800.0;
   double lat_dram = 1.2, bw_dram = 8.0e6;     // HBM3E read
   double lat_dram_write = 1.0, bw_dram_write = 8.0e6;
 };
@@ -51,6 +56,7 @@ class Corrector {
   void add(const double* x, double measured_us);   // one profiled trial
   void fit();                                      // ridge solve towards the prior
   double predict_log(const double* x) const;       // log(predicted microseconds)
+  double weight(int i) const { return w_[i]; }
 
  private:
   double xtx_[D][D], xty_[D], w_[D], prior_[D];

@@ -41,17 +41,17 @@ def test_table_rows_by_hand():
     # compute: 2*128*128*16 flop on 4096 flop/clk * 1800 clk/us, 4 waves fill the 4 pipes
     assert r["util"] == 1.0
     assert r["t_compute"] == pytest.approx(524288 / (4096 * 1800.0))
-    # register load: 128 clk latency + 4 waves * (64+64)*16*2 B at 128 B/clk
-    assert r["t_reg_load"] == pytest.approx((128 + 16384 / 128) / 1800.0)
+    # register load: 128 clk latency + 4 waves * (64+64)*16*2 B at 256 B/clk
+    assert r["t_reg_load"] == pytest.approx((128 + 16384 / 256) / 1800.0)
     # inner pipeline, R=2, one wave per pipe: hidden iff t_reg_load <= t_compute
     assert r["t_reg_load"] > r["t_compute"]
     t_pipe = (r["t_reg_load"] + r["t_compute"]) * 4 / 2
-    # LDS port: A 128x64x2 B read by 2 waves along n at 128 B/clk, B likewise at 240 B/clk,
-    # plus the 32 KiB k-tile written at 128 B/clk
-    t_port = (32768 / 128 + 32768 / 240 + 32768 / 128) / 1800.0
+    # LDS port: A 128x64x2 B read by 2 waves along n at 256 B/clk, B likewise at 170 B/clk
+    # (transposing read), plus the 32 KiB k-tile written at 256 B/clk
+    t_port = (32768 / 256 + 32768 / 170 + 32768 / 256) / 1800.0
     assert r["t_smem_use"] == pytest.approx(max(t_pipe, t_port))
-    # memory: LLC term 0.6 + 256 blocks * 32 KiB / 16e6 ; DRAM term 1.2 + (16+16 panels)*128*64*2/8e6
-    t_llc = 0.6 + 256 * 32768 / 16.0e6
+    # memory: LLC term 0.6 + 256 blocks * 32 KiB at 40 B/clk per CU ; DRAM term 1.2 + (16+16 panels)*128*64*2/8e6
+    t_llc = 0.6 + 256 * 32768 / (40 * 256 * 1800.0)
     t_dram = 1.2 + 32 * 128 * 64 * 2 / 8.0e6
     assert r["t_smem_load"] == pytest.approx(max(t_llc, t_dram))
     assert r["t_init"] == pytest.approx(r["t_smem_load"] + r["t_reg_load"])
@@ -61,6 +61,144 @@ def test_table_rows_by_hand():
     # epilogue: 1.0 + 256 tiles * 128*128*2 B / 8e6
     assert r["t_epilogue"] == pytest.approx(1.0 + 256 * 32768 / 8.0e6)
     assert r["t_kernel"] == pytest.approx(r["t_init"] + r["t_main_loop"] + r["t_epilogue"])
+
+
+def test_table_rows_by_hand_two_blocks_per_cu_three_batches_batched():
+    # batched Q.K^T: 96 x (512 x 64 . 64 x 512), B stored N x K, fp16 out; 128x128x64 tile,
+    # 64x64 waves, S=2, R=2, fused.  16 tiles per matrix, 1536 blocks.
+    d = pm.Device()
+    r = pm.predict(512, 512, 64, 96, 2, 128, 128, 64, 64, 64, 2, 2, True, d, transB=True)
+    # scheduler: ring 2 * 32 KiB = 64 KiB -> floor(160/64) = 2 blocks by LDS; registers
+    # 64*64/64 + 2*(2+2)*4 + 48 = 144 per lane -> floor(512/144) = 3 waves per pipe -> 3 blocks
+    # of 4 waves; 1536 blocks exist -> 2 per CU, 512 per batch, ceil(1536/512) = 3 batches
+    assert r["n_blk_per_cu"] == 2 and r["n_threadblk_batch"] == 3
+    # compute: 8 waves on 4 pipes -> all busy, one block gets half a CU
+    assert r["util"] == 0.5
+    assert r["t_compute"] == pytest.approx(2 * 128 * 128 * 16 / (d.flop_per_us_cu * 0.5))
+    # register load: latency + 4 waves * (64+64)*16*2 B, two blocks share the port
+    assert r["t_reg_load"] == pytest.approx(d.lat_lds + 16384 * 2 / d.bw_lds_cu)
+    # inner pipeline: 4 fragments, 2 register stages, 2 waves per pipe multiplexed
+    t_pipe = pm.pipeline_latency(r["t_reg_load"], r["t_compute"], 4, 2, 2)
+    # LDS port: A 16 KiB read by 2 wave columns, B 16 KiB by 2 wave rows, both k-contiguous
+    # (plain reads), plus the 32 KiB k-tile written; two blocks
+    t_port = (32768 / d.bw_lds_cu + 32768 / d.bw_lds_cu + 32768 / d.bw_lds_cu) * 2
+    assert r["t_smem_use"] == pytest.approx(max(t_pipe, t_port))
+    # memory: 512 blocks * 32 KiB over the LLC; DRAM working set: the 512 co-resident blocks are
+    # 32 whole matrices of 16 tiles, each a 4 x 4 patch: (4*128 + 4*128) rows of 64 halves
+    t_llc = d.lat_llc + 512 * 32768 / d.bw_llc
+    t_dram = d.lat_dram + 32 * (4 * 128 + 4 * 128) * 64 * 2 / d.bw_dram
+    assert r["t_smem_load"] == pytest.approx(max(t_llc, t_dram))
+    assert r["t_init"] == pytest.approx(r["t_smem_load"] + r["t_reg_load"])
+    # outer pipeline: one k-tile, 2 stages, 2 blocks per CU multiplexed
+    assert r["t_main_loop"] == pytest.approx(pm.pipeline_latency(r["t_smem_load"], r["t_smem_use"], 1, 2, 2))
+    # epilogue: 512 tiles of 128*128 fp16
+    assert r["t_epilogue"] == pytest.approx(d.lat_dram_write + 512 * 32768 / d.bw_dram_write)
+    assert r["t_threadblk"] == pytest.approx(r["t_init"] + r["t_main_loop"] + r["t_epilogue"])
+    assert r["t_kernel"] == pytest.approx(3 * r["t_threadblk"])
+
+
+def test_table_rows_by_hand_unfused_and_transposed_operands():
+    # unfused R=2: one fragment load per k-tile is exposed on top of the pipelined inner loop
+    d = pm.Device()
+    args = (2048, 2048, 2048, 1, 2, 128, 128, 64, 64, 64, 3, 2)
+    fused = pm.predict(*args, True, d)
+    unfused = pm.predict(*args, False, d)
+    t_pipe = pm.pipeline_latency(fused["t_reg_load"], fused["t_compute"], 4, 2, 1)
+    t_port = 32768 / d.bw_lds_cu + 32768 / d.bw_lds_tr_cu + 32768 / d.bw_lds_cu
+    assert fused["t_smem_use"] == pytest.approx(max(t_pipe, t_port))
+    assert unfused["t_smem_use"] == pytest.approx(max(t_pipe + fused["t_reg_load"], t_port))
+    assert unfused["t_smem_use"] > fused["t_smem_use"]
+    # R=1 has no register pipeline to refill: fusion flag irrelevant, each fragment load exposed
+    r1 = pm.predict(2048, 2048, 2048, 1, 2, 128, 128, 64, 64, 64, 3, 1, False, d)
+    assert r1["t_smem_use"] == pytest.approx(max((fused["t_reg_load"] + fused["t_compute"]) * 4, t_port))
+    # operand layouts only enter through the port term: A stored K x M is read through the
+    # transposing read, B stored N x K through the plain one
+    big = pm.Device(lat_lds=0.0, flop_per_us_cu=1e12)     # compute and latency negligible: port term rules
+    ta = pm.predict(*args, True, big, transA=True)
+    tb = pm.predict(*args, True, big, transB=True)
+    assert ta["t_smem_use"] == pytest.approx(32768 / big.bw_lds_tr_cu + 32768 / big.bw_lds_tr_cu + 32768 / big.bw_lds_cu)
+    assert tb["t_smem_use"] == pytest.approx(32768 / big.bw_lds_cu + 32768 / big.bw_lds_cu + 32768 / big.bw_lds_cu)
+
+
+def test_table_rows_by_hand_convolution_with_the_patch_in_lds():
+    # conv 32 x 56 x 56 x 64 -> 64, 3x3 as a GEMM 100352 x 64 x 576, fp16 out; 256x64x64 tile, 64x64
+    # waves, S=3, R=2, fused; 9 taps share one input patch that stays in LDS
+    d = pm.Device()
+    r = pm.predict(100352, 64, 576, 1, 2, 256, 64, 64, 64, 64, 3, 2, True, d, patch_taps=9)
+    plain = pm.predict(100352, 64, 576, 1, 2, 256, 64, 64, 64, 64, 3, 2, True, d)
+    # a k-tile brings 256/9 rows of A and 64 columns of B, 64 deep
+    stage = (256 / 9 + 64) * 64 * 2
+    # LDS: 3 stages of the 8 KiB B tile + the patch (1.5 A tiles = 48 KiB) = 72 KiB -> 2 blocks per
+    # CU by LDS; registers 64 + 32 + 48 = 144 -> 3; 392 blocks -> ceil(392/256) = 2 -> 2 per CU,
+    # one batch of 392 blocks
+    assert r["n_blk_per_cu"] == 2 and r["n_threadblk_batch"] == 1
+    assert plain["n_blk_per_cu"] == 1 and plain["n_threadblk_batch"] == 2      # 3 * 40 KiB ring
+    assert r["util"] == 0.5
+    assert r["t_compute"] == pytest.approx(2 * 256 * 64 * 16 / (d.flop_per_us_cu * 0.5))
+    assert r["t_reg_load"] == pytest.approx(d.lat_lds + 4 * (64 + 64) * 16 * 2 * 2 / d.bw_lds_cu)
+    t_pipe = pm.pipeline_latency(r["t_reg_load"], r["t_compute"], 4, 2, 2)
+    # port: the whole A tile is still read from LDS (by one wave column), B by 4 wave rows through
+    # the transposing read; only the fetched bytes shrink
+    t_port = (256 * 64 * 2 / d.bw_lds_cu + 4 * 64 * 64 * 2 / d.bw_lds_tr_cu + stage / d.bw_lds_cu) * 2
+    assert r["t_smem_use"] == pytest.approx(max(t_pipe, t_port))
+    t_llc = d.lat_llc + 392 * stage / d.bw_llc
+    # DRAM working set: 392 tiles in one column of tiles (ntn = 1): 20 x 1 patch by the
+    # near-square rule (ceil(sqrt(392)) = 20 rows, then ceil(392/20) = 20 -> capped at ntn = 1)
+    t_dram = d.lat_dram + (20 * 256 / 9 + 1 * 64) * 64 * 2 / d.bw_dram
+    assert r["t_smem_load"] == pytest.approx(max(t_llc, t_dram))
+    assert r["t_main_loop"] == pytest.approx(pm.pipeline_latency(r["t_smem_load"], r["t_smem_use"], 9, 3, 2))
+    assert r["t_epilogue"] == pytest.approx(d.lat_dram_write + 392 * 256 * 64 * 2 / d.bw_dram_write)
+    assert r["t_kernel"] == pytest.approx(r["t_smem_load"] + r["t_reg_load"] + r["t_main_loop"] + r["t_epilogue"])
+    # the plain kernel of the same schedule fetches 9x the A rows per k-tile
+    assert plain["t_smem_load"] > r["t_smem_load"]
+
+
+def test_bottleneck_model_by_hand_each_resource_in_turn():
+    # Sec. 6.4 comparison model: max(compute, LDS traffic, DRAM traffic), each at full rate
+    # 2048^3, 128x128x64, 64x64 waves: 256 blocks, 32 k-tiles of 4 register loops
+    def terms(d):
+        t_cmp = 256 * 32 * 4 * (2 * 128 * 128 * 16) / (256 * d.flop_per_us_cu)
+        t_lds = 256 * 32 * 4 * (4 * (64 + 64) * 16 * 2) / (256 * d.bw_lds_cu)
+        t_mem = (256 * 32 * (128 + 128) * 64 * 2 + 256 * 128 * 128 * 2) / d.bw_dram
+        return t_cmp, t_lds, t_mem
+    args = (2048, 2048, 2048, 1, 2, 128, 128, 64, 64, 64)
+    for d in (pm.Device(),
+              pm.Device(flop_per_us_cu=1e3),                  # compute is the bottleneck
+              pm.Device(bw_lds_cu=1e2),                       # LDS traffic is
+              pm.Device(bw_dram=1e3)):                        # device memory traffic is
+        assert pm.bottleneck(*args, d) == pytest.approx(max(terms(d)))
+    assert pm.bottleneck(*args, pm.Device(flop_per_us_cu=1e3)) == pytest.approx(terms(pm.Device(flop_per_us_cu=1e3))[0])
+    assert pm.bottleneck(*args, pm.Device(bw_lds_cu=1e2)) == pytest.approx(terms(pm.Device(bw_lds_cu=1e2))[1])
+    assert pm.bottleneck(*args, pm.Device(bw_dram=1e3)) == pytest.approx(terms(pm.Device(bw_dram=1e3))[2])
+    # batched, ragged: blocks = ceil(1000/128) * ceil(264/64) * 3 = 8 * 5 * 3, k-tiles = ceil(520/32)
+    d = pm.Device(bw_dram=1e3)
+    blocks, ktiles = 8 * 5 * 3, 17
+    t_mem = (blocks * ktiles * (128 + 64) * 32 * 2 + blocks * 128 * 64 * 4) / d.bw_dram
+    assert pm.bottleneck(1000, 264, 520, 3, 4, 128, 64, 32, 64, 32, d) == pytest.approx(t_mem)
+
+
+def test_splitk_prediction_time_by_hand():
+    # 1024 x 64 output, K = 2048, 64x64x64 tile: 32 k-tiles; 16 slices requested -> 2 k-tiles each
+    d = pm.Device()
+    t, slices = pm.predict_splitk(1024, 64, 2048, 1, 2, 64, 64, 64, 32, 32, 4, 2, True, 16, d)
+    assert slices == 16
+    # the sliced problem: 16 times the blocks, K = 2 * 64, fp32 partial tiles
+    sliced = pm.predict(1024, 64, 128, 16, 4, 64, 64, 64, 32, 32, 4, 2, True, d)["t_kernel"]
+    # second pass: read 16 fp32 partials and write one fp16 result per output element, one
+    # DRAM read latency and one write latency
+    reduce_pass = d.lat_dram + d.lat_dram_write + 1024 * 64 * (4 * 16 + 2) / d.bw_dram
+    assert t == pytest.approx(sliced + reduce_pass)
+    # one slice: no second pass is charged (but the output is still fp32: the kernel's own)
+    t1, s1 = pm.predict_splitk(1024, 64, 2048, 1, 2, 64, 64, 64, 32, 32, 4, 2, True, 1, d)
+    assert s1 == 1
+    assert t1 == pytest.approx(pm.predict(1024, 64, 2048, 1, 4, 64, 64, 64, 32, 32, 4, 2, True, d)["t_kernel"])
+    # batched, uneven: 33 k-tiles over 4 -> 9 per slice -> 4 slices, the last one short; the
+    # model charges every slice the full 9 k-tiles
+    t4, s4 = pm.predict_splitk(128, 128, 33 * 64, 3, 2, 128, 128, 64, 64, 64, 3, 2, True, 4, d)
+    assert s4 == 4
+    want = pm.predict(128, 128, 9 * 64, 12, 4, 128, 128, 64, 64, 64, 3, 2, True, d)["t_kernel"] + \
+        d.lat_dram + d.lat_dram_write + 3 * 128 * 128 * (4 * 4 + 2) / d.bw_dram
+    assert t4 == pytest.approx(want)
 
 
 def test_model_monotone_in_stages_when_load_bound():
@@ -150,3 +288,41 @@ def test_library_patch_convolution_model_matches_oracle():
             plain = al.sched(s.bm, s.bn, s.bk, s.wm, s.wn, s.stages, s.reg_stages, s.fuse_inner)
             assert terms[5] < al.alcop_model_predict(prob, plain, 0)[1][5]
     assert seen >= 6
+
+
+# ---- the learned corrector (Sec. 5.3, "Analytical + ML") ----------------------------------------
+def test_corrector_features_by_their_definition():
+    prob = al.problem(al.OP_GEMM, 2048, 2048, 2048, al.F16, al.F16)
+    s = al.sched(256, 128, 32, 128, 64, 3, 2, 1, 1, 0)
+    x = al.alcop_corrector_features(prob, s)
+    a0 = al.alcop_model_predict(prob, s, 0)[0]
+    a1 = al.alcop_model_predict(prob, s, 1)[0]
+    want = [1.0, math.log(a0), math.log(a1), math.log2(256 * 128) - 14, math.log2(32) - 6, 3 - 2, 2 - 1, 1.0,
+            math.log2(4) - 2, 0.0]
+    assert x == pytest.approx(want, rel=1e-12, abs=1e-12)
+
+
+def test_corrector_ridge_solve_against_a_library_solver():
+    import numpy as np
+    rng = np.random.default_rng(7)
+    D = al.CORRECTOR_DIM
+    prior = np.zeros(D)
+    prior[1] = 1.0
+    # no trials: the prior, i.e. the analytical model itself
+    assert al.alcop_corrector_fit([], []) == pytest.approx(list(prior))
+    for n in (1, 3, D, 40):
+        X = rng.normal(size=(n, D))
+        X[:, 0] = 1.0
+        w_true = rng.normal(size=D)
+        t = np.exp(X @ w_true + 0.05 * rng.normal(size=n))
+        got = np.array(al.alcop_corrector_fit(X.tolist(), t.tolist()))
+        want = np.linalg.solve(X.T @ X + 0.3 * np.eye(D), X.T @ np.log(t) + 0.3 * prior)
+        assert got == pytest.approx(want, rel=1e-9, abs=1e-9)
+    # plenty of clean data: the weights that generated it are recovered (up to the shrinkage)
+    X = rng.normal(size=(4000, D))
+    w_true = rng.normal(size=D)
+    got = np.array(al.alcop_corrector_fit(X.tolist(), np.exp(X @ w_true).tolist()))
+    assert np.max(np.abs(got - w_true)) < 1e-2
+    # a measurement that agrees with the analytical model leaves the prior in place
+    x = [1.0, math.log(20.0)] + [0.0] * (D - 2)
+    assert al.alcop_corrector_fit([x], [20.0]) == pytest.approx(list(prior), abs=1e-12)
