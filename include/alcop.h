@@ -213,6 +213,28 @@ int alcop_gemm_splitk(const void* A, const void* B, void* C, int batch, int M, i
                       const alcop_sched* sched /* host */, int split,
                       void* workspace /* device */, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * alcop_gemm_splitk for callers that cannot allocate device memory or are not allowed to: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bit-identical results, but no workspace argument: the fp32 partial tiles go to
+ * an array of ALCOP_SPLITK_STATIC_BYTES that lives in the library's own device image (each GPU
+ * the library runs on holds it until the process ends).  The call allocates and frees nothing;
+ * the first call on a device looks the array's device address up, which may make the runtime
+ * load the library's device code, so make one call on each device before capturing a graph.
+ *   ALCOP_ERR_SIZE if 4 * slices * batch * M * N exceeds ALCOP_SPLITK_STATIC_BYTES (checked on
+ *   the host before anything touches the device); other errors as for alcop_gemm_splitk.
+ * Every call on one GPU uses that GPU's array and nothing in it is kept between calls: calls on
+ * different streams of one GPU that overlap in time race on it, so order them (one stream, or
+ * events).  Nothing needs clearing: every slice writes its whole M x N partial tile before the
+ * second kernel, ordered after it on the stream, reads exactly those.
+ */
+#define ALCOP_SPLITK_STATIC_BYTES (32u << 20)
+int alcop_gemm_splitk_static(const void* A, const void* B, void* C, int batch, int M, int N, int K,
+                             long lda, long ldb, long ldc, long strideA, long strideB,
+                             long strideC, int transA, int transB, alcop_dtype in, alcop_dtype out,
+                             const alcop_epilogue* ep /* host, may be NULL */,
+                             const alcop_sched* sched /* host */, int split, void* hip_stream);
+
 /* GEMM view of the convolution: M = N*P*Q, N = K, reduction R*S*C; workspace as above. */
 int alcop_conv2d_igemm_splitk(const void* x, const void* w, void* y, int N, int H, int W, int C,
                               int K, int R, int S, int stride_h, int stride_w, int pad_h,

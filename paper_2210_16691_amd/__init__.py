@@ -25,7 +25,7 @@ EXPORTS = [
     "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
-    "alcop_corrector_features", "alcop_corrector_fit", "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_sched_variants",
+    "alcop_corrector_features", "alcop_corrector_fit", "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_gemm_splitk_static", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_sched_variants",
 ]
 
 
@@ -121,6 +121,8 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
     L.alcop_gemm_splitk.restype = i
     L.alcop_gemm_splitk.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, ep, sp, i,
                                     vp, sz, vp]
+    L.alcop_gemm_splitk_static.restype = i
+    L.alcop_gemm_splitk_static.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, ep, sp, i, vp]
     L.alcop_conv2d_igemm_splitk.restype = i
     L.alcop_conv2d_igemm_splitk.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, i, vp, sz, vp]
     L.alcop_tune_splitk.restype = i
@@ -271,6 +273,32 @@ def alcop_gemm_splitk(A, B, C, split, workspace, sched=None, alpha=1.0, bias=Non
                                  ctypes.byref(e), _sp(sched), int(split), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream(stream))
     _check(rc, "alcop_gemm_splitk")
+    return C
+
+
+SPLITK_STATIC_BYTES = 32 << 20
+
+
+def alcop_gemm_splitk_static(A, B, C, split, sched=None, alpha=1.0, bias=None, act=0,
+                             transB=False, stream=None, transA=False):
+    """alcop_gemm_splitk without a workspace argument: the partial tiles go to the library's own
+    device array (at most SPLITK_STATIC_BYTES); the call allocates nothing."""
+    if A.dim() == 2:
+        b, sA, sB, sC = 1, 0, 0, 0
+        K, M = A.shape if transA else A.shape[::-1]
+        N = B.shape[0] if transB else B.shape[1]
+        lda, ldb, ldc = A.stride(0), B.stride(0), C.stride(0)
+    else:
+        b = A.shape[0]
+        K, M = A.shape[1:] if transA else A.shape[:0:-1]
+        N = B.shape[1] if transB else B.shape[2]
+        lda, ldb, ldc = A.stride(1), B.stride(1), C.stride(1)
+        sA, sB, sC = A.stride(0), B.stride(0), C.stride(0)
+    e = _epilogue(alpha, bias, act)
+    rc = lib().alcop_gemm_splitk_static(_ptr(A), _ptr(B), _ptr(C), b, M, N, K, lda, ldb, ldc, sA, sB,
+                                        sC, int(transA), int(transB), _dtype_code(A), _dtype_code(C),
+                                        ctypes.byref(e), _sp(sched), int(split), _stream(stream))
+    _check(rc, "alcop_gemm_splitk_static")
     return C
 
 

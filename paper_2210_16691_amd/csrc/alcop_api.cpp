@@ -499,14 +499,21 @@ int auto_splitk(const alcop_problem& p, int split, alcop_sched* out, int* split_
   return have ? ALCOP_OK : ALCOP_ERR_SCHED;
 }
 
+static_assert(kSplitkStaticBytes == ALCOP_SPLITK_STATIC_BYTES, "scratch size: header and device array");
+
+// ws == nullptr with own_scratch: the partial tiles go to the library's own device array.
 int run_splitk(const Call& c, const alcop_sched* sched, int split, void* ws, size_t ws_bytes,
-               void* stream)
+               void* stream, bool own_scratch = false)
 {
   int rc = check_call(c);
   if (rc) return rc;
   if (split < 0 || split > 64) return ALCOP_ERR_SHAPE;
-  if (!ws) return ALCOP_ERR_NULL;
-  if (!aligned16(ws)) return ALCOP_ERR_ALIGN;
+  if (own_scratch) {
+    ws_bytes = ALCOP_SPLITK_STATIC_BYTES;
+  } else {
+    if (!ws) return ALCOP_ERR_NULL;
+    if (!aligned16(ws)) return ALCOP_ERR_ALIGN;
+  }
   const alcop_problem prob = problem_of(c);
   alcop_sched s;
   if (!sched || sched->bm == 0) {
@@ -526,9 +533,16 @@ int run_splitk(const Call& c, const alcop_sched* sched, int split, void* ws, siz
   if (s.l2_prefetch != 0) return ALCOP_ERR_SCHED;
   rc = span_check(c, s);
   if (rc) return rc;
-  const Split sp = make_split(c.K, s.bk, split, ws);
+  Split sp = make_split(c.K, s.bk, split, ws);
   const double need = 4.0 * sp.nz * c.batch * c.M * c.N;
   if (need > (double)ws_bytes) return ALCOP_ERR_SIZE;
+  if (own_scratch) {
+    // sizes are settled; only now touch the device (the first call per device looks the array up)
+    void* mine = nullptr;
+    size_t have = 0;
+    if (splitk_scratch(&mine, &have) != hipSuccess || need > (double)have) return ALCOP_ERR_LAUNCH;
+    sp.ws = mine;
+  }
   return launch_call(c, s, e, (hipStream_t)stream, &sp);
 }
 
@@ -730,6 +744,22 @@ int alcop_gemm_splitk(const void* A, const void* B, void* C, int batch, int M, i
     c.act = ep->act;
   }
   return run_splitk(c, sched, split, workspace, workspace_bytes, hip_stream);
+}
+
+int alcop_gemm_splitk_static(const void* A, const void* B, void* C, int batch, int M, int N, int K,
+                             long lda, long ldb, long ldc, long strideA, long strideB,
+                             long strideC, int transA, int transB, alcop_dtype in, alcop_dtype out,
+                             const alcop_epilogue* ep, const alcop_sched* sched, int split,
+                             void* hip_stream)
+{
+  Call c = gemm_call(batch > 1 ? ALCOP_OP_BMM : ALCOP_OP_GEMM, A, B, C, batch, M, N, K, lda, ldb, ldc,
+                     strideA, strideB, strideC, transA, transB, in, out);
+  if (ep) {
+    c.alpha = ep->alpha;
+    c.bias = ep->bias;
+    c.act = ep->act;
+  }
+  return run_splitk(c, sched, split, nullptr, 0, hip_stream, true);
 }
 
 int alcop_conv2d_igemm_splitk(const void* x, const void* w, void* y, int N, int H, int W, int C,

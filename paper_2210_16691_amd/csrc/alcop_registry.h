@@ -37,6 +37,12 @@ void register_splitk_conv(std::vector<KernelEntry>&);
 // Second step of a split-K product (alcop_splitk.hip.h).
 hipError_t launch_splitk_reduce(const ReduceParams& p, dim3 grid, hipStream_t st);
 
+// Device address and size of the library's own scratch array on the current device (set up on
+// the first call per device; allocates nothing afterwards).  Its size is part of the interface
+// (ALCOP_SPLITK_STATIC_BYTES in alcop.h; alcop_api.cpp checks that the two agree).
+constexpr size_t kSplitkStaticBytes = 32u << 20;
+hipError_t splitk_scratch(void** ptr, size_t* bytes);
+
 const std::vector<KernelEntry>& registry();
 
 }  // namespace alcop

@@ -181,6 +181,14 @@ hipError_t launch_splitk_reduce(const ReduceParams& p, dim3 grid, hipStream_t)
   emu::run_grid(&reduce_entry, &p, REDUCE_THREADS, 0, grid.x, grid.y, grid.z);
   return hipSuccess;
 }
+// host stand-in for the library's device scratch array
+hipError_t splitk_scratch(void** ptr, size_t* bytes)
+{
+  static std::vector<unsigned char> mem(kSplitkStaticBytes);
+  *ptr = mem.data();
+  *bytes = mem.size();
+  return hipSuccess;
+}
 void register_f16_kn_big(std::vector<KernelEntry>&) {}
 void register_f16_kn_small(std::vector<KernelEntry>&) {}
 void register_bf16_kn(std::vector<KernelEntry>&) {}
