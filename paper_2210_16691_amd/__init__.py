@@ -183,12 +183,79 @@ def _check(rc, what):
         raise AlcopError(rc, what)
 
 
+def _same_place(*ts):
+    dev = ts[0].device
+    for t in ts:
+        if t is not None and t.device != dev:
+            raise ValueError("operands live on different devices: %s and %s" % (dev, t.device))
+
+
+def _mm_shapes(A, B, C, transA, transB, bias=None):
+    """Operand checks of the matrix entry points, before anything reaches the C call: the library
+    sizes its buffer descriptors from (M, N, K) and the leading dimensions it is told, so a tensor
+    that does not have that shape would be read or written past its end on the GPU.  Returns
+    (batch, M, N, K)."""
+    if A.dim() != B.dim() or A.dim() != C.dim() or A.dim() not in (2, 3):
+        raise ValueError("A, B, C must all be 2-D (GEMM) or all 3-D (batched)")
+    if A.dtype != B.dtype:
+        raise ValueError("A and B differ in dtype: %s and %s" % (A.dtype, B.dtype))
+    _dtype_code(C)
+    _same_place(A, B, C, bias)
+    for name, t in (("A", A), ("B", B), ("C", C)):
+        if t.stride(-1) != 1:
+            raise ValueError("%s: the last dimension must be contiguous" % name)
+    b = A.shape[0] if A.dim() == 3 else 1
+    if A.dim() == 3 and (B.shape[0] != b or C.shape[0] != b):
+        raise ValueError("batch sizes differ: %d, %d, %d" % (b, B.shape[0], C.shape[0]))
+    K, M = tuple(A.shape[-2:]) if transA else tuple(A.shape[-2:])[::-1]
+    Kb, N = tuple(B.shape[-2:])[::-1] if transB else tuple(B.shape[-2:])
+    if Kb != K:
+        raise ValueError("reduction extents differ: A has K = %d, B has K = %d" % (K, Kb))
+    if tuple(C.shape[-2:]) != (M, N):
+        raise ValueError("C is %s, expected %s" % (tuple(C.shape[-2:]), (M, N)))
+    if bias is not None and (bias.dim() != 1 or bias.shape[0] != N or not bias.is_contiguous()
+                             or bias.element_size() != 4 or not bias.is_floating_point()):
+        raise ValueError("bias must be a contiguous fp32 vector of N = %d values" % N)
+    return b, M, N, K
+
+
+def _conv_shapes(x, w, y, stride, pad, krsc=False, bias=None):
+    """Operand checks of the convolution entry points.  Returns (N, H, W, C, K, R, S)."""
+    if x.dim() != 4 or w.dim() != 4 or y.dim() != 4:
+        raise ValueError("x, w, y must be 4-D (NHWC, RSCK or KRSC, NPQK)")
+    if x.dtype != w.dtype:
+        raise ValueError("x and w differ in dtype: %s and %s" % (x.dtype, w.dtype))
+    _dtype_code(y)
+    _same_place(x, w, y, bias)
+    for name, t in (("x", x), ("w", w), ("y", y)):
+        if not t.is_contiguous():
+            raise ValueError("%s must be contiguous" % name)
+    N, H, W, Cc = x.shape
+    if krsc:
+        K, R, S, Cw = w.shape
+    else:
+        R, S, Cw, K = w.shape
+    if Cw != Cc:
+        raise ValueError("channel counts differ: x has %d, w has %d" % (Cc, Cw))
+    if stride[0] <= 0 or stride[1] <= 0 or pad[0] < 0 or pad[1] < 0:
+        raise ValueError("stride must be positive and padding non-negative")
+    P = (H + 2 * pad[0] - R) // stride[0] + 1
+    Q = (W + 2 * pad[1] - S) // stride[1] + 1
+    if tuple(y.shape) != (N, P, Q, K):
+        raise ValueError("y is %s, expected %s" % (tuple(y.shape), (N, P, Q, K)))
+    if bias is not None and (bias.dim() != 1 or bias.shape[0] != K or not bias.is_contiguous()
+                             or bias.element_size() != 4 or not bias.is_floating_point()):
+        raise ValueError("bias must be a contiguous fp32 vector of K = %d values" % K)
+    return N, H, W, Cc, K, R, S
+
+
 # ---- the entry points (same names as the C ABI) ----------------------------------------------
 def alcop_gemm(A, B, C, sched=None, transB=False, stream=None, transA=False):
     """C[M,N] = A . B  (A is [M,K], or [K,M] if transA; B is [K,N], or [N,K] if transB).  Tensors
     are 2-D CUDA tensors whose last dimension is contiguous; C's dtype selects the output type."""
-    K, M = A.shape if transA else A.shape[::-1]
-    N = B.shape[0] if transB else B.shape[1]
+    if A.dim() != 2:
+        raise ValueError("alcop_gemm takes 2-D tensors")
+    _, M, N, K = _mm_shapes(A, B, C, transA, transB)
     rc = lib().alcop_gemm(_ptr(A), _ptr(B), _ptr(C), M, N, K, A.stride(0), B.stride(0), C.stride(0),
                           int(transA), int(transB), _dtype_code(A), _dtype_code(C), _sp(sched),
                           _stream(stream))
@@ -198,9 +265,9 @@ def alcop_gemm(A, B, C, sched=None, transB=False, stream=None, transA=False):
 
 def alcop_bmm(A, B, C, sched=None, transB=False, stream=None, transA=False):
     """Batched: A [b,M,K] (or [b,K,M] if transA), B [b,K,N] (or [b,N,K] if transB), C [b,M,N]."""
-    b = A.shape[0]
-    K, M = A.shape[1:] if transA else A.shape[:0:-1]
-    N = B.shape[1] if transB else B.shape[2]
+    if A.dim() != 3:
+        raise ValueError("alcop_bmm takes 3-D tensors")
+    b, M, N, K = _mm_shapes(A, B, C, transA, transB)
     rc = lib().alcop_bmm(_ptr(A), _ptr(B), _ptr(C), b, M, N, K, A.stride(1), B.stride(1), C.stride(1),
                          A.stride(0), B.stride(0), C.stride(0), int(transA), int(transB),
                          _dtype_code(A), _dtype_code(C), _sp(sched), _stream(stream))
@@ -214,8 +281,9 @@ def _epilogue(alpha, bias, act):
 
 def alcop_gemm_fused(A, B, C, alpha=1.0, bias=None, act=0, sched=None, transB=False, stream=None):
     """C = act(alpha * A.B + bias[j]); bias is an fp32 CUDA vector of N values or None; act 1 = ReLU."""
-    M, K = A.shape
-    N = B.shape[0] if transB else B.shape[1]
+    if A.dim() != 2:
+        raise ValueError("alcop_gemm_fused takes 2-D tensors")
+    _, M, N, K = _mm_shapes(A, B, C, False, transB, bias)
     e = _epilogue(alpha, bias, act)
     rc = lib().alcop_gemm_fused(_ptr(A), _ptr(B), _ptr(C), M, N, K, A.stride(0), B.stride(0),
                                 C.stride(0), 0, int(transB), _dtype_code(A), _dtype_code(C),
@@ -225,8 +293,9 @@ def alcop_gemm_fused(A, B, C, alpha=1.0, bias=None, act=0, sched=None, transB=Fa
 
 
 def alcop_bmm_fused(A, B, C, alpha=1.0, bias=None, act=0, sched=None, transB=False, stream=None):
-    b, M, K = A.shape
-    N = B.shape[1] if transB else B.shape[2]
+    if A.dim() != 3:
+        raise ValueError("alcop_bmm_fused takes 3-D tensors")
+    b, M, N, K = _mm_shapes(A, B, C, False, transB, bias)
     e = _epilogue(alpha, bias, act)
     rc = lib().alcop_bmm_fused(_ptr(A), _ptr(B), _ptr(C), b, M, N, K, A.stride(1), B.stride(1),
                                C.stride(1), A.stride(0), B.stride(0), C.stride(0), 0, int(transB),
@@ -238,8 +307,7 @@ def alcop_bmm_fused(A, B, C, alpha=1.0, bias=None, act=0, sched=None, transB=Fal
 
 def alcop_conv2d_igemm(x, w, y, stride=(1, 1), pad=(0, 0), sched=None, stream=None):
     """x NHWC [N,H,W,C], w RSCK [R,S,C,K], y NPQK [N,P,Q,K]; all contiguous."""
-    N, H, W, Cc = x.shape
-    R, S, _, K = w.shape
+    N, H, W, Cc, K, R, S = _conv_shapes(x, w, y, stride, pad)
     rc = lib().alcop_conv2d_igemm(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cc, K, R, S,
                                   stride[0], stride[1], pad[0], pad[1],
                                   _dtype_code(x), _dtype_code(y), _sp(sched), _stream(stream))
@@ -256,15 +324,11 @@ def alcop_gemm_splitk(A, B, C, split, workspace, sched=None, alpha=1.0, bias=Non
     """C = act(alpha * A.B + bias) with the reduction axis cut into `split` slices (0 = the model's
     choice).  A, B, C are 2-D (GEMM) or 3-D (batched) tensors; `workspace` is a tensor of at least
     alcop_splitk_workspace_bytes(batch, M, N, split) bytes that the call overwrites."""
+    b, M, N, K = _mm_shapes(A, B, C, transA, transB, bias)
     if A.dim() == 2:
-        b, sA, sB, sC = 1, 0, 0, 0
-        K, M = A.shape if transA else A.shape[::-1]
-        N = B.shape[0] if transB else B.shape[1]
+        sA, sB, sC = 0, 0, 0
         lda, ldb, ldc = A.stride(0), B.stride(0), C.stride(0)
     else:
-        b = A.shape[0]
-        K, M = A.shape[1:] if transA else A.shape[:0:-1]
-        N = B.shape[1] if transB else B.shape[2]
         lda, ldb, ldc = A.stride(1), B.stride(1), C.stride(1)
         sA, sB, sC = A.stride(0), B.stride(0), C.stride(0)
     e = _epilogue(alpha, bias, act)
@@ -283,15 +347,11 @@ def alcop_gemm_splitk_static(A, B, C, split, sched=None, alpha=1.0, bias=None, a
                              transB=False, stream=None, transA=False):
     """alcop_gemm_splitk without a workspace argument: the partial tiles go to the library's own
     device array (at most SPLITK_STATIC_BYTES); the call allocates nothing."""
+    b, M, N, K = _mm_shapes(A, B, C, transA, transB, bias)
     if A.dim() == 2:
-        b, sA, sB, sC = 1, 0, 0, 0
-        K, M = A.shape if transA else A.shape[::-1]
-        N = B.shape[0] if transB else B.shape[1]
+        sA, sB, sC = 0, 0, 0
         lda, ldb, ldc = A.stride(0), B.stride(0), C.stride(0)
     else:
-        b = A.shape[0]
-        K, M = A.shape[1:] if transA else A.shape[:0:-1]
-        N = B.shape[1] if transB else B.shape[2]
         lda, ldb, ldc = A.stride(1), B.stride(1), C.stride(1)
         sA, sB, sC = A.stride(0), B.stride(0), C.stride(0)
     e = _epilogue(alpha, bias, act)
@@ -305,8 +365,8 @@ def alcop_gemm_splitk_static(A, B, C, split, sched=None, alpha=1.0, bias=None, a
 def alcop_conv2d_igemm_splitk(x, w, y, split, workspace, stride=(1, 1), pad=(0, 0), sched=None,
                               stream=None):
     """alcop_conv2d_igemm with the reduction axis R*S*C cut into `split` slices."""
-    N, H, W, Cc = x.shape
-    R, S, _, K = w.shape
+    N, H, W, Cc, K, R, S = _conv_shapes(x, w, y, stride, pad)
+    _same_place(x, workspace)
     rc = lib().alcop_conv2d_igemm_splitk(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cc, K, R, S,
                                          stride[0], stride[1], pad[0], pad[1],
                                          _dtype_code(x), _dtype_code(y), _sp(sched), int(split),
@@ -336,11 +396,7 @@ def alcop_splitk_auto(prob: "Problem", split: int = 0):
 def alcop_conv2d_igemm_fused(x, w, y, stride=(1, 1), pad=(0, 0), alpha=1.0, bias=None, act=0,
                              krsc=False, sched=None, stream=None):
     """y = act(alpha * conv(x, w) + bias[k]); w is RSCK [R,S,C,K], or KRSC [K,R,S,C] if krsc."""
-    N, H, W, Cc = x.shape
-    if krsc:
-        K, R, S, _ = w.shape
-    else:
-        R, S, _, K = w.shape
+    N, H, W, Cc, K, R, S = _conv_shapes(x, w, y, stride, pad, krsc, bias)
     e = _epilogue(alpha, bias, act)
     rc = lib().alcop_conv2d_igemm_fused(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cc, K, R, S,
                                         stride[0], stride[1], pad[0], pad[1], _dtype_code(x),
@@ -352,8 +408,7 @@ def alcop_conv2d_igemm_fused(x, w, y, stride=(1, 1), pad=(0, 0), alpha=1.0, bias
 
 def alcop_conv2d_igemm_krsc(x, w, y, stride=(1, 1), pad=(0, 0), sched=None, stream=None):
     """x NHWC [N,H,W,C], w KRSC [K,R,S,C], y NPQK [N,P,Q,K]; all contiguous."""
-    N, H, W, Cc = x.shape
-    K, R, S, _ = w.shape
+    N, H, W, Cc, K, R, S = _conv_shapes(x, w, y, stride, pad, krsc=True)
     rc = lib().alcop_conv2d_igemm_krsc(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cc, K, R, S,
                                        stride[0], stride[1], pad[0], pad[1],
                                        _dtype_code(x), _dtype_code(y), _sp(sched), _stream(stream))

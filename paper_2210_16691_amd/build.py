@@ -19,6 +19,7 @@ CSRC = os.path.join(HERE, "csrc")
 ROOT = os.path.dirname(HERE)
 OBJDIR = os.path.join(ROOT, "_build", "alcop")
 LIB = os.path.join(HERE, "libalcop.so")
+DIAG_LIB = os.path.join(HERE, "libalcop_diag.so")     # measurement aid: csrc/diag_*.hip
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -30,7 +31,12 @@ FLAGS = [
 
 
 def sources():
-    return sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
+    hip = [f for f in glob.glob(os.path.join(CSRC, "*.hip")) if not os.path.basename(f).startswith("diag_")]
+    return sorted(hip + glob.glob(os.path.join(CSRC, "*.cpp")))
+
+
+def diag_sources():
+    return sorted(glob.glob(os.path.join(CSRC, "diag_*.hip")))
 
 
 def _deps_mtime(obj: str) -> float:
@@ -64,11 +70,13 @@ def _compile(src: str, force: bool) -> str:
 def build(jobs: int = 8, force: bool = False) -> str:
     os.makedirs(OBJDIR, exist_ok=True)
     srcs = sources()
+    dsrcs = diag_sources()
     with cf.ThreadPoolExecutor(max_workers=max(1, min(jobs, 16))) as ex:
-        objs = list(ex.map(lambda s: _compile(s, force), srcs))
-    if force or not os.path.exists(LIB) or any(os.path.getmtime(o) > os.path.getmtime(LIB) for o in objs):
-        cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
-        subprocess.check_call(cmd)
+        allobjs = list(ex.map(lambda s: _compile(s, force), srcs + dsrcs))
+    objs, dobjs = allobjs[:len(srcs)], allobjs[len(srcs):]
+    for lib, obs in ((LIB, objs), (DIAG_LIB, dobjs)):
+        if obs and (force or not os.path.exists(lib) or any(os.path.getmtime(o) > os.path.getmtime(lib) for o in obs)):
+            subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib] + obs)
     return LIB
 
 

@@ -1,5 +1,7 @@
 // Helpers used by the instance shards: launcher template and cartesian-product macros.
 #pragma once
+#include <mutex>
+
 #include "alcop_gfx950.hip.h"
 #include "alcop_registry.h"
 
@@ -8,17 +10,17 @@ namespace alcop {
 template <class C>
 hipError_t launch_instance(const Params& p, dim3 grid, hipStream_t st)
 {
-  // (two threads making the first launch together both set the attribute: harmless)
-  static bool attr_set = false;
-  if (!attr_set) {
-    // LDS rings above the default 64 KB per-block limit need an explicit opt-in (the patch
-    // convolution sizes its LDS per call, up to the 160 KB a block can have).
-    hipError_t e = hipFuncSetAttribute((const void*)alcop_mainloop<C, Gfx950>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       C::AM == 3 ? 160 * 1024 : C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // LDS rings above the default 64 KB per-block limit need an explicit opt-in (the patch
+  // convolution sizes its LDS per call, up to the 160 KB a block can have).  Once per kernel
+  // and process; concurrent first launches wait for the one that sets it.
+  static std::once_flag once;
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(once, [] {
+    attr_rc = hipFuncSetAttribute((const void*)alcop_mainloop<C, Gfx950>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  C::AM == 3 ? 160 * 1024 : C::LDS_BYTES);
+  });
+  if (attr_rc != hipSuccess) return attr_rc;
   alcop_mainloop<C, Gfx950><<<grid, dim3(C::NT), dynamic_lds_bytes<C>(p), st>>>(p);
   return hipGetLastError();
 }

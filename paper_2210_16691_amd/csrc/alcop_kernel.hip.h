@@ -21,8 +21,8 @@
 // applied on the source side by choosing which 16-byte chunk of the global tile each lane
 // fetches (the paper applies shared-memory swizzling to all its kernels, Sec. 6.1).
 //   K-contiguous tile (A stored M x K, B stored N x K): rows of BK halves, CPR = BK/8 chunks per
-//     row, physical chunk = logical chunk XOR ((row/2) mod CPR) (XOR (row mod CPR) for the
-//     256-byte rows of BK = 128); read with ds_read_b128.
+//     row, RPL = 128/BK rows per 256-byte bank line; physical chunk = logical chunk XOR
+//     ((row/RPL) mod CPR); read with ds_read_b128.
 //   M/N-contiguous tile (A stored K x M, B stored K x N): one row per k, physical chunk =
 //     logical chunk XOR (((k/RPB) mod min(4,BX/32)) << 2); read with ds_read_b64_tr_b16,
 //     which hands each lane 4 consecutive k of one column (and runs at ~2x the LDS bandwidth
@@ -109,16 +109,17 @@ struct Opnd {
   // 128-byte lines (or parts of lines) in the k-slice of one tile, for the L2 touches
   static constexpr int LINES = LAY == LAY_K ? BX : BK * ((BX * 2) / 128);
   static_assert(BYTES % (NT * 16) == 0, "loads per thread");
-  // a k-contiguous row of 16 chunks (BK = 128) spans all 64 banks, so consecutive rows must
-  // differ; shorter rows share a 256-byte bank line in pairs and differ per pair
-  static constexpr bool WIDE = LAY == LAY_K && CPR >= 16;
-  static_assert(LAY == LAY_K ? (WIDE ? RSTEP % CPR == 0 : (RSTEP % 2 == 0 && (RSTEP / 2) % CPR == 0))
-                             : (RSTEP % (4 * RPB) == 0), "swizzle period");
+  // K-contiguous layout: the LDS has 64 banks of 4 bytes, so RPL = 256 / (row bytes) rows share
+  // one 256-byte bank line (4, 2, 1 rows for BK = 32, 64, 128).  A 16-byte read instruction is
+  // served 16 lanes (= 16 consecutive rows of one chunk column) per clock; they hit 16 distinct
+  // 16-byte bank groups when rows in the same position of consecutive bank lines take different
+  // chunks: physical chunk = logical chunk XOR ((row / RPL) mod CPR).
+  static constexpr int RPL = (128 / BK) > 1 ? (128 / BK) : 1;
+  static_assert(LAY == LAY_K ? (RSTEP % (RPL * CPR) == 0) : (RSTEP % (4 * RPB) == 0), "swizzle period");
   // logical 16-byte chunk -> physical chunk within LDS row `row`
   __device__ static __forceinline__ int swz(int row)
   {
-    if constexpr (WIDE) return row % CPR;
-    return LAY == LAY_K ? ((row >> 1) % CPR) : (((row / RPB) % GM) << 2);
+    return LAY == LAY_K ? ((row / RPL) % CPR) : (((row / RPB) % GM) << 2);
   }
 };
 

@@ -254,3 +254,44 @@ def test_tuning_cache_named_by_the_environment(tmp_path):
     env["ALCOP_TUNE_CACHE"] = str(tmp_path / "missing.txt")          # ignored, the model decides
     out = subprocess.check_output([sys.executable, "-c", code], env=env, cwd=ROOT).decode()
     assert out.strip() != "(64, 64, 32, 32, 32, 2, 2, 1, 1, 0, 0)"
+
+
+def test_binding_rejects_mismatched_operands_before_the_c_call():
+    # the library sizes its buffer descriptors from the shapes it is told; the binding must not
+    # tell it shapes the tensors do not have (CPU tensors here: nothing may reach the C call)
+    import torch
+    f16, f32 = torch.float16, torch.float32
+    A, B, C = torch.zeros(128, 64, dtype=f16), torch.zeros(64, 136, dtype=f16), torch.zeros(128, 136, dtype=f16)
+    s = al.sched(128, 128, 64, 64, 64, 1, 1, 0)
+    with pytest.raises(ValueError, match="reduction extents"):
+        al.alcop_gemm(A, torch.zeros(56, 136, dtype=f16), C, s)
+    with pytest.raises(ValueError, match="reduction extents"):
+        al.alcop_gemm(A, B, torch.zeros(128, 64, dtype=f16), s, transB=True)     # B read as [N, K]: K = 136
+    with pytest.raises(ValueError, match="C is"):
+        al.alcop_gemm(A, B, torch.zeros(128, 128, dtype=f16), s)
+    with pytest.raises(ValueError, match="dtype"):
+        al.alcop_gemm(A, B.to(torch.bfloat16), C, s)
+    with pytest.raises(ValueError, match="contiguous"):
+        al.alcop_gemm(torch.zeros(64, 128, dtype=f16).t(), B, C, s)
+    with pytest.raises(ValueError, match="2-D"):
+        al.alcop_gemm(A[None], B[None], C[None], s)
+    with pytest.raises(KeyError):
+        al.alcop_gemm(A, B, C.to(torch.float64), s)
+    Ab, Bb, Cb = A[None].repeat(3, 1, 1), B[None].repeat(2, 1, 1), C[None].repeat(3, 1, 1)
+    with pytest.raises(ValueError, match="batch sizes"):
+        al.alcop_bmm(Ab, Bb, Cb, s)
+    with pytest.raises(ValueError, match="bias"):
+        al.alcop_gemm_fused(A, B, C, 1.0, torch.zeros(128, dtype=f32), 0, s)
+    with pytest.raises(ValueError, match="reduction extents"):
+        al.alcop_gemm_splitk(A, torch.zeros(72, 136, dtype=f16), C, 2, torch.zeros(1 << 16), s)
+    x, w = torch.zeros(2, 8, 8, 64, dtype=f16), torch.zeros(3, 3, 64, 32, dtype=f16)
+    with pytest.raises(ValueError, match="y is"):
+        al.alcop_conv2d_igemm(x, w, torch.zeros(2, 8, 8, 64, dtype=f16), (1, 1), (1, 1))
+    with pytest.raises(ValueError, match="y is"):
+        al.alcop_conv2d_igemm(x, w, torch.zeros(2, 8, 8, 32, dtype=f16), (1, 1), (0, 0))   # 6 x 6 without padding
+    with pytest.raises(ValueError, match="channel counts"):
+        al.alcop_conv2d_igemm(x, torch.zeros(3, 3, 32, 32, dtype=f16), torch.zeros(2, 8, 8, 32, dtype=f16), (1, 1), (1, 1))
+    with pytest.raises(ValueError, match="channel counts"):
+        al.alcop_conv2d_igemm_krsc(x, w, torch.zeros(2, 8, 8, 3, dtype=f16), (1, 1), (1, 1))  # w read as KRSC: C = 32
+    with pytest.raises(ValueError, match="contiguous"):
+        al.alcop_conv2d_igemm(x.permute(0, 2, 1, 3), w, torch.zeros(2, 8, 8, 32, dtype=f16), (1, 1), (1, 1))
