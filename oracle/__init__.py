@@ -57,6 +57,8 @@ def _load():
         lib.alcop_oracle_bmm.argtypes = [u16p, u16p, f64p, i, i, i, i, l, l, l, l, l, l, i, i, i]
         lib.alcop_oracle_conv2d.restype = i
         lib.alcop_oracle_conv2d.argtypes = [u16p, u16p, f64p] + [i] * 12
+        lib.alcop_oracle_conv2d_dilated.restype = i
+        lib.alcop_oracle_conv2d_dilated.argtypes = [u16p, u16p, f64p] + [i] * 14
         _lib = lib
     return _lib
 
@@ -124,8 +126,10 @@ def bmm(A, B, dtype: int, transA: bool = False, transB: bool = False) -> np.ndar
     return C
 
 
-def conv2d(x, w, dtype: int, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
-    """y[n,p,q,k] = sum_{r,s,c} x[n, p*sh-ph+r, q*sw-pw+s, c] * w[r,s,c,k] in fp64 (zero padding)."""
+def conv2d(x, w, dtype: int, stride=(1, 1), pad=(0, 0), dilation=(1, 1)) -> np.ndarray:
+    """y[n,p,q,k] = sum_{r,s,c} x[n, p*sh-ph+r*dh, q*sw-pw+s*dw, c] * w[r,s,c,k] in fp64 (zero padding).
+    Dilation (1, 1) is the paper's operator and runs the plain seven-loop routine; any other
+    dilation runs the routine that carries the two extra factors."""
     x, w = _u16(x), _u16(w)
     N, H, W, C = x.shape
     R, S, C2, K = w.shape
@@ -133,11 +137,16 @@ def conv2d(x, w, dtype: int, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
         raise ValueError("channel counts differ")
     sh, sw = stride
     ph, pw = pad
-    P = (H + 2 * ph - R) // sh + 1
-    Q = (W + 2 * pw - S) // sw + 1
+    dh, dw = dilation
+    P = (H + 2 * ph - dh * (R - 1) - 1) // sh + 1
+    Q = (W + 2 * pw - dw * (S - 1) - 1) // sw + 1
     y = np.empty((N, P, Q, K), dtype=np.float64)
-    rc = _load().alcop_oracle_conv2d(_p16(x), _p16(w), _p64(y), N, H, W, C, K, R, S,
-                                     sh, sw, ph, pw, dtype)
+    if (dh, dw) == (1, 1):
+        rc = _load().alcop_oracle_conv2d(_p16(x), _p16(w), _p64(y), N, H, W, C, K, R, S,
+                                         sh, sw, ph, pw, dtype)
+    else:
+        rc = _load().alcop_oracle_conv2d_dilated(_p16(x), _p16(w), _p64(y), N, H, W, C, K, R, S,
+                                                 sh, sw, ph, pw, dh, dw, dtype)
     if rc:
         raise MemoryError("oracle conv2d failed (%d)" % rc)
     return y

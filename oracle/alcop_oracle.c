@@ -192,3 +192,51 @@ int alcop_oracle_conv2d(const uint16_t *x, const uint16_t *w, double *y,
     free(wd);
     return 0;
 }
+
+/*
+ * Dilated convolution (an extension for real workloads; the paper's operators have dilation 1):
+ * tap (r, s) reads x[n][p*stride_h - pad_h + r*dil_h][q*stride_w - pad_w + s*dil_w][c], zero
+ * outside the image; P = (H + 2*pad_h - dil_h*(R-1) - 1)/stride_h + 1, Q likewise.  Same seven
+ * loops and the same summation order (r, s, c ascending) as alcop_oracle_conv2d.
+ */
+int alcop_oracle_conv2d_dilated(const uint16_t *x, const uint16_t *w, double *y,
+                                int N, int H, int W, int C, int K, int R, int S,
+                                int stride_h, int stride_w, int pad_h, int pad_w,
+                                int dil_h, int dil_w, int dtype)
+{
+    int P = (H + 2 * pad_h - dil_h * (R - 1) - 1) / stride_h + 1;
+    int Q = (W + 2 * pad_w - dil_w * (S - 1) - 1) / stride_w + 1;
+    size_t wn = (size_t)R * S * C * K;
+    double *wd = (double *)malloc(wn * sizeof(double) + 8);
+    if (!wd)
+        return -1;
+    for (size_t i = 0; i < wn; i++)
+        wd[i] = decode(w[i], dtype);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; n++)
+        for (int p = 0; p < P; p++)
+            for (int q = 0; q < Q; q++) {
+                double *out = y + (((size_t)n * P + p) * Q + q) * K;
+                for (int k = 0; k < K; k++)
+                    out[k] = 0.0;
+                for (int r = 0; r < R; r++) {
+                    int ih = p * stride_h - pad_h + r * dil_h;
+                    if (ih < 0 || ih >= H)
+                        continue;
+                    for (int s = 0; s < S; s++) {
+                        int iw = q * stride_w - pad_w + s * dil_w;
+                        if (iw < 0 || iw >= W)
+                            continue;
+                        const uint16_t *xp = x + (((size_t)n * H + ih) * W + iw) * C;
+                        for (int c = 0; c < C; c++) {
+                            double xv = decode(xp[c], dtype);
+                            const double *wp = wd + (((size_t)r * S + s) * C + c) * K;
+                            for (int k = 0; k < K; k++)
+                                out[k] += xv * wp[k];
+                        }
+                    }
+                }
+            }
+    free(wd);
+    return 0;
+}

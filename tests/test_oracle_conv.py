@@ -123,3 +123,51 @@ def test_matches_torch_conv2d_on_integers():
             x.to(torch.float64).permute(0, 3, 1, 2), w.to(torch.float64).permute(3, 2, 0, 1),
             stride=stride, padding=pad).permute(0, 2, 3, 1).numpy()
         assert np.array_equal(got, ref)
+
+
+# ---- dilation (not in the paper; the dilated routine is pinned on its own) -----------------------
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=9, W=8, C=3, K=4, R=3, S=3, stride=(1, 1), pad=(2, 2), dil=(2, 2)),
+    dict(N=1, H=11, W=10, C=2, K=3, R=3, S=2, stride=(2, 1), pad=(3, 0), dil=(3, 2)),
+    dict(N=2, H=7, W=7, C=4, K=2, R=2, S=3, stride=(1, 2), pad=(0, 1), dil=(1, 2)),
+])
+def test_dilated_conv_against_a_library_convolution_on_integers(geom):
+    g = geom
+    x = wl.small_ints((g["N"], g["H"], g["W"], g["C"]), "f16", 41)
+    w = wl.small_ints((g["R"], g["S"], g["C"], g["K"]), "f16", 42)
+    got = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, g["stride"], g["pad"], g["dil"])
+    want = torch.nn.functional.conv2d(x.double().permute(0, 3, 1, 2), w.double().permute(3, 2, 0, 1),
+                                      stride=g["stride"], padding=g["pad"], dilation=g["dil"])
+    assert np.array_equal(got, want.permute(0, 2, 3, 1).numpy())
+
+
+def test_dilated_routine_with_dilation_one_is_the_plain_routine():
+    import ctypes
+    x = wl.normal((2, 6, 7, 5), "bf16", 43, 0.5)
+    w = wl.normal((3, 2, 5, 4), "bf16", 44, 0.5)
+    plain = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.BF16, (2, 1), (1, 1))
+    xb, wb = np.ascontiguousarray(wl.bits(x)), np.ascontiguousarray(wl.bits(w))
+    y = np.empty_like(plain)
+    rc = oracle._load().alcop_oracle_conv2d_dilated(oracle._p16(xb), oracle._p16(wb), oracle._p64(y),
+                                                   2, 6, 7, 5, 4, 3, 2, 2, 1, 1, 1, 1, 1, oracle.BF16)
+    assert rc == 0 and np.array_equal(y, plain)
+
+
+def test_dilated_delta_taps_shift_by_the_dilation():
+    # one nonzero tap (r0, s0) with identity channels: y[p, q] = x[p - pad + r0*dh, q - pad + s0*dw]
+    N, H, W, C = 1, 8, 9, 4
+    x = wl.normal((N, H, W, C), "f16", 45, 1.0)
+    xv = _vals(x)
+    dh, dw, ph, pw = 2, 3, 2, 3
+    for (r0, s0) in [(0, 0), (1, 1), (2, 0), (0, 2), (2, 2)]:
+        w = torch.zeros(3, 3, C, C, dtype=torch.float16)
+        w[r0, s0] = torch.eye(C, dtype=torch.float16)
+        got = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, (1, 1), (ph, pw), (dh, dw))
+        assert got.shape == (N, H, W, C)          # "same" padding for a 3x3 filter: pad = dilation
+        want = np.zeros_like(got)
+        for p in range(H):
+            for q in range(W):
+                ih, iw = p - ph + r0 * dh, q - pw + s0 * dw
+                if 0 <= ih < H and 0 <= iw < W:
+                    want[:, p, q, :] = xv[:, ih, iw, :]
+        assert np.array_equal(got, want), (r0, s0)
