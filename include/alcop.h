@@ -186,6 +186,21 @@ int alcop_conv2d_igemm_fused(const void* x, const void* w, void* y, int N, int H
                              int krsc, const alcop_sched* sched /* host */, void* hip_stream);
 
 /*
+ * Dilated convolution (beyond the paper's dilation-1 operators; the gather of Sec. 4's
+ * load-and-use loop only changes its addresses): filter tap (r, s) reads
+ * x[n][p*stride_h - pad_h + r*dil_h][q*stride_w - pad_w + s*dil_w][c];
+ * P = (H + 2*pad_h - dil_h*(R-1) - 1)/stride_h + 1, Q likewise.  dil_h, dil_w >= 1.
+ * krsc: 0 = weights [R][S][C][K], 1 = [K][R][S][C]; ep (host, may be NULL) as for
+ * alcop_conv2d_igemm_fused.  Schedules as for alcop_conv2d_igemm, except that the LDS-resident
+ * patch variant (variant 1) needs dilation 1.  Errors as for alcop_conv2d_igemm.
+ */
+int alcop_conv2d_igemm_dilated(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                               int K, int R, int S, int stride_h, int stride_w, int pad_h,
+                               int pad_w, int dil_h, int dil_w, int krsc, alcop_dtype in,
+                               alcop_dtype out, const alcop_epilogue* ep /* host, may be NULL */,
+                               const alcop_sched* sched /* host */, void* hip_stream);
+
+/*
  * Split-K: the reduction axis is cut into `split` slices of whole k-tiles, every slice is a block
  * of its own (grid.z), and a second kernel adds the slices' fp32 partial tiles in ascending
  * order, applies f(.) and converts to the output type.  For outputs with few tiles and a long

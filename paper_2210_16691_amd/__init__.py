@@ -25,7 +25,7 @@ EXPORTS = [
     "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
-    "alcop_corrector_features", "alcop_corrector_fit", "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_gemm_splitk_static", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_sched_variants",
+    "alcop_corrector_features", "alcop_corrector_fit", "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_gemm_splitk_static", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_conv2d_igemm_dilated", "alcop_sched_variants",
 ]
 
 
@@ -123,6 +123,8 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
                                     vp, sz, vp]
     L.alcop_gemm_splitk_static.restype = i
     L.alcop_gemm_splitk_static.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, ep, sp, i, vp]
+    L.alcop_conv2d_igemm_dilated.restype = i
+    L.alcop_conv2d_igemm_dilated.argtypes = [vp, vp, vp] + [i] * 14 + [i, i, ep, sp, vp]
     L.alcop_conv2d_igemm_splitk.restype = i
     L.alcop_conv2d_igemm_splitk.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, i, vp, sz, vp]
     L.alcop_tune_splitk.restype = i
@@ -219,7 +221,7 @@ def _mm_shapes(A, B, C, transA, transB, bias=None):
     return b, M, N, K
 
 
-def _conv_shapes(x, w, y, stride, pad, krsc=False, bias=None):
+def _conv_shapes(x, w, y, stride, pad, krsc=False, bias=None, dilation=(1, 1)):
     """Operand checks of the convolution entry points.  Returns (N, H, W, C, K, R, S)."""
     if x.dim() != 4 or w.dim() != 4 or y.dim() != 4:
         raise ValueError("x, w, y must be 4-D (NHWC, RSCK or KRSC, NPQK)")
@@ -237,10 +239,10 @@ def _conv_shapes(x, w, y, stride, pad, krsc=False, bias=None):
         R, S, Cw, K = w.shape
     if Cw != Cc:
         raise ValueError("channel counts differ: x has %d, w has %d" % (Cc, Cw))
-    if stride[0] <= 0 or stride[1] <= 0 or pad[0] < 0 or pad[1] < 0:
-        raise ValueError("stride must be positive and padding non-negative")
-    P = (H + 2 * pad[0] - R) // stride[0] + 1
-    Q = (W + 2 * pad[1] - S) // stride[1] + 1
+    if stride[0] <= 0 or stride[1] <= 0 or pad[0] < 0 or pad[1] < 0 or dilation[0] <= 0 or dilation[1] <= 0:
+        raise ValueError("stride and dilation must be positive and padding non-negative")
+    P = (H + 2 * pad[0] - dilation[0] * (R - 1) - 1) // stride[0] + 1
+    Q = (W + 2 * pad[1] - dilation[1] * (S - 1) - 1) // stride[1] + 1
     if tuple(y.shape) != (N, P, Q, K):
         raise ValueError("y is %s, expected %s" % (tuple(y.shape), (N, P, Q, K)))
     if bias is not None and (bias.dim() != 1 or bias.shape[0] != K or not bias.is_contiguous()
@@ -403,6 +405,20 @@ def alcop_conv2d_igemm_fused(x, w, y, stride=(1, 1), pad=(0, 0), alpha=1.0, bias
                                         _dtype_code(y), ctypes.byref(e), int(krsc), _sp(sched),
                                         _stream(stream))
     _check(rc, "alcop_conv2d_igemm_fused")
+    return y
+
+
+def alcop_conv2d_igemm_dilated(x, w, y, stride=(1, 1), pad=(0, 0), dilation=(1, 1), alpha=1.0, bias=None,
+                               act=0, krsc=False, sched=None, stream=None):
+    """y = act(alpha * conv(x, w) + bias[k]) with filter taps dilation[0] rows / dilation[1] columns
+    apart; w is RSCK [R,S,C,K], or KRSC [K,R,S,C] if krsc."""
+    N, H, W, Cc, K, R, S = _conv_shapes(x, w, y, stride, pad, krsc, bias, dilation)
+    e = _epilogue(alpha, bias, act)
+    rc = lib().alcop_conv2d_igemm_dilated(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cc, K, R, S,
+                                          stride[0], stride[1], pad[0], pad[1], dilation[0], dilation[1],
+                                          int(krsc), _dtype_code(x), _dtype_code(y), ctypes.byref(e),
+                                          _sp(sched), _stream(stream))
+    _check(rc, "alcop_conv2d_igemm_dilated")
     return y
 
 

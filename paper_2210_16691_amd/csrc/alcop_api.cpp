@@ -54,6 +54,7 @@ struct Call {
   alcop_dtype in, out;
   // conv geometry
   int cN, cH, cW, cC, cK, cR, cS, csh, csw, cph, cpw, cP, cQ;
+  int cdh, cdw;   // dilation
   // fused epilogue
   float alpha;
   const void* bias;
@@ -278,7 +279,8 @@ struct Patch {
 };
 int patch_of(const Call& c, const alcop_sched& s, const KernelEntry* e, Patch* out)
 {
-  if (c.op != ALCOP_OP_CONV2D || c.csh != 1 || c.csw != 1) return ALCOP_ERR_SCHED;
+  if (c.op != ALCOP_OP_CONV2D || c.csh != 1 || c.csw != 1 || c.cdh != 1 || c.cdw != 1)
+    return ALCOP_ERR_SCHED;
   Patch pt;
   pt.wp = c.cW + 2 * c.cpw;                                    // row length of the padded image
   const long positions = (long)(c.cP - 1) * pt.wp + c.cQ;      // output positions per image
@@ -363,6 +365,8 @@ int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipSt
     p.csw = c.csw;
     p.cph = c.cph;
     p.cpw = c.cpw;
+    p.cdh = c.cdh;
+    p.cdw = c.cdw;
     p.a_span = (unsigned)(2L * c.cN * c.cH * c.cW * c.cC);
     if (e->am == 3) {
       Patch pt;
@@ -576,14 +580,16 @@ Call gemm_call(alcop_op op, const void* A, const void* B, void* C, int batch, in
 
 int conv_call(Call* c, const void* x, const void* w, void* y, int N, int H, int W, int Cc, int K,
               int R, int S, int sh, int sw, int ph, int pw, alcop_dtype in, alcop_dtype out,
-              int krsc = 0)
+              int krsc = 0, int dh = 1, int dw = 1)
 {
   std::memset(c, 0, sizeof(*c));
   if (N <= 0 || H <= 0 || W <= 0 || Cc <= 0 || K <= 0 || R <= 0 || S <= 0 || sh <= 0 || sw <= 0 ||
-      ph < 0 || pw < 0)
+      ph < 0 || pw < 0 || dh <= 0 || dw <= 0)
     return ALCOP_ERR_SHAPE;
-  if (H + 2 * ph < R || W + 2 * pw < S) return ALCOP_ERR_SHAPE;
-  const long P = (H + 2 * ph - R) / sh + 1, Q = (W + 2 * pw - S) / sw + 1;
+  // extent of the dilated filter: dil * (R - 1) + 1
+  const long eh = (long)dh * (R - 1) + 1, ew = (long)dw * (S - 1) + 1;
+  if (H + 2L * ph < eh || W + 2L * pw < ew) return ALCOP_ERR_SHAPE;
+  const long P = (H + 2L * ph - eh) / sh + 1, Q = (W + 2L * pw - ew) / sw + 1;
   const long Mg = (long)N * P * Q, Kg = (long)R * S * Cc;
   if (Mg > 0x7fffffffL || Kg > 0x7fffffffL) return ALCOP_ERR_SHAPE;
   c->op = ALCOP_OP_CONV2D;
@@ -613,6 +619,8 @@ int conv_call(Call* c, const void* x, const void* w, void* y, int N, int H, int 
   c->cpw = pw;
   c->cP = (int)P;
   c->cQ = (int)Q;
+  c->cdh = dh;
+  c->cdw = dw;
   c->alpha = 1.0f;
   return ALCOP_OK;
 }
@@ -721,6 +729,24 @@ int alcop_conv2d_igemm(const void* x, const void* w, void* y, int N, int H, int 
   Call c;
   int rc = conv_call(&c, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, in, out);
   if (rc) return rc;
+  return run(c, sched, hip_stream);
+}
+
+int alcop_conv2d_igemm_dilated(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                               int K, int R, int S, int stride_h, int stride_w, int pad_h,
+                               int pad_w, int dil_h, int dil_w, int krsc, alcop_dtype in,
+                               alcop_dtype out, const alcop_epilogue* ep, const alcop_sched* sched,
+                               void* hip_stream)
+{
+  Call c;
+  int rc = conv_call(&c, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, in, out,
+                     krsc ? 1 : 0, dil_h, dil_w);
+  if (rc) return rc;
+  if (ep) {
+    c.alpha = ep->alpha;
+    c.bias = ep->bias;
+    c.act = ep->act;
+  }
   return run(c, sched, hip_stream);
 }
 

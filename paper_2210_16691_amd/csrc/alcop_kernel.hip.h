@@ -58,6 +58,7 @@ struct Params {
   int raster, group_m;         // block -> tile order
   // convolution geometry (AM != 0): x is NHWC, A rows are (img, p, q)
   int cH, cW, cC, cP, cQ, cS, csh, csw, cph, cpw;
+  int cdh, cdw;                // dilation: filter tap (r, s) reads row ih0 + r * cdh, column iw0 + s * cdw
   unsigned a_span, b_span;     // conv: bytes of x; unused otherwise
   // third pipeline level (HBM -> L2): every wave touches lines of k-tile kt + pf_dist when it
   // issues k-tile kt; the lines of a panel are split among the pf_pa (pf_pb) blocks that share it
@@ -352,6 +353,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   int ih0[NLA > 0 ? NLA : 1], iw0[NLA > 0 ? NLA : 1];
   uint32_t coff[NLA > 0 ? NLA : 1];
   int cr = 0, cs = 0, cc0 = 0;                // (r, s, c0) of the next k-tile to issue
+  int crd = 0, csd = 0;                       // r * dilation_h, s * dilation_w of that tap
   bool a_in_k = true;                         // AM == 2: this lane's chunk lies below K
   int a_k8 = 0;                               // AM == 2: k of this lane's chunk within a k-tile
   if constexpr (C::SK && C::AM == 1) {        // the slice starts at tap k0 / C, channel k0 % C
@@ -359,6 +361,8 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     cc0 = k0 - tap * p.cC;
     cr = tap / p.cS;
     cs = tap - cr * p.cS;
+    crd = cr * p.cdh;
+    csd = cs * p.cdw;
   }
   // AM == 3: the tile is BM consecutive positions j of one image's output space laid out with
   // the padded row length Wp (positions with column >= Q are computed and not stored); for
@@ -403,6 +407,8 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       cc0 = kc - tap * p.cC;
       cr = tap / p.cS;
       cs = tap - cr * p.cS;
+      crd = cr * p.cdh;
+      csd = cs * p.cdw;
     }
 #pragma unroll
     for (int i = 0; i < NLA; i++) {
@@ -463,7 +469,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     if constexpr (C::AM == 0)
       st_ka = st_live ? (uint32_t)kt * la.kstep : 0x80000000u;
     else if constexpr (C::AM != 3)
-      st_tap = (uint32_t)(((cr * p.cW + cs) * p.cC + cc0) * 2);
+      st_tap = (uint32_t)(((crd * p.cW + csd) * p.cC + cc0) * 2);
     if constexpr (C::AM == 2) a_in_k = kt * BK + a_k8 < Kb;
     st_kb = st_live ? (uint32_t)kt * lb.kstep : 0x80000000u;
   };
@@ -473,8 +479,8 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       if constexpr (C::AM == 0) {
         HW::dma16(la.rsrc, st_voffA + st_ka + (uint32_t)i * la.step, st_dst + i * (NWAVES * 1024));
       } else {
-        bool ok = st_live && (unsigned)(ih0[i] + cr) < (unsigned)p.cH &&
-                  (unsigned)(iw0[i] + cs) < (unsigned)p.cW;
+        bool ok = st_live && (unsigned)(ih0[i] + crd) < (unsigned)p.cH &&
+                  (unsigned)(iw0[i] + csd) < (unsigned)p.cW;
         if constexpr (C::AM == 2) ok = ok && a_in_k;
         HW::dma16(la.rsrc, ok ? coff[i] + st_tap : 0x80000000u, st_dst + i * (NWAVES * 1024));
       }
@@ -490,11 +496,17 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   auto stage_end = [&]() {
     if constexpr (C::AM == 1) {
       cc0 += BK;
-      if (cc0 == p.cC) { cc0 = 0; cs++; if (cs == p.cS) { cs = 0; cr++; } }
+      if (cc0 == p.cC) {
+        cc0 = 0; cs++; csd += p.cdw;
+        if (cs == p.cS) { cs = 0; csd = 0; cr++; crd += p.cdh; }
+      }
     }
     if constexpr (C::AM == 2) {
       cc0 += BK;
-      while (cc0 >= p.cC) { cc0 -= p.cC; cs++; if (cs == p.cS) { cs = 0; cr++; } }
+      while (cc0 >= p.cC) {
+        cc0 -= p.cC; cs++; csd += p.cdw;
+        if (cs == p.cS) { cs = 0; csd = 0; cr++; crd += p.cdh; }
+      }
     }
   };
   auto issue = [&](int kt, int slot) {

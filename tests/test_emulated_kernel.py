@@ -539,3 +539,33 @@ def test_k_tile_of_128_all_policies_and_l2_touches():
             errs, ok = _gemm_case("f16", 0, transB, s, 2 * s.bm - 24, s.bn + 8, 5 * 128 + (0 if s.l2_prefetch else 40),
                                   policy, out="f32")
             assert not errs and ok, (repr(s), policy, errs[:4])
+
+
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=9, W=8, C=64, K=64, R=3, S=3, stride=(1, 1), pad=(2, 2), dil=(2, 2), krsc=False),
+    dict(N=1, H=12, W=11, C=32, K=72, R=3, S=2, stride=(2, 1), pad=(3, 0), dil=(3, 2), krsc=False),
+    dict(N=2, H=8, W=8, C=24, K=64, R=3, S=3, stride=(1, 1), pad=(2, 1), dil=(2, 1), krsc=True),
+])
+def test_dilated_convolution_exact_and_in_bounds(geom):
+    g = geom
+    x = wl.small_ints((g["N"], g["H"], g["W"], g["C"]), "f16", 131)
+    w = wl.small_ints((g["R"], g["S"], g["C"], g["K"]), "f16", 132)
+    ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, g["stride"], g["pad"], g["dil"])
+    wk = w.permute(3, 0, 1, 2).contiguous() if g["krsc"] else w
+    prob = al.problem(al.OP_CONV2D, ref.shape[0] * ref.shape[1] * ref.shape[2], g["K"],
+                      g["R"] * g["S"] * g["C"], al.F16, al.F32, conv_C=g["C"], transB=g["krsc"])
+    scheds = emu.space(prob)
+    assert scheds
+    for n, s in enumerate(scheds):
+        y = torch.full(tuple(ref.shape), float("nan"), dtype=torch.float32)
+        errs = emu.call(al.alcop_conv2d_igemm_dilated, x, wk, y, g["stride"], g["pad"], g["dil"],
+                        krsc=g["krsc"], sched=s, reads=[x, wk], writes=[y], policy=emu.POLICIES[n % 4])
+        assert not errs, (repr(s), errs[:4])
+        assert _exact(y, ref), repr(s)
+    # the patch kernels keep dilation 1
+    if g["C"] == 64 and not g["krsc"]:
+        y = torch.zeros(tuple(ref.shape), dtype=torch.float32)
+        with pytest.raises(al.AlcopError) as e:
+            emu.call(al.alcop_conv2d_igemm_dilated, x, wk, y, g["stride"], g["pad"], g["dil"],
+                     sched=al.sched(256, 64, 64, 64, 64, 3, 2, 1, 1, 0, 1), reads=[x, wk], writes=[y])
+        assert e.value.code == al.ERR_SCHED

@@ -89,3 +89,39 @@ def test_config_resnet_convs_full(name):
     ref1 = oracle.conv2d(wl.bits(x1), wl.bits(w), oracle.F16, (1, 1), (1, 1))
     got1 = to_f64(run_conv(x1, w, "f32", None))
     assert np.max(np.abs(got1 - ref1)) < 1e-4 * max(1.0, float(np.max(np.abs(ref1))))
+
+
+@pytest.mark.parametrize("geom", [
+    dict(N=2, H=14, W=12, C=64, K=64, R=3, S=3, stride=(1, 1), pad=(2, 2), dil=(2, 2), krsc=False),
+    dict(N=3, H=13, W=11, C=32, K=72, R=3, S=2, stride=(2, 1), pad=(3, 0), dil=(3, 2), krsc=False),
+    dict(N=2, H=10, W=9, C=40, K=64, R=3, S=3, stride=(1, 1), pad=(4, 1), dil=(4, 1), krsc=True),
+])
+def test_dilated_convolution_integers_bit_exact_every_schedule(geom):
+    g = geom
+    x = wl.small_ints((g["N"], g["H"], g["W"], g["C"]), "f16", 311)
+    w = wl.small_ints((g["R"], g["S"], g["C"], g["K"]), "f16", 312)
+    ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, g["stride"], g["pad"], g["dil"])
+    wd = (w.permute(3, 0, 1, 2).contiguous() if g["krsc"] else w).to(DEV)
+    xd = x.to(DEV)
+    prob = al.problem(al.OP_CONV2D, ref.shape[0] * ref.shape[1] * ref.shape[2], g["K"],
+                      g["R"] * g["S"] * g["C"], al.F16, al.F32, conv_C=g["C"], transB=g["krsc"])
+    scheds = feasible(prob)
+    assert scheds
+    for s in scheds + [None]:
+        y = torch.full(tuple(ref.shape), float("nan"), dtype=torch.float32, device=DEV)
+        al.alcop_conv2d_igemm_dilated(xd, wd, y, g["stride"], g["pad"], g["dil"], krsc=g["krsc"], sched=s)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_f64(y), ref), repr(s)
+
+
+def test_dilated_convolution_random_with_bias_relu():
+    N, H, W, C, K = 4, 28, 28, 64, 128
+    x = wl.normal((N, H, W, C), "f16", 313, 1.0)
+    w = wl.normal((3, 3, C, K), "f16", 314, 1.0 / (9 * C) ** 0.5)
+    bias = wl.normal((K,), "f16", 315, 0.5).float()
+    ref = oracle.epilogue(oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, (1, 1), (2, 2), (2, 2)),
+                          1.0, bias.double().numpy(), 1)
+    y = torch.full((N, H, W, K), float("nan"), dtype=torch.float16, device=DEV)
+    al.alcop_conv2d_igemm_dilated(x.to(DEV), w.to(DEV), y, (1, 1), (2, 2), (2, 2), bias=bias.to(DEV), act=1)
+    torch.cuda.synchronize()
+    assert_close(to_f64(y), ref, "dilated conv + bias + relu")

@@ -295,3 +295,17 @@ def test_binding_rejects_mismatched_operands_before_the_c_call():
         al.alcop_conv2d_igemm_krsc(x, w, torch.zeros(2, 8, 8, 3, dtype=f16), (1, 1), (1, 1))  # w read as KRSC: C = 32
     with pytest.raises(ValueError, match="contiguous"):
         al.alcop_conv2d_igemm(x.permute(0, 2, 1, 3), w, torch.zeros(2, 8, 8, 32, dtype=f16), (1, 1), (1, 1))
+
+
+def test_diagnostic_library_exports_what_its_header_declares():
+    from paper_2210_16691_amd import diag
+    text = open(os.path.join(ROOT, "include", "alcop_diag.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(alcop_diag_[a-z0-9_]+)\s*\(", text)))
+    assert set(names) == set(diag.EXPORTS)
+    L = diag.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+    cfgs = diag.configs()
+    assert len(cfgs) >= 3 and all(c.split()[0] in ("f16", "bf16") for c in cfgs)
+    assert L.alcop_diag_config_name(len(cfgs)) is None
