@@ -83,7 +83,20 @@ typedef struct {
                       /* once and forms the filter taps by shifted LDS reads, so only the    */
                       /* weights stream through the ring.  Needs stride 1, RSCK weights,     */
                       /* bk equal to the channel count, and a patch that fits the LDS;       */
-                      /* a call that does not meet this returns ALCOP_ERR_SCHED              */
+                      /* a call that does not meet this returns ALCOP_ERR_SCHED.             */
+                      /* 2 = persistent producer / consumer kernel (any operator): a block    */
+                      /* stays on its compute unit and walks a list of output tiles; four     */
+                      /* producer waves keep the S-stage ring filled across tile boundaries   */
+                      /* while four consumer waves multiply and store, so the loads of the    */
+                      /* next tile overlap the epilogue of this one (the paper's load / use   */
+                      /* overlap, Sec. 1, carried across tiles; for short reduction axes,     */
+                      /* Sec. 6.1).  Needs stages >= 2, reg_stages = 2, fuse_inner = 0,       */
+                      /* l2_prefetch = 0, four waves' worth of wave tiles per block tile, and */
+                      /* for a convolution a k-tile that divides the channel count.  Results  */
+                      /* are bit-identical to the default kernels of the same tile.  The      */
+                      /* number of blocks is one or two per compute unit (by LDS), at most    */
+                      /* the number of tiles; the environment variable ALCOP_STREAM_BLOCKS    */
+                      /* (a positive integer, read at every launch) overrides it              */
 } alcop_sched;
 
 /* Problem description used by the model / tuner / feasibility entry points. */

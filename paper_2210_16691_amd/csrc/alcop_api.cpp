@@ -35,6 +35,7 @@ const std::vector<KernelEntry>& registry()
     register_bk128(t);
     register_deep(t);
     register_pf(t);
+    register_stream(t);
     register_splitk_gemm(t);
     register_splitk_conv(t);
     return t;
@@ -98,7 +99,7 @@ const KernelEntry* find_entry(const alcop_problem& p, const alcop_sched& s, int 
         e.am == am && e.bm == s.bm &&
         e.bn == s.bn && e.bk == s.bk && e.wm == s.wm && e.wn == s.wn && e.stages == s.stages &&
         e.reg_stages == s.reg_stages && e.fuse == (s.fuse_inner ? 1 : 0) &&
-        e.pf == (s.l2_prefetch > 0 ? 1 : 0))
+        e.pf == (s.l2_prefetch > 0 ? 1 : 0) && e.st == (s.variant == 2 ? 1 : 0))
       return &e;
   return nullptr;
 }
@@ -133,8 +134,13 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
   if (s.raster != 0 && s.raster != 1) return ALCOP_ERR_SCHED;
   if (s.l2_prefetch < 0 || s.l2_prefetch > 64 || (s.l2_prefetch > 0 && s.raster != 1))
     return ALCOP_ERR_SCHED;
-  if (s.variant != 0 &&
+  if (s.variant != 0 && s.variant != 2 &&
       !(s.variant == 1 && p.op == ALCOP_OP_CONV2D && !p.transB && p.conv_C == s.bk && sk == 0))
+    return ALCOP_ERR_SCHED;
+  // variant 2, the persistent producer / consumer kernels: two register stages inside a k-tile,
+  // no fusion across k-tiles, no L2 touches, no split-K; convolutions with one tap per k-tile
+  if (s.variant == 2 && (s.reg_stages != 2 || s.fuse_inner || s.l2_prefetch != 0 || sk != 0 ||
+                         s.stages < 2 || (p.op == ALCOP_OP_CONV2D && p.conv_C % s.bk != 0)))
     return ALCOP_ERR_SCHED;
   const KernelEntry* e = find_entry(p, s, sk);
   if (!e) return ALCOP_ERR_SCHED;
@@ -157,7 +163,7 @@ int default_l2_prefetch(int bk) { return 256 / bk; }
 // tuner for them, never picked by the model on its own.  These are the patch convolution (its
 // feasibility depends on the call, not only on the problem description) and the kernels with a
 // k-tile of 128 (two stages of a 128 x 128 tile fill the LDS: a trade the tuner should measure).
-bool opt_in(const KernelEntry& e) { return e.am == 3 || e.bk == 128; }
+bool opt_in(const KernelEntry& e) { return e.am == 3 || e.bk == 128 || e.st == 1; }
 
 // variants: 0 = the default kernels; 1 = also the opt-in kernels; 2 = only those.
 std::vector<alcop_sched> space_of(const alcop_problem& p, int sk = 0, int variants = 0)
@@ -171,7 +177,7 @@ std::vector<alcop_sched> space_of(const alcop_problem& p, int sk = 0, int varian
     {
       // a kernel with the third (HBM -> L2) level is offered with that level on
       v.push_back(alcop_sched{e.bm, e.bn, e.bk, e.wm, e.wn, e.stages, e.reg_stages, e.fuse, 1,
-                              e.pf ? default_l2_prefetch(e.bk) : 0, e.am == 3 ? 1 : 0});
+                              e.pf ? default_l2_prefetch(e.bk) : 0, e.am == 3 ? 1 : (e.st ? 2 : 0)});
     }
   return v;
 }
@@ -321,6 +327,20 @@ Split make_split(int K, int bk, int requested, void* ws)
   return sp;
 }
 
+// Compute units of the current device (256 on an MI355X; that number also when no device answers).
+int compute_units()
+{
+  static std::once_flag once;
+  static int n = 256;
+  std::call_once(once, [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+  });
+  return n;
+}
+
 int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipStream_t st,
                 const Split* split = nullptr)
 {
@@ -380,6 +400,20 @@ int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipSt
     }
   }
   dim3 grid((unsigned)(p.ntm * p.ntn), (unsigned)c.batch, 1);
+  if (e->st) {
+    // persistent blocks: as many as stay resident (by LDS, at most two per compute unit), never
+    // more than there are tiles; ALCOP_STREAM_BLOCKS overrides the count (a tuning and test knob)
+    const long total = (long)p.ntm * p.ntn * c.batch;
+    if (total > 0x7fffffffL) return ALCOP_ERR_SHAPE;
+    long blocks = (long)compute_units() * std::max(1, std::min(2, (160 * 1024) / e->lds_bytes));
+    if (const char* env = std::getenv("ALCOP_STREAM_BLOCKS")) {
+      const long v = std::atol(env);
+      if (v > 0) blocks = v;
+    }
+    p.sgrid = (int)std::min(total, blocks);
+    p.sbatch = c.batch;
+    grid = dim3((unsigned)p.sgrid, 1, 1);
+  }
   if (split) {
     // the slices write plain fp32 tiles into the workspace; f(.) and the conversion to the
     // output type happen in the reduction step

@@ -45,7 +45,7 @@ void add_instance(std::vector<KernelEntry>& t)
 {
   if constexpr (instance_feasible(BM, BN, BK, WM, WN, S, R, F, PF)) {
     using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF>;
-    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF, C::LDS_BYTES, C::NT,
+    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF, 0, C::LDS_BYTES, C::NT,
                             C::L, C::PATCH_OFF, &launch_instance<C>});
   }
 }

@@ -1,0 +1,45 @@
+// Launcher and table helpers of the persistent producer / consumer kernels; included by their
+// instance shard only, so that work on that kernel does not recompile the other shards.
+#pragma once
+#include "alcop_instantiate.hip.h"
+#include "alcop_stream.hip.h"
+
+namespace alcop {
+
+// Persistent producer / consumer kernels (schedule variant 2).
+template <class C>
+hipError_t launch_stream(const Params& p, dim3 grid, hipStream_t st)
+{
+  static std::once_flag once;
+  static hipError_t attr_rc = hipSuccess;
+  std::call_once(once, [] {
+    attr_rc = hipFuncSetAttribute((const void*)alcop_stream<C, Gfx950>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+  });
+  if (attr_rc != hipSuccess) return attr_rc;
+  alcop_stream<C, Gfx950><<<grid, dim3(C::NT), C::LDS_BYTES, st>>>(p);
+  return hipGetLastError();
+}
+
+constexpr bool stream_feasible(int bm, int bn, int bk, int wm, int wn, int s)
+{
+  const int waves = (bm / wm) * (bn / wn);
+  const int a = bm * bk * 2, b = bn * bk * 2;
+  if (waves != 4) return false;
+  if (a % (256 * 16) || b % (256 * 16)) return false;
+  if (s * (a + b) + waves * 32 * (wn * 4 + 16) > 160 * 1024) return false;
+  if ((s - 2) * ((a + b) / (256 * 16)) > 63) return false;
+  return s >= 2 && s <= 4;
+}
+
+template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int BL, int AM, int AL = 0>
+void add_stream(std::vector<KernelEntry>& t)
+{
+  if constexpr (stream_feasible(BM, BN, BK, WM, WN, S)) {
+    using C = SCfg<DT, BM, BN, BK, WM, WN, S, BL, AM, AL>;
+    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, 2, 0, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT,
+                            C::L, 0, &launch_stream<C>});
+  }
+}
+
+}  // namespace alcop

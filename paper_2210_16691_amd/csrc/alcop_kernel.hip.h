@@ -75,6 +75,9 @@ struct Params {
   // convolution with an LDS-resident input patch (AM == 3): filter height, row length of the
   // zero-padded image, tiles per image, direct-to-LDS loads per thread that bring in the patch
   int cR, cWp, ntj, patch_loads;
+  // persistent producer / consumer kernels (alcop_stream.hip.h): blocks launched and batch count;
+  // block b works on tiles b, b + sgrid, b + 2 sgrid, ... of the ntm * ntn * sbatch tiles
+  int sgrid, sbatch;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

@@ -12,6 +12,7 @@ struct KernelEntry {
   int dt, bm, bn, bk, wm, wn, stages, reg_stages, fuse, bl, am, al;
   int sk;   // 1: split-K variant (grid.z slices of the reduction axis, fp32 partial tiles)
   int pf;   // 1: the kernel has the HBM -> L2 touch level (schedules with l2_prefetch > 0)
+  int st;   // 1: persistent producer / consumer kernel (schedule variant 2)
   int lds_bytes, threads, loads_per_stage;
   int patch_off;   // am == 3: LDS offset of the input patch (its size is per call)
   hipError_t (*launch)(const Params&, dim3, hipStream_t);
@@ -31,6 +32,7 @@ void register_conv_patch(std::vector<KernelEntry>&);
 void register_bk128(std::vector<KernelEntry>&);
 void register_deep(std::vector<KernelEntry>&);
 void register_pf(std::vector<KernelEntry>&);
+void register_stream(std::vector<KernelEntry>&);
 void register_splitk_gemm(std::vector<KernelEntry>&);
 void register_splitk_conv(std::vector<KernelEntry>&);
 

@@ -157,8 +157,8 @@ int alcop_diag_time(int config, int drop, const void* A, const void* B, void* C,
     if (rc == 0 && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = -2;
     if (rc == 0 && ms * 1e3 / iters < best) best = ms * 1e3 / iters;
   }
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
   if (rc) return rc;
   *mean_us = best;
   return 0;

@@ -49,6 +49,7 @@
 #include <vector>
 
 #include "alcop_kernel.hip.h"
+#include "alcop_stream.hip.h"
 
 namespace emu {
 
@@ -595,6 +596,11 @@ template <class C>
 void mainloop_entry(const void* p)
 {
   alcop::alcop_mainloop<C, Emu>(*(const alcop::Params*)p);
+}
+template <class C>
+void stream_entry(const void* p)
+{
+  alcop::alcop_stream<C, Emu>(*(const alcop::Params*)p);
 }
 
 }  // namespace emu

@@ -23,8 +23,23 @@ template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int R, int F, i
 void add(std::vector<KernelEntry>& t)
 {
   using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF>;
-  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF, C::LDS_BYTES, C::NT, C::L,
+  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF, 0, C::LDS_BYTES, C::NT, C::L,
                           C::PATCH_OFF, &launch_emulated<C>});
+}
+
+template <class C>
+hipError_t launch_emulated_stream(const Params& p, dim3 grid, hipStream_t)
+{
+  emu::run_grid(&emu::stream_entry<C>, &p, C::NT, C::LDS_BYTES, grid.x, grid.y, grid.z);
+  return hipSuccess;
+}
+
+template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int BL, int AM, int AL = 0>
+void add_stream(std::vector<KernelEntry>& t)
+{
+  using C = SCfg<DT, BM, BN, BK, WM, WN, S, BL, AM, AL>;
+  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, 2, 0, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT, C::L, 0,
+                          &launch_emulated_stream<C>});
 }
 
 #if EMU_PART == 0
@@ -120,6 +135,20 @@ void emu_part_5(std::vector<KernelEntry>& t)
   add<0, 256, 64, 64, 64, 64, 3, 4, 1, 0, 3>(t);       // input patch resident in LDS
   add<0, 128, 128, 64, 64, 64, 3, 4, 1, 0, 0, 0, 1>(t);   // split-K
 }
+#elif EMU_PART == 6
+void emu_part_6(std::vector<KernelEntry>& t)
+{
+  // persistent producer / consumer kernels (schedule variant 2)
+  add_stream<0, 128, 128, 64, 64, 64, 3, 0, 0>(t);
+  add_stream<0, 128, 128, 64, 64, 64, 2, 1, 0>(t);     // B stored N x K
+  add_stream<0, 128, 64, 32, 64, 32, 4, 0, 0>(t);
+  add_stream<0, 64, 64, 64, 32, 32, 3, 1, 0>(t);
+  add_stream<1, 64, 64, 32, 32, 32, 2, 0, 0>(t);       // bf16
+  add_stream<0, 256, 64, 64, 64, 64, 2, 0, 0>(t);
+  add_stream<0, 128, 64, 64, 64, 32, 3, 0, 1>(t);      // convolution gather
+  add_stream<0, 64, 64, 32, 32, 32, 4, 0, 1>(t);
+  add_stream<0, 256, 64, 64, 64, 64, 2, 0, 1>(t);
+}
 #elif EMU_PART == 3
 void emu_part_3(std::vector<KernelEntry>& t)
 {
@@ -154,6 +183,7 @@ void emu_part_2(std::vector<KernelEntry>&);
 void emu_part_3(std::vector<KernelEntry>&);
 void emu_part_4(std::vector<KernelEntry>&);
 void emu_part_5(std::vector<KernelEntry>&);
+void emu_part_6(std::vector<KernelEntry>&);
 void register_f16_kn_mid(std::vector<KernelEntry>& t)
 {
   emu_part_0(t);
@@ -162,6 +192,7 @@ void register_f16_kn_mid(std::vector<KernelEntry>& t)
   emu_part_3(t);
   emu_part_4(t);
   emu_part_5(t);
+  emu_part_6(t);
 }
 void register_splitk_gemm(std::vector<KernelEntry>&) {}
 void register_splitk_conv(std::vector<KernelEntry>&) {}
@@ -171,6 +202,7 @@ void register_conv_patch(std::vector<KernelEntry>&) {}
 void register_bk128(std::vector<KernelEntry>&) {}
 void register_deep(std::vector<KernelEntry>&) {}
 void register_pf(std::vector<KernelEntry>&) {}
+void register_stream(std::vector<KernelEntry>&) {}
 
 static void reduce_entry(const void* p)
 {

@@ -470,8 +470,8 @@ def test_conv_patch_variant_exact_and_in_bounds(geom):
     prob = al.problem(al.OP_CONV2D, g["N"] * P * Q, g["K"], g["R"] * g["S"] * g["C"], al.F16, al.F16,
                       conv_C=g["C"])
     with emu._swapped():
-        scheds = al.alcop_sched_variants(prob)
-        assert scheds and all(s.variant == 1 and al.alcop_sched_supported(prob, s) == al.OK for s in scheds)
+        scheds = [s for s in al.alcop_sched_variants(prob) if s.variant == 1]
+        assert scheds and all(al.alcop_sched_supported(prob, s) == al.OK for s in scheds)
         assert all(s.variant == 0 for s in al.alcop_sched_space(prob))
     for n, s in enumerate(scheds):
         for policy in (emu.POLICIES[n % 4], emu.POLICIES[(n + 2) % 4]):
@@ -568,4 +568,106 @@ def test_dilated_convolution_exact_and_in_bounds(geom):
         with pytest.raises(al.AlcopError) as e:
             emu.call(al.alcop_conv2d_igemm_dilated, x, wk, y, g["stride"], g["pad"], g["dil"],
                      sched=al.sched(256, 64, 64, 64, 64, 3, 2, 1, 1, 0, 1), reads=[x, wk], writes=[y])
+        assert e.value.code == al.ERR_SCHED
+
+
+# ---- persistent producer / consumer kernels (schedule variant 2) ---------------------------------
+def _stream_scheds(prob):
+    return [s for s in emu.space(prob, opt_in=True) if s.variant == 2]
+
+
+@pytest.mark.parametrize("dt,transB", [("f16", 0), ("f16", 1), ("bf16", 0)])
+def test_stream_kernels_batched_every_block_count(dt, transB, monkeypatch):
+    # one block walks all tiles; two and three blocks interleave them; more blocks than tiles; one
+    # k-tile per tile (the pipeline is all fill and drain), two with a partial one, five
+    prob = al.problem(al.OP_BMM, 512, 512, 512, ADT[dt], ADT[dt], batch=3, transB=bool(transB))
+    scheds = _stream_scheds(prob)
+    assert scheds
+    for n, s in enumerate(scheds):
+        for blocks in (1, 2, 3, 1000):
+            monkeypatch.setenv("ALCOP_STREAM_BLOCKS", str(blocks))
+            for nk, extra in ((1, 0), (2, 8), (5, 0)):
+                b, M, N, K = 2, 2 * s.bm + 24, s.bn + 8, nk * s.bk + extra
+                A = wl.small_ints((b, M, K), dt, 500 + n)
+                B = wl.small_ints((b, N, K) if transB else (b, K, N), dt, 501 + n)
+                C = torch.full((b, M, N), float("nan"), dtype=torch.float32)
+                policy = emu.POLICIES[(n + blocks + nk) % 4]
+                errs = emu.call(al.alcop_bmm, A, B, C, s, transB=bool(transB), reads=[A, B], writes=[C],
+                                policy=policy)
+                ref = oracle.bmm(wl.bits(A), wl.bits(B), ODT[dt], transB=bool(transB))
+                assert not errs, (repr(s), blocks, K, policy, errs[:4])
+                assert _exact(C, ref), (repr(s), blocks, K, policy)
+
+
+def test_stream_kernels_convolution_gemm_and_fused_epilogue(monkeypatch):
+    x = wl.small_ints((2, 9, 7, 64), "f16", 31)
+    w = wl.small_ints((3, 3, 64, 64), "f16", 32)
+    ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, (1, 1), (1, 1))
+    prob = al.problem(al.OP_CONV2D, 2 * 9 * 7, 64, 576, al.F16, al.F32, conv_C=64)
+    scheds = _stream_scheds(prob)
+    assert scheds
+    for n, s in enumerate(scheds):
+        for blocks in (1, 2, 1000):
+            monkeypatch.setenv("ALCOP_STREAM_BLOCKS", str(blocks))
+            y = torch.full((2, 9, 7, 64), float("nan"), dtype=torch.float32)
+            errs = emu.call(al.alcop_conv2d_igemm, x, w, y, (1, 1), (1, 1), s, reads=[x, w], writes=[y],
+                            policy=emu.POLICIES[(n + blocks) % 4])
+            assert not errs, (repr(s), blocks, errs[:4])
+            assert _exact(y, ref), (repr(s), blocks)
+    # strided, dilated, ragged channel tile count per tap (C = 128, bk = 64: two k-tiles per tap)
+    x = wl.small_ints((1, 11, 10, 128), "f16", 33)
+    w = wl.small_ints((3, 2, 128, 72), "f16", 34)
+    ref = oracle.conv2d(wl.bits(x), wl.bits(w), oracle.F16, (2, 1), (2, 1), (2, 1))
+    monkeypatch.setenv("ALCOP_STREAM_BLOCKS", "2")
+    y = torch.full(tuple(ref.shape), float("nan"), dtype=torch.float32)
+    errs = emu.call(al.alcop_conv2d_igemm_dilated, x, w, y, (2, 1), (2, 1), (2, 1),
+                    sched=al.sched(128, 64, 64, 64, 32, 3, 2, 0, 1, 0, 2), reads=[x, w], writes=[y], policy=(1, 1))
+    assert not errs, errs[:4]
+    assert _exact(y, ref)
+    # plain GEMM with bias and ReLU, fp16 output, three blocks over six tiles
+    M, N, K = 3 * 128 - 8, 2 * 128 - 56, 3 * 64 + 16
+    A = wl.small_ints((M, K), "f16", 35)
+    B = wl.small_ints((K, N), "f16", 36)
+    bias = torch.arange(N, dtype=torch.float32) - 90
+    C = torch.full((M, N), float("nan"), dtype=torch.float16)
+    monkeypatch.setenv("ALCOP_STREAM_BLOCKS", "3")
+    errs = emu.call(al.alcop_gemm_fused, A, B, C, 0.5, bias, 1, al.sched(128, 128, 64, 64, 64, 3, 2, 0, 1, 0, 2),
+                    reads=[A, B, bias], writes=[C], policy=(1, 0))
+    assert not errs, errs[:4]
+    ref = oracle.epilogue(oracle.gemm(wl.bits(A), wl.bits(B), oracle.F16), 0.5, bias.double().numpy(), 1)
+    assert _exact(C, ref)
+
+
+def test_stream_kernel_planted_mistakes_are_noticed(monkeypatch):
+    monkeypatch.setenv("ALCOP_STREAM_BLOCKS", "2")
+    s = al.sched(128, 128, 64, 64, 64, 3, 2, 0, 1, 0, 2)
+    b, M, N, K = 2, 256, 128, 5 * 64
+    A = wl.small_ints((b, M, K), "f16", 1)
+    B = wl.small_ints((b, K, N), "f16", 2)
+    ref = oracle.bmm(wl.bits(A), wl.bits(B), oracle.F16)
+
+    def run(policy, mutation):
+        C = torch.full((b, M, N), float("nan"), dtype=torch.float32)
+        errs = emu.call(al.alcop_bmm, A, B, C, s, reads=[A, B], writes=[C], policy=policy, mutation=mutation)
+        return errs, _exact(C, ref)
+    for policy in emu.POLICIES:
+        errs, ok = run(policy, 0)
+        assert not errs and ok
+    assert not run((1, 0), 1)[1]          # a wait that lets too many loads stay in flight
+    for policy in emu.POLICIES:
+        assert not run(policy, 2)[1]      # no block barrier between producers and consumers
+    assert not run((1, 0), 3)[1]          # producers do not wait for their loads
+    errs, _ = run((1, 0), 4)              # consumers do not wait for their reads before the barrier
+    assert errs and "may still be fetching" in " ".join(errs)
+
+
+def test_stream_schedules_are_refused_where_they_do_not_apply():
+    A = wl.small_ints((128, 64), "f16", 1)
+    B = wl.small_ints((64, 128), "f16", 2)
+    C = torch.zeros(128, 128, dtype=torch.float32)
+    for bad in (al.sched(128, 128, 64, 64, 64, 3, 2, 1, 1, 0, 2),      # fusion across k-tiles
+                al.sched(128, 128, 64, 64, 64, 3, 1, 0, 1, 0, 2),      # one register stage
+                al.sched(128, 128, 64, 64, 64, 1, 2, 0, 1, 0, 2)):     # a ring of one slot
+        with pytest.raises(al.AlcopError) as e:
+            emu.call(al.alcop_gemm, A, B, C, bad, reads=[A, B], writes=[C])
         assert e.value.code == al.ERR_SCHED

@@ -62,7 +62,8 @@ def test_config_conv56_with_the_patch_variant_and_in_the_tuner():
     c2 = (2, 16, 16, 64, 64, 3, 3, 2, 2, 1, 1)
     a = al.alcop_tune(p2, x2, wd, y2, top_k=0, model=0, iters=2, conv=c2)
     b = al.alcop_tune(p2, x2, wd, y2, top_k=0, model=0, iters=2, conv=c2, variants=True)
-    assert a.space == b.space
+    assert a.space + sum(1 for s in al.alcop_sched_variants(p2) if s.variant == 2) == b.space
+    assert not any(s.variant == 1 for s, _, _ in b.log)
     with pytest.raises(al.AlcopError) as e:
         al.alcop_conv2d_igemm(x2, wd, y2, (2, 2), (1, 1), al.sched(128, 64, 64, 64, 32, 2, 2, 1, variant=1))
     assert e.value.code == al.ERR_SCHED
