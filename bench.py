@@ -155,7 +155,11 @@ def main():
         return best_ex / min(meas[s.key()] for _, _, s in ranked[:k])
 
     top10 = al.alcop_tune(prob, Ad, Bd, Cd, top_k=10, model=0, iters=30, variants=a.variants)
-    best = top10.best
+    # the tuner's 30-launch trials of the leading schedules lie within their noise: time its three
+    # fastest again, 500 launches each, and keep the winner
+    finalists = sorted(top10.log, key=lambda t: t[2])[:3]
+    retimed = [(al.alcop_time(prob, Ad, Bd, Cd, s, 20, 500), s) for s, _, _ in finalists]
+    best = min(retimed, key=lambda t: t[0])[1]
     # the 1-stage (unpipelined) schedule at the same tile
     base = al.sched(best.bm, best.bn, best.bk, best.wm, best.wn, 1, 1, 0, best.raster)
     us_base = al.alcop_time(prob, Ad, Bd, Cd, base, 10, 200)
@@ -234,7 +238,8 @@ def main():
         "us_1stage": round(us_base, 2), "us_best": round(us_best, 2),
         "tile_speedups_vs_1stage": tile_speedups,
         "ablation_speedup_vs_unpipelined": ablation,
-        "tuner": {"trials": top10.trials, "exhaustive_trials": ex.trials,
+        "tuner": {"trials": top10.trials, "finalists_retimed_us": [[repr(s), round(us, 2)] for us, s in retimed],
+                  "exhaustive_trials": ex.trials,
                   "best_in_top10_pct": round(100 * best_in_top(10, 0), 1),
                   "best_in_top10_pct_bottleneck_model": round(100 * best_in_top(10, 1), 1),
                   "best_in_top5_pct": round(100 * best_in_top(5, 0), 1),
@@ -254,7 +259,10 @@ def main():
 
     if not a.quick:
         out["vendor_library_context"] = vendor_context(wl, torch, dev)
-        out["other_shapes"] = other_shapes(al, wl, torch, dev, a.variants)
+        # the other configurations are tuned over the whole kernel table, including the kernels
+        # outside the default schedule space (persistent producer / consumer kernels, k-tile 128,
+        # LDS-resident convolution patch)
+        out["other_shapes"] = other_shapes(al, wl, torch, dev, True)
         out["cpu_baseline"] = cpu_baseline(wl, A, B, flops)
         if a.workload == "gemm2048":
             # the timed schedule's output against the oracle's (the test suite does this for many
@@ -461,8 +469,22 @@ def other_shapes(al, wl, torch, dev, variants=False):
             conv = (n, H, W, C, Ko, R, S, 1, 1, 1, 1)
         iters = 10 if name == "gemm8192" else 50
         r = al.alcop_tune(prob, Ad, Bd, Cd, top_k=10, model=0, iters=iters, conv=conv, variants=variants)
+        if variants:
+            # the model predicts a persistent producer / consumer kernel like the default kernel of
+            # its tile, so its top 10 rarely holds one: time those (a dozen per problem) as well
+            for s in al.alcop_sched_variants(prob):
+                if s.variant != 2 or al.alcop_sched_supported(prob, s) != al.OK:
+                    continue
+                try:
+                    us = al.alcop_time(prob, Ad, Bd, Cd, s, 3, iters, conv=conv)
+                except al.AlcopError:
+                    continue
+                r.trials += 1
+                if us < r.best_us:
+                    r.best, r.best_us = s, us
+        # the unpipelined schedule at the same tile (the tile-at-a-time kernel also for a persistent best)
         base = al.sched(r.best.bm, r.best.bn, r.best.bk, r.best.wm, r.best.wn, 1, 1, 0, r.best.raster,
-                        0, r.best.variant)
+                        0, 1 if r.best.variant == 1 else 0)
         us1 = al.alcop_time(prob, Ad, Bd, Cd, base, 3, iters, conv=conv)
         fl = 2.0 * M * N * K * b
         byts = 2.0 * (A.numel() + B.numel() + Cd.numel())

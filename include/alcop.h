@@ -342,6 +342,10 @@ int alcop_sched_variants(const alcop_problem* prob /* host */, alcop_sched* out 
  *   [5] T_smem_load  [6] T_smem_use  [7] N_threadblk_batch
  * model: 0 = the paper's pipeline-aware model; 1 = the bottleneck-only model it is compared
  * against in Sec. 6.4 (max of compute, LDS traffic and DRAM traffic at full rate).
+ * One deliberate deviation from Table 1: the multiplexing factor of the register-level pipeline
+ * is the number of wavefronts per SIMD, not the number of warps per threadblock (a wavefront is
+ * pinned to one of a compute unit's four matrix pipes).  A schedule of variant 2 is predicted
+ * like the default kernel of the same tile and stage count.
  */
 int alcop_model_predict(const alcop_problem* prob /* host */, const alcop_sched* sched /* host */,
                         int model, double* predicted_us /* host */, double* terms /* host */);
@@ -409,6 +413,8 @@ int alcop_sched_auto(const alcop_problem* prob /* host */, alcop_sched* out /* h
  * alcop_cache_save writes every cached entry and returns their number; alcop_cache_load merges
  * the file's entries into the cache (entries that name a schedule this library cannot run for
  * that problem are skipped) and returns the number accepted.  Negative return = alcop_status.
+ * If the environment variable ALCOP_LOG is set (to anything), every launch prints one line to
+ * stderr: the problem, the schedule it resolved to, the grid and the LDS size.
  * If the environment variable ALCOP_TUNE_CACHE names a file, it is merged in once, before the
  * first time a NULL / zero schedule is resolved (a missing or unreadable file is ignored).
  */

@@ -7,8 +7,11 @@ follows:
   * Util(N_warp_per_threadblk, N_threadblk_per_SM): share of one CU's matrix throughput that one
     threadblock obtains = min(1, N_warp*N_blk/4) / N_blk  (4 matrix pipes per CU).
   * T_reg_load (used in Table 1 but not defined there): LAT_LDS + Bytes_one_reg_loop * N_blk / BW_LDS.
-  * N_mplx of the inner (register-level) pipeline: wavefronts sharing one matrix pipe,
-    max(1, N_warp*N_blk/4) - the CDNA counterpart of "parallel warps in a threadblock".
+  * N_mplx of the inner (register-level) pipeline: a DELIBERATE DEVIATION from Table 1, which
+    gives N_warp_per_threadblk.  Here it is the number of wavefronts sharing one matrix pipe,
+    max(1, N_warp*N_blk/4): on this machine a wavefront is pinned to one of a CU's four SIMDs and
+    only the wavefronts of the same SIMD can fill each other's load latency; four waves on four
+    SIMDs do not multiplex at all.
   * N_threadblk_batch: ceil(blocks / (256 * N_blk_per_CU)); N_blk_per_CU limited by LDS
     (160 KB / ring bytes), by registers (512 per lane / estimated registers per wave) and by the
     number of blocks that exist.

@@ -430,6 +430,13 @@ int launch_call(const Call& c, const alcop_sched& s, const KernelEntry* e, hipSt
     p.ksplit_len = split->len;
     grid.z = (unsigned)split->nz;
   }
+  if (std::getenv("ALCOP_LOG"))
+    std::fprintf(stderr,
+                 "alcop: op %d M %d N %d K %d batch %d -> tile %dx%dx%d waves %dx%d S%d R%d F%d pf%d "
+                 "variant %d%s grid (%u,%u,%u) threads %d lds %d\n",
+                 (int)c.op, c.M, c.N, c.K, c.batch, s.bm, s.bn, s.bk, s.wm, s.wn, s.stages, s.reg_stages,
+                 s.fuse_inner, s.l2_prefetch, s.variant, split ? " split-K" : "", grid.x, grid.y, grid.z,
+                 e->threads, e->lds_bytes);
   hipError_t err = e->launch(p, grid, st);
   if (err != hipSuccess) return ALCOP_ERR_LAUNCH;
   if (split) {

@@ -76,7 +76,10 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   // --- register-level loop.  T_reg_load is not printed in the paper; reading: same form as the
   // LLC term, latency + bytes / bandwidth, the LDS port shared by the co-resident blocks.
   const double t_reg_load = dev.lat_lds + frag_bytes * blk_per_cu / dev.bw_lds_cu;
-  // Workers that can be multiplexed onto one matrix pipe = wavefronts per SIMD.
+  // Deliberate deviation from Table 1, which gives N_warp_per_threadblk as the multiplexing
+  // factor of the inner pipeline: a wavefront is pinned to one of the CU's four SIMDs, and only
+  // wavefronts of the same SIMD can fill each other's load latency, so the factor is the number
+  // of wavefronts per SIMD (four waves on four SIMDs do not multiplex at all).
   const double mplx_inner = std::max(1.0, n_warp * blk_per_cu / dev.simd_per_cu);
   double t_smem_use = pipeline_latency(t_reg_load, t_compute, n_reg_loop, R, mplx_inner);
   // The paper's T_smem_use is the fused steady state.  Without fusion the register pipeline is

@@ -93,7 +93,13 @@ __global__ void __launch_bounds__(C::NT) alcop_stream(const Params p)
 
   // tile id -> (batch, tm, tn); within a matrix, group_m row tiles form a column-major band so
   // that the tiles the blocks of the chip hold at one time share operand panels in L2
+  // Blocks are dealt to the 8 XCDs (each with an L2 of its own) round robin.  When the counts
+  // allow, the tile list is permuted so that XCD x owns the x-th eighth of the tile sequence:
+  // neighbouring tiles, which share operand panels (and, batched, whole matrices), then meet in
+  // one L2 instead of being fetched by all eight.
+  const bool by_xcd = p.raster == 1 && (total & 7) == 0 && (p.sgrid & 7) == 0;
   auto decode = [&](int t, int& batch, int& tm, int& tn) __attribute__((always_inline)) {
+    if (by_xcd) t = (t & 7) * (total >> 3) + (t >> 3);
     batch = t / per_mat;
     const int r = t - batch * per_mat;
     const int width = p.group_m * p.ntn;

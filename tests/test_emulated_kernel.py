@@ -599,6 +599,20 @@ def test_stream_kernels_batched_every_block_count(dt, transB, monkeypatch):
                 assert _exact(C, ref), (repr(s), blocks, K, policy)
 
 
+def test_stream_kernels_tile_list_dealt_by_xcd(monkeypatch):
+    # 4 matrices of 2 x 2 tiles = 16 tiles and 8 blocks: the permuted tile list (one eighth of
+    # the sequence per XCD) must still cover every tile exactly once; also 16 blocks and 24 tiles
+    s = al.sched(64, 64, 64, 32, 32, 3, 2, 0, 1, 0, 2)
+    for b, blocks in ((4, 8), (4, 16), (6, 8)):
+        monkeypatch.setenv("ALCOP_STREAM_BLOCKS", str(blocks))
+        A = wl.small_ints((b, 128, 136), "f16", 61)
+        B = wl.small_ints((b, 128, 136), "f16", 62)
+        C = torch.full((b, 128, 128), float("nan"), dtype=torch.float32)
+        errs = emu.call(al.alcop_bmm, A, B, C, s, transB=True, reads=[A, B], writes=[C], policy=(1, 1))
+        assert not errs, errs[:4]
+        assert _exact(C, oracle.bmm(wl.bits(A), wl.bits(B), oracle.F16, transB=True)), (b, blocks)
+
+
 def test_stream_kernels_convolution_gemm_and_fused_epilogue(monkeypatch):
     x = wl.small_ints((2, 9, 7, 64), "f16", 31)
     w = wl.small_ints((3, 3, 64, 64), "f16", 32)
