@@ -150,9 +150,8 @@ def main():
     best_ex = min(meas.values())
 
     def best_in_top(k, model):
-        ranked = sorted(((al.alcop_model_predict(prob, s, model)[0], i, s)
-                         for i, (s, _, _) in enumerate(ex.log)), key=lambda t: (t[0], t[1]))
-        return best_ex / min(meas[s.key()] for _, _, s in ranked[:k])
+        order = [s for s in al.alcop_sched_ranked(prob, model, a.variants, k) if s.key() in meas]
+        return best_ex / min(meas[s.key()] for s in order[:k])
 
     top10 = al.alcop_tune(prob, Ad, Bd, Cd, top_k=10, model=0, iters=30, variants=a.variants)
     # the tuner's 30-launch trials of the leading schedules lie within their noise: time its three
@@ -343,14 +342,15 @@ def tune_report(al, wl, torch, dev):
         best = min(us for _, us in meas)
         curves = {}
         ks = [k for k in (1, 5, 10, 20, 50) if k <= len(meas)]
+        by_key = {s.key(): us for s, us in meas}
         for model, label in ((0, "analytical"), (1, "bottleneck")):
-            order = sorted(range(len(meas)),
-                           key=lambda i: (al.alcop_model_predict(prob, meas[i][0], model)[0], i))
-            curves[label] = {str(k): round(100.0 * best / min(meas[i][1] for i in order[:k]), 1)
-                             for k in ks}
+            # the tuner's own order of trials for a budget of k (per-family cap included)
+            curves[label] = {}
+            for k in ks:
+                order = [s for s in al.alcop_sched_ranked(prob, model, False, k) if s.key() in by_key]
+                curves[label][str(k)] = round(100.0 * best / min(by_key[s.key()] for s in order[:k]), 1)
         # grid search: schedules in table order
         table = [s.key() for s in al.alcop_sched_space(prob)]
-        by_key = {s.key(): us for s, us in meas}
         grid = [by_key[k] for k in table if k in by_key]
         curves["grid"] = {str(k): round(100.0 * best / min(grid[:k]), 1) for k in ks}
         # measurement-corrected model: a real tuning run of 20 trials, best after each prefix
@@ -469,19 +469,6 @@ def other_shapes(al, wl, torch, dev, variants=False):
             conv = (n, H, W, C, Ko, R, S, 1, 1, 1, 1)
         iters = 10 if name == "gemm8192" else 50
         r = al.alcop_tune(prob, Ad, Bd, Cd, top_k=10, model=0, iters=iters, conv=conv, variants=variants)
-        if variants:
-            # the model predicts a persistent producer / consumer kernel like the default kernel of
-            # its tile, so its top 10 rarely holds one: time those (a dozen per problem) as well
-            for s in al.alcop_sched_variants(prob):
-                if s.variant != 2 or al.alcop_sched_supported(prob, s) != al.OK:
-                    continue
-                try:
-                    us = al.alcop_time(prob, Ad, Bd, Cd, s, 3, iters, conv=conv)
-                except al.AlcopError:
-                    continue
-                r.trials += 1
-                if us < r.best_us:
-                    r.best, r.best_us = s, us
         # the unpipelined schedule at the same tile (the tile-at-a-time kernel also for a persistent best)
         base = al.sched(r.best.bm, r.best.bn, r.best.bk, r.best.wm, r.best.wn, 1, 1, 0, r.best.raster,
                         0, 1 if r.best.variant == 1 else 0)

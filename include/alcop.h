@@ -90,7 +90,7 @@ typedef struct {
                       /* while four consumer waves multiply and store, so the loads of the    */
                       /* next tile overlap the epilogue of this one (the paper's load / use   */
                       /* overlap, Sec. 1, carried across tiles; for short reduction axes,     */
-                      /* Sec. 6.1).  Needs stages >= 2, reg_stages = 2, fuse_inner = 0,       */
+                      /* Sec. 6.1).  Needs stages >= 2, reg_stages = 2 (fuse_inner 0 or 1),   */
                       /* l2_prefetch = 0, four waves' worth of wave tiles per block tile, and */
                       /* for a convolution a k-tile that divides the channel count.  Results  */
                       /* are bit-identical to the default kernels of the same tile.  The      */
@@ -354,8 +354,11 @@ int alcop_model_predict(const alcop_problem* prob /* host */, const alcop_sched*
  * Model-ranked tuning (paper Sec. 5.3 "Analytical-only": rank all schedules by predicted
  * latency and measure the best-ranked ones).  Runs on the caller's buffers (contents of C
  * are overwritten), synchronises the stream, times each trial with HIP events.
- *   top_k > 0: time the top_k feasible schedules by predicted latency; top_k == 0: time all
- *   feasible schedules (exhaustive / grid search, the 100 % reference of Sec. 6.4).
+ *   top_k > 0: time the top_k feasible schedules by predicted latency, at most max(2, top_k / 4)
+ *   of them from one (tile, wave tile, variant) family (the pipelining variants of one tile are
+ *   predicted within a few percent of each other and would otherwise fill the budget);
+ *   top_k == 0: time all feasible schedules (exhaustive / grid search, the 100 % reference of
+ *   Sec. 6.4).
  *   model: 0 / 1 as in alcop_model_predict (fixed ranking by that model);
  *          2 = measurement-corrected model (Sec. 5.3 "Analytical + ML"): a regression whose prior
  *              is model 0 and which is refitted after every timed trial; the next trial is the
@@ -397,6 +400,14 @@ int alcop_corrector_features(const alcop_problem* prob /* host */, const alcop_s
                              double* x /* host, ALCOP_CORRECTOR_DIM */);
 int alcop_corrector_fit(const double* x /* host */, const double* measured_us /* host */, int n,
                         double* weights /* host, ALCOP_CORRECTOR_DIM */);
+
+/*
+ * The order in which alcop_tune(top_k, model 0 or 1) tries the schedules of a problem (those that
+ * only the call's geometry could still prune included): by predicted latency with the per-family
+ * cap described there.  Host only.  Writes up to cap schedules, returns their total number.
+ */
+int alcop_sched_ranked(const alcop_problem* prob /* host */, int model, int variants, int top_k,
+                       alcop_sched* out /* host */, int cap);
 
 /*
  * The schedule a NULL / zero schedule argument resolves to for this problem: the entry of the

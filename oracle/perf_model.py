@@ -23,6 +23,10 @@ follows:
     the single LDS port needs to move the fragment reads of every wave (K-contiguous operand at
     256 B/clk, N-contiguous operand through the transposing read at ~170 B/clk) plus the
     direct-to-LDS writes of one k-tile.
+  * Fill path (another addition): one compute unit's L2 -> LDS path delivers bw_llc / num_cu;
+    T_smem_use is at least the time that path needs for the k-tiles of the CU's blocks.  The
+    pipeline criterion of Table 1 treats a load as a latency to hide and would otherwise call a
+    bandwidth-bound loop compute-bound as soon as there are enough stages.
   * Clock: rates are taken at the ~1.8 GHz a GEMM sustains under the power cap.
 
 Pins (tests/test_model.py): the pipeline latency model against hand-computed values and the
@@ -68,13 +72,19 @@ def pipeline_latency_caption_form(t_load, t_use, n_loop, n_pipe, n_mplx):
 
 
 def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Device = Device(),
-            transB: bool = False, transA: bool = False, patch_taps: int = 0):
+            transB: bool = False, transA: bool = False, patch_taps: int = 0, persistent: bool = False):
     """Returns a dict of the Table 1 quantities (microseconds).
 
     patch_taps > 0 (not in the paper): a convolution whose input patch stays in LDS; the A rows
     of a tile are fetched once per block instead of once per filter tap, so one k-tile accounts
     for bm / patch_taps of them, and the patch (reading: 1.5 tiles) occupies LDS beside the
-    ring of B tiles."""
+    ring of B tiles.
+
+    persistent (not in the paper): blocks that stay on their compute unit and walk a list of
+    tiles; a block's tiles form one load-and-use loop, the epilogue's stores are consumer work
+    inside that loop (bandwidth term only, they are not waited for), T_init is paid once and
+    one write latency ends the kernel.  A staging band per consumer wave follows the ring in
+    LDS, and at most two blocks share a compute unit."""
     ntm, ntn = math.ceil(M / bm), math.ceil(N / bn)
     tiles = ntm * ntn
     n_blocks = tiles * batch
@@ -84,6 +94,8 @@ def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Devi
     a_rows = bm / patch_taps if patch_taps > 0 else bm
     bytes_one_smem_loop = (a_rows + bn) * bk * 2
     lds_use = (S * bn * bk * 2 + 1.5 * bm * bk * 2) if patch_taps > 0 else S * bytes_one_smem_loop
+    if persistent:
+        lds_use += n_warp * 32 * (wn * 4 + 16)
     bytes_one_reg_loop = n_warp * (wm + wn) * 16 * 2
     flops_one_reg_loop = 2 * bm * bn * 16
 
@@ -93,6 +105,8 @@ def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Devi
     n_blk_per_cu = min(math.floor(dev.lds_bytes / lds_use),
                        math.floor(waves_per_simd * dev.simd_per_cu / n_warp))
     n_blk_per_cu = max(1, n_blk_per_cu)
+    if persistent:
+        n_blk_per_cu = max(1, min(2, math.floor(dev.lds_bytes / lds_use)))
     n_blk_per_cu = min(n_blk_per_cu, math.ceil(n_blocks / dev.num_cu))
     n_batch = math.ceil(n_blocks / (dev.num_cu * n_blk_per_cu))
     n_blk_per_batch = min(n_blocks, dev.num_cu * n_blk_per_cu)
@@ -113,6 +127,9 @@ def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Devi
     t_port = (a_read / (dev.bw_lds_tr_cu if transA else dev.bw_lds_cu) + b_read / (dev.bw_lds_cu if transB else dev.bw_lds_tr_cu)
               + bytes_one_smem_loop / dev.bw_lds_cu) * n_blk_per_cu
     t_smem_use = max(t_smem_use, t_port)
+    # fill path of one compute unit: its blocks cannot consume k-tiles faster than L2 -> LDS delivers
+    t_fill = bytes_one_smem_loop * n_blk_per_cu / (dev.bw_llc / dev.num_cu)
+    t_smem_use = max(t_smem_use, t_fill)
 
     # Memory Latency Model
     t_llc_load = dev.lat_llc + bytes_one_smem_loop * n_blk_per_batch / dev.bw_llc
@@ -125,6 +142,16 @@ def predict(M, N, K, batch, out_bytes, bm, bn, bk, wm, wn, S, R, fuse, dev: Devi
     t_smem_load = max(t_llc_load, t_dram_load)
 
     t_init = t_smem_load + t_reg_load
+    if persistent:
+        tiles_per_block = math.ceil(n_blocks / (dev.num_cu * n_blk_per_cu))
+        t_store = bm * bn * out_bytes * n_blk_per_batch / dev.bw_dram_write
+        t_use = t_smem_use + t_store / n_smem_loop
+        t_main_loop = pipeline_latency(t_smem_load, t_use, tiles_per_block * n_smem_loop, S, n_blk_per_cu)
+        t_kernel = t_init + t_main_loop + dev.lat_dram_write
+        return dict(t_kernel=t_kernel, t_threadblk=t_kernel, t_init=t_init, t_main_loop=t_main_loop,
+                    t_epilogue=dev.lat_dram_write, t_smem_load=t_smem_load, t_smem_use=t_use,
+                    n_threadblk_batch=1, t_compute=t_compute, t_reg_load=t_reg_load,
+                    n_blk_per_cu=n_blk_per_cu, util=util)
     t_main_loop = pipeline_latency(t_smem_load, t_smem_use, n_smem_loop, S, n_blk_per_cu)
     # Epilogue Model
     t_epilogue = dev.lat_dram_write + bm * bn * out_bytes * n_blk_per_batch / dev.bw_dram_write

@@ -25,7 +25,7 @@ EXPORTS = [
     "alcop_gemm", "alcop_bmm", "alcop_gemm_fused", "alcop_bmm_fused", "alcop_conv2d_igemm", "alcop_sched_supported", "alcop_sched_space",
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
-    "alcop_corrector_features", "alcop_corrector_fit", "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_gemm_splitk_static", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_conv2d_igemm_dilated", "alcop_sched_variants",
+    "alcop_corrector_features", "alcop_corrector_fit", "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_gemm_splitk_static", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_conv2d_igemm_dilated", "alcop_sched_variants", "alcop_sched_ranked",
 ]
 
 
@@ -101,6 +101,8 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
     L.alcop_tune.restype = i
     L.alcop_tune.argtypes = [pp, vp, vp, vp, l, l, l, l, l, l, ip, i, i, i, i, sp, dp, ip, ip,
                              sp, dp, dp, i, vp]
+    L.alcop_sched_ranked.restype = i
+    L.alcop_sched_ranked.argtypes = [pp, i, i, i, sp, i]
     L.alcop_sched_variants.restype = i
     L.alcop_sched_variants.argtypes = [pp, sp, i]
     L.alcop_time.restype = i
@@ -456,6 +458,16 @@ def alcop_sched_variants(prob: Problem):
         raise AlcopError(n, "alcop_sched_variants")
     arr = (Sched * max(n, 1))()
     lib().alcop_sched_variants(ctypes.byref(prob), arr, n)
+    return [Sched(*arr[i].key()) for i in range(n)]
+
+
+def alcop_sched_ranked(prob: Problem, model: int = 0, variants: bool = False, top_k: int = 10):
+    """Schedules in the order alcop_tune(top_k, model) would try them."""
+    n = lib().alcop_sched_ranked(ctypes.byref(prob), model, int(variants), top_k, None, 0)
+    if n < 0:
+        raise AlcopError(n, "alcop_sched_ranked")
+    arr = (Sched * max(n, 1))()
+    lib().alcop_sched_ranked(ctypes.byref(prob), model, int(variants), top_k, arr, n)
     return [Sched(*arr[i].key()) for i in range(n)]
 
 

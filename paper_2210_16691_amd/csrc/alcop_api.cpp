@@ -137,9 +137,10 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
   if (s.variant != 0 && s.variant != 2 &&
       !(s.variant == 1 && p.op == ALCOP_OP_CONV2D && !p.transB && p.conv_C == s.bk && sk == 0))
     return ALCOP_ERR_SCHED;
-  // variant 2, the persistent producer / consumer kernels: two register stages inside a k-tile,
-  // no fusion across k-tiles, no L2 touches, no split-K; convolutions with one tap per k-tile
-  if (s.variant == 2 && (s.reg_stages != 2 || s.fuse_inner || s.l2_prefetch != 0 || sk != 0 ||
+  // variant 2, the persistent producer / consumer kernels: two register stages (fused across
+  // k-tiles and tiles, or restarted per k-tile), no L2 touches, no split-K; convolutions with one
+  // tap per k-tile
+  if (s.variant == 2 && (s.reg_stages != 2 || s.l2_prefetch != 0 || sk != 0 ||
                          s.stages < 2 || (p.op == ALCOP_OP_CONV2D && p.conv_C % s.bk != 0)))
     return ALCOP_ERR_SCHED;
   const KernelEntry* e = find_entry(p, s, sk);
@@ -163,7 +164,7 @@ int default_l2_prefetch(int bk) { return 256 / bk; }
 // tuner for them, never picked by the model on its own.  These are the patch convolution (its
 // feasibility depends on the call, not only on the problem description) and the kernels with a
 // k-tile of 128 (two stages of a 128 x 128 tile fill the LDS: a trade the tuner should measure).
-bool opt_in(const KernelEntry& e) { return e.am == 3 || e.bk == 128 || e.st == 1; }
+bool opt_in(const KernelEntry& e) { return e.am == 3 || e.bk == 128; }
 
 // variants: 0 = the default kernels; 1 = also the opt-in kernels; 2 = only those.
 std::vector<alcop_sched> space_of(const alcop_problem& p, int sk = 0, int variants = 0)
@@ -617,6 +618,31 @@ Call gemm_call(alcop_op op, const void* A, const void* B, void* C, int batch, in
   c.out = out;
   c.alpha = 1.0f;
   return c;
+}
+
+// Order of the trials of a fixed-ranking tuning run: by predicted latency, but among the first
+// top_k at most max(2, top_k / 4) schedules of one (tile, wave tile, variant) family.  The
+// pipelining variants of one tile are predicted within a few percent of each other; without the
+// cap the near-ties of one tile fill the whole budget and a mispredicted tile costs the run.
+template <class Cand>
+void spread_over_tiles(std::vector<Cand>& ranked, int top_k)
+{
+  if (top_k <= 0 || (int)ranked.size() <= top_k) return;
+  const int cap = std::max(2, top_k / 4);
+  std::map<std::tuple<int, int, int, int, int, int>, int> taken;
+  std::vector<Cand> head, tail;
+  for (const Cand& cd : ranked) {
+    const alcop_sched& s = cd.s;
+    int& n = taken[std::make_tuple(s.bm, s.bn, s.bk, s.wm, s.wn, s.variant)];
+    if ((int)head.size() < top_k && n < cap) {
+      n++;
+      head.push_back(cd);
+    } else {
+      tail.push_back(cd);
+    }
+  }
+  head.insert(head.end(), tail.begin(), tail.end());
+  ranked.swap(head);
 }
 
 int conv_call(Call* c, const void* x, const void* w, void* y, int N, int H, int W, int Cc, int K,
@@ -1083,6 +1109,7 @@ int alcop_tune(const alcop_problem* prob, const void* A, const void* B, void* C,
   if (cands.empty()) return ALCOP_ERR_SCHED;
   std::stable_sort(cands.begin(), cands.end(),
                    [](const Cand& a, const Cand& b) { return a.pred < b.pred; });
+  if (model == 0 || model == 1) spread_over_tiles(cands, top_k);
   const int n = top_k == 0 ? (int)cands.size() : std::min(top_k, (int)cands.size());
   Corrector corr;
   bool have = false;
@@ -1128,6 +1155,28 @@ int alcop_tune(const alcop_problem* prob, const void* A, const void* B, void* C,
   std::lock_guard<std::mutex> lk(g_cache_mu);
   g_cache[key_of(p)] = *best;
   return ALCOP_OK;
+}
+
+int alcop_sched_ranked(const alcop_problem* prob, int model, int variants, int top_k, alcop_sched* out,
+                       int cap)
+{
+  if (!prob) return ALCOP_ERR_NULL;
+  const int rc = check_problem(*prob);
+  if (rc) return rc;
+  if (model < 0 || model > 1 || top_k < 0) return ALCOP_ERR_SHAPE;
+  struct Cand {
+    alcop_sched s;
+    double pred;
+  };
+  std::vector<Cand> cands;
+  const Device dev;
+  for (const alcop_sched& s : space_of(*prob, 0, variants ? 1 : 0))
+    if (check_sched(*prob, s, nullptr) == ALCOP_OK) cands.push_back(Cand{s, predict(*prob, s, model, dev, nullptr)});
+  std::stable_sort(cands.begin(), cands.end(), [](const Cand& a, const Cand& b) { return a.pred < b.pred; });
+  spread_over_tiles(cands, top_k);
+  if (out)
+    for (int i = 0; i < (int)cands.size() && i < cap; i++) out[i] = cands[i].s;
+  return (int)cands.size();
 }
 
 int alcop_sched_variants(const alcop_problem* prob, alcop_sched* out, int cap)

@@ -32,12 +32,12 @@ constexpr bool stream_feasible(int bm, int bn, int bk, int wm, int wn, int s)
   return s >= 2 && s <= 4;
 }
 
-template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int BL, int AM, int AL = 0>
+template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int BL, int AM, int AL = 0, int FU = 1>
 void add_stream(std::vector<KernelEntry>& t)
 {
   if constexpr (stream_feasible(BM, BN, BK, WM, WN, S)) {
-    using C = SCfg<DT, BM, BN, BK, WM, WN, S, BL, AM, AL>;
-    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, 2, 0, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT,
+    using C = SCfg<DT, BM, BN, BK, WM, WN, S, BL, AM, AL, FU>;
+    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, 2, FU, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT,
                             C::L, 0, &launch_stream<C>});
   }
 }

@@ -38,7 +38,11 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   const double taps = patch ? std::max(1.0, (double)prob.K / prob.conv_C) : 1.0;
   const double a_rows = bm / taps;                           // A rows fetched per k-tile
   const double stage_bytes = (a_rows + bn) * bk * 2.0;      // Bytes_one_smem_loop
-  const double lds_use = patch ? S * bn * bk * 2.0 + 1.5 * bm * bk * 2.0 : S * stage_bytes;
+  // Schedule variant 2: persistent blocks of four consumer and four producer waves; the ring is
+  // followed by a staging band per consumer wave, and at most two blocks share a compute unit.
+  const bool persistent = s.variant == 2;
+  const double lds_use = patch ? S * bn * bk * 2.0 + 1.5 * bm * bk * 2.0
+                               : S * stage_bytes + (persistent ? n_warp * 32.0 * (wn * 4.0 + 16.0) : 0.0);
   const double frag_bytes = n_warp * (wm + wn) * 16.0 * 2.0; // Bytes_one_reg_loop (LDS reads)
   const double flops_reg_loop = 2.0 * bm * bn * 16.0;        // FLOPs_one_reg_loop
 
@@ -62,6 +66,7 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   double blk_per_cu = std::min(std::floor(dev.lds_bytes / lds_use),
                                std::floor(waves_per_simd * dev.simd_per_cu / n_warp));
   blk_per_cu = std::max(1.0, blk_per_cu);
+  if (persistent) blk_per_cu = std::max(1.0, std::min(2.0, std::floor(dev.lds_bytes / lds_use)));
   blk_per_cu = std::min(blk_per_cu, ceil_div(n_blocks, dev.num_cu));   // no more than exist
   const double slots = dev.num_cu * blk_per_cu;
   const double n_batch = ceil_div(n_blocks, slots);           // N_threadblk_batch
@@ -96,6 +101,11 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
                            b_read / (prob.transB ? dev.bw_lds_cu : dev.bw_lds_tr_cu) +
                            stage_bytes / dev.bw_lds_cu) * blk_per_cu;
     t_smem_use = std::max(t_smem_use, t_port);
+    // Fill path (not in Table 1 either): the pipeline criterion treats a load as a latency to
+    // hide, but one compute unit's L2 -> LDS path delivers only bw_llc / num_cu bytes per
+    // microsecond; the blocks of a CU cannot consume k-tiles faster than it delivers them.
+    const double t_fill = stage_bytes * blk_per_cu / (dev.bw_llc / dev.num_cu);
+    t_smem_use = std::max(t_smem_use, t_fill);
   }
 
   // --- memory latency
@@ -111,6 +121,21 @@ double predict(const alcop_problem& prob, const alcop_sched& s, int model, const
   const double t_smem_load = std::max(t_llc, t_dram);
 
   const double t_init = t_smem_load + t_reg_load;
+  if (persistent) {
+    // Schedule variant 2 (not in the paper; its model applied to the kernel's loop structure):
+    // a block's tiles form ONE load-and-use loop of tiles_per_block * N_smem_loop iterations; the
+    // epilogue of a tile is consumer work inside that loop (its stores are not waited for, so only
+    // their bandwidth term counts, spread over the tile's iterations); T_init is paid once and one
+    // write latency ends the kernel.
+    const double tiles_per_block = ceil_div(n_blocks, slots);
+    const double t_store = bm * bn * out_bytes * n_in_batch / dev.bw_dram_write;
+    const double t_use = t_smem_use + t_store / n_smem_loop;
+    const double t_main = pipeline_latency(t_smem_load, t_use, tiles_per_block * n_smem_loop, S, blk_per_cu);
+    const double t_kernel = t_init + t_main + dev.lat_dram_write;
+    if (terms)
+      *terms = ModelTerms{t_kernel, t_kernel, t_init, t_main, dev.lat_dram_write, t_smem_load, t_use, 1.0};
+    return t_kernel;
+  }
   const double t_main = pipeline_latency(t_smem_load, t_smem_use, n_smem_loop, S, blk_per_cu);
   const double t_epi = dev.lat_dram_write + bm * bn * out_bytes * n_in_batch / dev.bw_dram_write;
   const double t_blk = t_init + t_main + t_epi;

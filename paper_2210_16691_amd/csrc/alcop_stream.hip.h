@@ -24,10 +24,14 @@
 //              s_barrier B_i
 //              issue k-tile i+S-1 into slot (i-1) mod S   (producer_acquire: the consumers
 //              passed B_i, so they have finished reading k-tile i-1)
-//   consumer:  s_waitcnt lgkmcnt(0)      (my reads of k-tile i-1 are done: consumer_release)
+//   consumer:  in the last register step of k-tile i-1, after its first matrix instructions
+//              (every fragment of k-tile i-1 is in registers by then):
+//              s_waitcnt lgkmcnt(0)      (my reads of k-tile i-1 are done: consumer_release)
 //              s_barrier B_i             (consumer_wait, second half)
-//              fragments and matrix instructions of k-tile i; after the last k-tile of a tile
-//              the epilogue, through an LDS staging area of the wave's own outside the ring.
+//              then the rest of that step's matrix instructions, which cover the reads of the
+//              first fragment of k-tile i: the register-level pipeline is fused across k-tiles
+//              (Fig. 3(d)) and across output tiles.  After the last k-tile of a tile comes the
+//              epilogue, through an LDS staging area of the wave's own outside the ring.
 // Past the end of the stream the producers issue out-of-range loads (they fetch nothing), so the
 // number of loads in flight at every wait is the same constant.
 //
@@ -40,10 +44,13 @@ namespace alcop {
 
 // DT, tile, wave tile, stages, layouts as in KCfg; AM: 0 = A is a matrix, 1 = convolution gather
 // with one filter tap per k-tile (bk divides the channel count).
-template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int S_, int BL_, int AM_, int AL_ = 0>
+// FU: 1 = the consumers' register pipeline is fused across k-tiles and tiles (the barrier sits inside
+// the last register step); 0 = it restarts after the barrier that opens each k-tile.
+template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int S_, int BL_, int AM_, int AL_ = 0,
+          int FU_ = 1>
 struct SCfg {
   static constexpr int DT = DT_, BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, S = S_;
-  static constexpr int BL = BL_, AM = AM_, AL = AL_;
+  static constexpr int BL = BL_, AM = AM_, AL = AL_, FU = FU_;
   static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
   static constexpr int NCW = WAVES_M * WAVES_N;      // consumer waves
   static constexpr int NPW = NCW;                    // producer waves
@@ -225,6 +232,32 @@ __global__ void __launch_bounds__(C::NT) alcop_stream(const Params p)
     const uint32_t ebase = lds0 + C::RING_BYTES + (uint32_t)wave * C::EPI_WAVE_BYTES;
     const bool fused = p.alpha != 1.0f || p.bias != nullptr || p.act != 0;
     int slot = 0;
+    int i_stream = 0;                      // k-tile of the stream being consumed
+    u32x4 fa[2][TM], fb[2][TN];
+    auto open_slot = [&]() __attribute__((always_inline)) {
+      const uint32_t sbase = lds0 + (uint32_t)slot * STAGE_BYTES;
+      slot = (slot + 1 == S) ? 0 : slot + 1;
+#pragma unroll
+      for (int i = 0; i < OA::NRD; i++) curA[i] = sbase + rdA[i];
+#pragma unroll
+      for (int i = 0; i < OB::NRD; i++) curB[i] = sbase + rdB[i];
+    };
+    // The register-level pipeline runs across k-tiles and across output tiles (Fig. 3(d)): the
+    // barrier B_{i+1} sits after the first matrix instructions of the LAST step of k-tile i, when
+    // every fragment of k-tile i is already in registers, and the rest of that step's matrix
+    // instructions cover the reads of the first fragment of k-tile i+1.
+    if constexpr (C::FU) {
+      HW::wait_lds();
+      HW::block_barrier();                 // B_0: k-tile 0 has landed for every producer wave
+      open_slot();
+#pragma unroll
+      for (int r = 0; r < NRI; r++) read_one(0, r, fa[0], fb[0]);
+      HW::sched_fence();
+    }
+    static_assert(NKI % 2 == 0, "fragment parity must repeat per k-tile");
+    constexpr int FIRST = NMM >= 8 ? NMM / 4 : 1;
+    constexpr int GAPS = NMM - FIRST > 0 ? NMM - FIRST : 1;
+    constexpr int RPGL = (NRI + GAPS - 1) / GAPS > 2 ? (NRI + GAPS - 1) / GAPS : 2;   // reads per gap, last step
     for (int j = 0; j < my_tiles; j++) {
       int batch, tm, tn;
       decode(first + j * p.sgrid, batch, tm, tn);
@@ -235,21 +268,17 @@ __global__ void __launch_bounds__(C::NT) alcop_stream(const Params p)
         for (int b = 0; b < TM; b++)
 #pragma unroll
           for (int v = 0; v < 16; v++) acc[a][b][v] = 0.f;
-      u32x4 fa[2][TM], fb[2][TN];
       for (int ko = 0; ko < nko; ko++) {
-        HW::wait_lds();                    // consumer_release: my reads of the previous k-tile are done
-        HW::block_barrier();               // B_i: k-tile i has landed for every producer wave
-        const uint32_t sbase = lds0 + (uint32_t)slot * STAGE_BYTES;
-        slot = (slot + 1 == S) ? 0 : slot + 1;
+        const bool more = C::FU && i_stream + 1 < T;   // another k-tile follows in the stream (uniform)
+        i_stream++;
+        if constexpr (!C::FU) {
+          HW::wait_lds();                  // consumer_release: my reads of the previous k-tile are done
+          HW::block_barrier();             // B_i: k-tile i has landed for every producer wave
+          open_slot();
 #pragma unroll
-        for (int i = 0; i < OA::NRD; i++) curA[i] = sbase + rdA[i];
-#pragma unroll
-        for (int i = 0; i < OB::NRD; i++) curB[i] = sbase + rdB[i];
-#pragma unroll
-        for (int r = 0; r < NRI; r++) read_one(0, r, fa[0], fb[0]);
-        HW::sched_fence();
-        // register-level pipeline inside the k-tile: the reads of fragment ki+1 are spread over
-        // the matrix instructions of fragment ki
+          for (int r = 0; r < NRI; r++) read_one(0, r, fa[0], fb[0]);
+          HW::sched_fence();
+        }
 #pragma unroll
         for (int ki = 0; ki < NKI; ki++) {
 #pragma unroll
@@ -257,9 +286,22 @@ __global__ void __launch_bounds__(C::NT) alcop_stream(const Params p)
             const int a = m / TM, b = m % TM;
             acc[a][b] = HW::template mma<C::DT>(fb[ki & 1][a], fa[ki & 1][b], acc[a][b]);
             if (ki + 1 < NKI) {
+              // reads of fragment ki+1, spread over the matrix instructions of fragment ki
 #pragma unroll
               for (int r = m * RPG; r < (m + 1) * RPG && r < NRI; r++)
                 read_one(ki + 1, r, fa[(ki + 1) & 1], fb[(ki + 1) & 1]);
+            } else if (more) {
+              if (m + 1 == FIRST || (FIRST >= NMM && m == NMM - 1)) {
+                HW::wait_lds();            // consumer_release: my reads of k-tile i are done
+                HW::block_barrier();       // B_{i+1}: k-tile i+1 has landed, slot i may be refilled
+                open_slot();
+              }
+              if (m >= FIRST || m == NMM - 1) {
+                const int g = m >= FIRST ? m - FIRST : 0;
+                const int r1 = (m == NMM - 1) ? NRI : (g + 1) * RPGL;   // the last gap takes what is left
+#pragma unroll
+                for (int r = g * RPGL; r < r1 && r < NRI; r++) read_one(0, r, fa[0], fb[0]);
+              }
             }
             HW::sched_fence();
           }

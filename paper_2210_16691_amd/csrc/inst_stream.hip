@@ -3,10 +3,14 @@
 // convolution gather with one filter tap per k-tile.
 #include "alcop_instantiate_stream.hip.h"
 namespace alcop {
+// every ring depth, the consumers' register pipeline fused across k-tiles and not
 #define ALCOP_STREAM_STAGES(T, DT, BM, BN, BK, WM, WN, BL, AM)   \
-  add_stream<DT, BM, BN, BK, WM, WN, 2, BL, AM>(T);              \
-  add_stream<DT, BM, BN, BK, WM, WN, 3, BL, AM>(T);              \
-  add_stream<DT, BM, BN, BK, WM, WN, 4, BL, AM>(T);
+  add_stream<DT, BM, BN, BK, WM, WN, 2, BL, AM, 0, 1>(T);        \
+  add_stream<DT, BM, BN, BK, WM, WN, 3, BL, AM, 0, 1>(T);        \
+  add_stream<DT, BM, BN, BK, WM, WN, 4, BL, AM, 0, 1>(T);        \
+  add_stream<DT, BM, BN, BK, WM, WN, 2, BL, AM, 0, 0>(T);        \
+  add_stream<DT, BM, BN, BK, WM, WN, 3, BL, AM, 0, 0>(T);        \
+  add_stream<DT, BM, BN, BK, WM, WN, 4, BL, AM, 0, 0>(T);
 void register_stream(std::vector<KernelEntry>& t)
 {
   // fp16, B stored K x N

@@ -34,11 +34,11 @@ hipError_t launch_emulated_stream(const Params& p, dim3 grid, hipStream_t)
   return hipSuccess;
 }
 
-template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int BL, int AM, int AL = 0>
+template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int BL, int AM, int AL = 0, int FU = 1>
 void add_stream(std::vector<KernelEntry>& t)
 {
-  using C = SCfg<DT, BM, BN, BK, WM, WN, S, BL, AM, AL>;
-  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, 2, 0, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT, C::L, 0,
+  using C = SCfg<DT, BM, BN, BK, WM, WN, S, BL, AM, AL, FU>;
+  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, 2, FU, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT, C::L, 0,
                           &launch_emulated_stream<C>});
 }
 
@@ -148,6 +148,10 @@ void emu_part_6(std::vector<KernelEntry>& t)
   add_stream<0, 128, 64, 64, 64, 32, 3, 0, 1>(t);      // convolution gather
   add_stream<0, 64, 64, 32, 32, 32, 4, 0, 1>(t);
   add_stream<0, 256, 64, 64, 64, 64, 2, 0, 1>(t);
+  // ... with the register pipeline restarted in every k-tile
+  add_stream<0, 128, 128, 64, 64, 64, 3, 0, 0, 0, 0>(t);
+  add_stream<0, 64, 64, 64, 32, 32, 3, 1, 0, 0, 0>(t);
+  add_stream<0, 128, 64, 64, 64, 32, 3, 0, 1, 0, 0>(t);
 }
 #elif EMU_PART == 3
 void emu_part_3(std::vector<KernelEntry>& t)

@@ -21,7 +21,8 @@ def _groups(prob, keep=lambda s: True, variants=False):
     by_tile = {}
     for s in found:
         if s.l2_prefetch == 0 and al.alcop_sched_supported(prob, s) == al.OK and keep(s):
-            by_tile.setdefault((s.bm, s.bn, s.bk, s.wm, s.wn, s.variant), []).append(s)
+            # the persistent kernels (variant 2) accumulate in the same order as the default ones
+            by_tile.setdefault((s.bm, s.bn, s.bk, s.wm, s.wn, 1 if s.variant == 1 else 0), []).append(s)
     return by_tile
 
 

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _stream(prob):
-    return [s for s in al.alcop_sched_variants(prob) if s.variant == 2 and al.alcop_sched_supported(prob, s) == al.OK]
+    return [s for s in al.alcop_sched_space(prob) if s.variant == 2 and al.alcop_sched_supported(prob, s) == al.OK]
 
 
 @pytest.mark.parametrize("dt,transB", [("f16", False), ("f16", True), ("bf16", False)])
@@ -73,7 +73,7 @@ def test_same_bits_as_the_tile_at_a_time_kernel_on_random_data():
     for s in _stream(prob):
         C = torch.full((b, M, N), float("nan"), dtype=torch.float16, device=DEV)
         al.alcop_bmm(Ad, Bd, C, s)
-        plain = al.sched(s.bm, s.bn, s.bk, s.wm, s.wn, 2, 2, 0)
+        plain = al.sched(s.bm, s.bn, s.bk, s.wm, s.wn, 2, 2, 1)
         if al.alcop_sched_supported(prob, plain) != al.OK:
             plain = al.sched(s.bm, s.bn, s.bk, s.wm, s.wn, 1, 1, 0)
         D = torch.full((b, M, N), float("nan"), dtype=torch.float16, device=DEV)

@@ -309,3 +309,25 @@ def test_diagnostic_library_exports_what_its_header_declares():
     cfgs = diag.configs()
     assert len(cfgs) >= 3 and all(c.split()[0] in ("f16", "bf16") for c in cfgs)
     assert L.alcop_diag_config_name(len(cfgs)) is None
+
+
+def test_ranked_order_is_the_model_order_with_a_cap_per_tile_family():
+    prob = al.problem(al.OP_BMM, 512, 64, 512, al.F16, al.F16, batch=96)
+    space = [s for s in al.alcop_sched_space(prob) if al.alcop_sched_supported(prob, s) == al.OK]
+    ranked = al.alcop_sched_ranked(prob, 0, False, 10)
+    assert sorted(s.key() for s in ranked) == sorted(s.key() for s in space)      # a permutation of the space
+    fam = lambda s: (s.bm, s.bn, s.bk, s.wm, s.wn, s.variant)
+    pred = lambda s: al.alcop_model_predict(prob, s, 0)[0]
+    head = ranked[:10]
+    counts = {}
+    for s in head:
+        counts[fam(s)] = counts.get(fam(s), 0) + 1
+    assert max(counts.values()) <= 2 and len(counts) >= 5
+    # within a family the head holds its best-predicted members, and families enter in model order
+    for f in counts:
+        members = sorted((pred(s) for s in space if fam(s) == f))
+        assert sorted(pred(s) for s in head if fam(s) == f) == members[:counts[f]]
+    assert [pred(s) for s in head] == sorted(pred(s) for s in head)
+    # no budget: the plain model order
+    plain = al.alcop_sched_ranked(prob, 0, False, 0)
+    assert [pred(s) for s in plain] == sorted(pred(s) for s in plain)

@@ -49,7 +49,10 @@ def test_table_rows_by_hand():
     # LDS port: A 128x64x2 B read by 2 waves along n at 256 B/clk, B likewise at 170 B/clk
     # (transposing read), plus the 32 KiB k-tile written at 256 B/clk
     t_port = (32768 / 256 + 32768 / 170 + 32768 / 256) / 1800.0
-    assert r["t_smem_use"] == pytest.approx(max(t_pipe, t_port))
+    # fill path of the compute unit: the 32 KiB k-tile at 40 B/clk
+    t_fill = 32768 / 40 / 1800.0
+    assert t_fill > t_port and t_fill > t_pipe
+    assert r["t_smem_use"] == pytest.approx(max(t_pipe, t_port, t_fill))
     # memory: LLC term 0.6 + 256 blocks * 32 KiB at 40 B/clk per CU ; DRAM term 1.2 + (16+16 panels)*128*64*2/8e6
     t_llc = 0.6 + 256 * 32768 / (40 * 256 * 1800.0)
     t_dram = 1.2 + 32 * 128 * 64 * 2 / 8.0e6
@@ -82,7 +85,8 @@ def test_table_rows_by_hand_two_blocks_per_cu_three_batches_batched():
     # LDS port: A 16 KiB read by 2 wave columns, B 16 KiB by 2 wave rows, both k-contiguous
     # (plain reads), plus the 32 KiB k-tile written; two blocks
     t_port = (32768 / d.bw_lds_cu + 32768 / d.bw_lds_cu + 32768 / d.bw_lds_cu) * 2
-    assert r["t_smem_use"] == pytest.approx(max(t_pipe, t_port))
+    t_fill = 32768 * 2 / (d.bw_llc / 256)          # two blocks share the CU's fill path
+    assert r["t_smem_use"] == pytest.approx(max(t_pipe, t_port, t_fill))
     # memory: 512 blocks * 32 KiB over the LLC; DRAM working set: the 512 co-resident blocks are
     # 32 whole matrices of 16 tiles, each a 4 x 4 patch: (4*128 + 4*128) rows of 64 halves
     t_llc = d.lat_llc + 512 * 32768 / d.bw_llc
@@ -105,6 +109,10 @@ def test_table_rows_by_hand_unfused_and_transposed_operands():
     unfused = pm.predict(*args, False, d)
     t_pipe = pm.pipeline_latency(fused["t_reg_load"], fused["t_compute"], 4, 2, 1)
     t_port = 32768 / d.bw_lds_cu + 32768 / d.bw_lds_tr_cu + 32768 / d.bw_lds_cu
+    # a fill path fast enough not to be the floor, so that the register-level terms show
+    d = pm.Device(bw_llc=1e9)
+    fused = pm.predict(*args, True, d)
+    unfused = pm.predict(*args, False, d)
     assert fused["t_smem_use"] == pytest.approx(max(t_pipe, t_port))
     assert unfused["t_smem_use"] == pytest.approx(max(t_pipe + fused["t_reg_load"], t_port))
     assert unfused["t_smem_use"] > fused["t_smem_use"]
@@ -113,7 +121,7 @@ def test_table_rows_by_hand_unfused_and_transposed_operands():
     assert r1["t_smem_use"] == pytest.approx(max((fused["t_reg_load"] + fused["t_compute"]) * 4, t_port))
     # operand layouts only enter through the port term: A stored K x M is read through the
     # transposing read, B stored N x K through the plain one
-    big = pm.Device(lat_lds=0.0, flop_per_us_cu=1e12)     # compute and latency negligible: port term rules
+    big = pm.Device(lat_lds=0.0, flop_per_us_cu=1e12, bw_llc=1e12)     # compute, latency and fill negligible: port term rules
     ta = pm.predict(*args, True, big, transA=True)
     tb = pm.predict(*args, True, big, transB=True)
     assert ta["t_smem_use"] == pytest.approx(32768 / big.bw_lds_tr_cu + 32768 / big.bw_lds_tr_cu + 32768 / big.bw_lds_cu)
@@ -140,7 +148,8 @@ def test_table_rows_by_hand_convolution_with_the_patch_in_lds():
     # port: the whole A tile is still read from LDS (by one wave column), B by 4 wave rows through
     # the transposing read; only the fetched bytes shrink
     t_port = (256 * 64 * 2 / d.bw_lds_cu + 4 * 64 * 64 * 2 / d.bw_lds_tr_cu + stage / d.bw_lds_cu) * 2
-    assert r["t_smem_use"] == pytest.approx(max(t_pipe, t_port))
+    t_fill = stage * 2 / (d.bw_llc / 256)
+    assert r["t_smem_use"] == pytest.approx(max(t_pipe, t_port, t_fill))
     t_llc = d.lat_llc + 392 * stage / d.bw_llc
     # DRAM working set: 392 tiles in one column of tiles (ntn = 1): 20 x 1 patch by the
     # near-square rule (ceil(sqrt(392)) = 20 rows, then ceil(392/20) = 20 -> capped at ntn = 1)
@@ -151,6 +160,49 @@ def test_table_rows_by_hand_convolution_with_the_patch_in_lds():
     assert r["t_kernel"] == pytest.approx(r["t_smem_load"] + r["t_reg_load"] + r["t_main_loop"] + r["t_epilogue"])
     # the plain kernel of the same schedule fetches 9x the A rows per k-tile
     assert plain["t_smem_load"] > r["t_smem_load"]
+
+
+def test_table_rows_by_hand_persistent_blocks():
+    # batched Q.K^T again, 96 x (512 x 64 . 64 x 512), fp16 out, with persistent blocks: 128x128x64
+    # tile, 4 consumer waves of 64x64, S=3, R=2, fused.  1536 tiles, one k-tile each.
+    d = pm.Device()
+    r = pm.predict(512, 512, 64, 96, 2, 128, 128, 64, 64, 64, 3, 2, True, d, transB=True, persistent=True)
+    # LDS: ring 3 * 32 KiB + staging 4 waves * 32 rows * (64*4 + 16) B = 98304 + 34816 = 133120 B
+    # -> one block per CU; 256 blocks walk ceil(1536/256) = 6 tiles each
+    assert r["n_blk_per_cu"] == 1 and r["n_threadblk_batch"] == 1
+    assert r["util"] == 1.0
+    t_compute = 2 * 128 * 128 * 16 / d.flop_per_us_cu
+    t_reg_load = d.lat_lds + 16384 / d.bw_lds_cu
+    t_port = 32768 / d.bw_lds_cu + 32768 / d.bw_lds_cu + 32768 / d.bw_lds_cu       # B stored N x K: plain reads
+    t_fill = 32768 / (d.bw_llc / 256)
+    t_smem_use = max(pm.pipeline_latency(t_reg_load, t_compute, 4, 2, 1), t_port, t_fill)
+    # 256 blocks stream at once
+    t_llc = d.lat_llc + 256 * 32768 / d.bw_llc
+    t_dram = d.lat_dram + 16 * (4 * 128 + 4 * 128) * 64 * 2 / d.bw_dram            # 16 whole matrices of 4 x 4 tiles
+    t_smem_load = max(t_llc, t_dram)
+    assert r["t_smem_load"] == pytest.approx(t_smem_load)
+    # the stores of a tile are consumer work of its one iteration: 256 tiles of 32 KiB in flight
+    t_use = t_smem_use + (256 * 32768 / d.bw_dram_write) / 1
+    assert r["t_smem_use"] == pytest.approx(t_use)
+    assert r["t_init"] == pytest.approx(t_smem_load + t_reg_load)
+    # one loop of 6 tiles * 1 k-tile, 3 stages
+    assert r["t_main_loop"] == pytest.approx(pm.pipeline_latency(t_smem_load, t_use, 6, 3, 1))
+    assert r["t_kernel"] == pytest.approx(r["t_init"] + r["t_main_loop"] + d.lat_dram_write)
+    # against the tile-at-a-time schedule of the same tile: the fill and the write latency are paid
+    # once, not once per batch of blocks
+    plain = pm.predict(512, 512, 64, 96, 2, 128, 128, 64, 64, 64, 3, 2, True, d, transB=True)
+    assert r["t_kernel"] < plain["t_kernel"]
+    # long reduction axis, few tiles (2048^3: one tile per block): the stores are spread over the
+    # 32 iterations of the tile
+    g = pm.predict(2048, 2048, 2048, 1, 2, 128, 128, 64, 64, 64, 3, 2, True, d, persistent=True)
+    t_port = 32768 / d.bw_lds_cu + 32768 / d.bw_lds_tr_cu + 32768 / d.bw_lds_cu
+    t_use = max(pm.pipeline_latency(t_reg_load, t_compute, 4, 2, 1), t_port, t_fill) + (256 * 32768 / d.bw_dram_write) / 32
+    assert g["t_smem_use"] == pytest.approx(t_use)
+    assert g["t_main_loop"] == pytest.approx(pm.pipeline_latency(g["t_smem_load"], t_use, 32, 3, 1))
+    # two blocks per CU when the LDS allows: 64x64x64 tile, S=2: 2*16 KiB + 4*32*(32*4+16) = 51200 B
+    h = pm.predict(512, 512, 64, 96, 2, 64, 64, 64, 32, 32, 2, 2, True, d, transB=True, persistent=True)
+    assert h["n_blk_per_cu"] == 2 and h["util"] == 0.5
+    assert h["t_main_loop"] == pytest.approx(pm.pipeline_latency(h["t_smem_load"], h["t_smem_use"], 12 * 1, 2, 2))
 
 
 def test_bottleneck_model_by_hand_each_resource_in_turn():
@@ -241,7 +293,7 @@ def test_library_model_matches_oracle(P):
         us, terms = al.alcop_model_predict(prob, s, 0)
         r = pm.predict(P["M"], P["N"], P["K"], P["batch"], ob, s.bm, s.bn, s.bk, s.wm, s.wn,
                        s.stages, s.reg_stages, bool(s.fuse_inner), transB=P["tb"],
-                       transA=P.get("ta", False))
+                       transA=P.get("ta", False), persistent=s.variant == 2)
         want = [r[k] for k in ("t_kernel", "t_threadblk", "t_init", "t_main_loop", "t_epilogue",
                                "t_smem_load", "t_smem_use", "n_threadblk_batch")]
         assert us == pytest.approx(r["t_kernel"], rel=1e-12)
@@ -280,13 +332,14 @@ def test_library_patch_convolution_model_matches_oracle():
     for s in al.alcop_sched_space(prob) + al.alcop_sched_variants(prob):
         us, terms = al.alcop_model_predict(prob, s, 0)
         r = pm.predict(M, N, K, 1, 2, s.bm, s.bn, s.bk, s.wm, s.wn, s.stages, s.reg_stages,
-                       bool(s.fuse_inner), patch_taps=9 if s.variant == 1 else 0)
+                       bool(s.fuse_inner), patch_taps=9 if s.variant == 1 else 0, persistent=s.variant == 2)
         assert us == pytest.approx(r["t_kernel"], rel=1e-12)
         if s.variant == 1:
             seen += 1
             # less traffic per k-tile than the default kernel of the same schedule
             plain = al.sched(s.bm, s.bn, s.bk, s.wm, s.wn, s.stages, s.reg_stages, s.fuse_inner)
             assert terms[5] < al.alcop_model_predict(prob, plain, 0)[1][5]
+    assert any(s.variant == 2 for s in al.alcop_sched_space(prob))
     assert seen >= 6
 
 
