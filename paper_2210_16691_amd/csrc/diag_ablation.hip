@@ -54,6 +54,13 @@ struct Ablated : Gfx950 {
   {
     if constexpr (!(DROP & ALCOP_DIAG_NO_BARRIER)) Gfx950::block_barrier();
   }
+  __device__ static __forceinline__ void global_store16(void* ptr, u32x4 v)
+  {
+    if constexpr (DROP & ALCOP_DIAG_NO_STORE)
+      asm volatile("" : : "v"(ptr), "v"(v));    // the conversions and the staging stay
+    else
+      Gfx950::global_store16(ptr, v);
+  }
 };
 
 struct Config {
@@ -87,9 +94,15 @@ hipError_t launch_cfg(int drop, const Params& p, dim3 grid)
     case 8: return launch_one<C, 8>(p, grid);
     case 3: return launch_one<C, 3>(p, grid);
     case 6: return launch_one<C, 6>(p, grid);
+    case 7: return launch_one<C, 7>(p, grid);
+    case 16: return launch_one<C, 16>(p, grid);
+    case 23: return launch_one<C, 23>(p, grid);
     default: return hipErrorInvalidValue;
   }
 }
+
+// a kernel that does nothing: what a launch costs when launches follow each other on one stream
+__global__ void empty_kernel() {}
 
 const Config kConfigs[] = {
     {"f16 128x128x64 w64x64 S4 R2 F1", 0, 128, 128, 64, &launch_cfg<KCfg<0, 128, 128, 64, 64, 64, 4, 2, 1, 0, 0>>},
@@ -121,7 +134,9 @@ int alcop_diag_time(int config, int drop, const void* A, const void* B, void* C,
   if (M <= 0 || N <= 0 || K <= 0 || M % cf.bm || N % cf.bn || K % cf.bk) return -1;
   if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15) return -1;
   if ((double)M * K * 2 >= 2147483648.0 || (double)K * N * 2 >= 2147483648.0) return -1;
-  if (drop != 0 && drop != 1 && drop != 2 && drop != 4 && drop != 8 && drop != 3 && drop != 6) return -1;
+  if (drop != 0 && drop != 1 && drop != 2 && drop != 4 && drop != 8 && drop != 3 && drop != 6 && drop != 7 &&
+      drop != 16 && drop != 23)
+    return -1;
   Params p;
   std::memset(&p, 0, sizeof(p));
   p.A = A;
@@ -153,6 +168,32 @@ int alcop_diag_time(int config, int drop, const void* A, const void* B, void* C,
     for (int i = 0; i < iters && rc == 0; i++)
       if (cf.launch(drop, p, grid) != hipSuccess) rc = -2;
     if (rc == 0 && (hipEventRecord(e1, 0) != hipSuccess || hipEventSynchronize(e1) != hipSuccess)) rc = -2;
+    float ms = 0;
+    if (rc == 0 && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = -2;
+    if (rc == 0 && ms * 1e3 / iters < best) best = ms * 1e3 / iters;
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc) return rc;
+  *mean_us = best;
+  return 0;
+}
+
+int alcop_diag_launch_floor(int blocks, int threads, int iters, double* mean_us)
+{
+  if (blocks <= 0 || blocks > 65536 || threads <= 0 || threads > 1024 || iters <= 0 || !mean_us) return -1;
+  for (int i = 0; i < 20; i++) alcop::empty_kernel<<<dim3((unsigned)blocks), dim3((unsigned)threads), 0, 0>>>();
+  if (hipDeviceSynchronize() != hipSuccess) return -2;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return -2;
+  double best = 1e30;
+  int rc = 0;
+  for (int rep = 0; rep < 3 && rc == 0; rep++) {
+    if (hipEventRecord(e0, 0) != hipSuccess) rc = -2;
+    for (int i = 0; i < iters; i++) alcop::empty_kernel<<<dim3((unsigned)blocks), dim3((unsigned)threads), 0, 0>>>();
+    if (rc == 0 && (hipGetLastError() != hipSuccess || hipEventRecord(e1, 0) != hipSuccess ||
+                    hipEventSynchronize(e1) != hipSuccess))
+      rc = -2;
     float ms = 0;
     if (rc == 0 && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = -2;
     if (rc == 0 && ms * 1e3 / iters < best) best = ms * 1e3 / iters;

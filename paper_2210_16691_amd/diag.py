@@ -6,8 +6,8 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-FULL, NO_DMA, NO_LDS_READ, NO_MFMA, NO_BARRIER = 0, 1, 2, 4, 8
-EXPORTS = ("alcop_diag_configs", "alcop_diag_config_name", "alcop_diag_time")
+FULL, NO_DMA, NO_LDS_READ, NO_MFMA, NO_BARRIER, NO_STORE = 0, 1, 2, 4, 8, 16
+EXPORTS = ("alcop_diag_configs", "alcop_diag_config_name", "alcop_diag_time", "alcop_diag_launch_floor")
 _lib = None
 
 
@@ -25,6 +25,8 @@ def lib() -> ctypes.CDLL:
         L.alcop_diag_time.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.POINTER(ctypes.c_double)]
+        L.alcop_diag_launch_floor.restype = ctypes.c_int
+        L.alcop_diag_launch_floor.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
         _lib = L
     return _lib
 
@@ -48,4 +50,13 @@ def alcop_diag_time(config: int, drop: int, A, B, C, iters: int = 200) -> float:
                                ctypes.byref(us))
     if rc != 0:
         raise RuntimeError("alcop_diag_time failed (%d)" % rc)
+    return us.value
+
+
+def alcop_diag_launch_floor(blocks: int = 256, threads: int = 256, iters: int = 1000) -> float:
+    """Microseconds per launch of an empty kernel of that shape, launches back to back."""
+    us = ctypes.c_double()
+    rc = lib().alcop_diag_launch_floor(blocks, threads, iters, ctypes.byref(us))
+    if rc != 0:
+        raise RuntimeError("alcop_diag_launch_floor failed (%d)" % rc)
     return us.value
