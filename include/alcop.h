@@ -214,6 +214,53 @@ int alcop_conv2d_igemm_dilated(const void* x, const void* w, void* y, int N, int
                                const alcop_sched* sched /* host */, void* hip_stream);
 
 /*
+ * Operands the pipelined loops cannot take as they are (paper Sec. 4.2: a pipeline stage is
+ * filled by asynchronous copies; here they move 16-byte chunks, hence the alignment rules of
+ * alcop_gemm): N or K not a multiple of 8, M not a multiple of 8 with transA, leading dimensions,
+ * batch strides or base addresses that are not 16-byte aligned.  A, B (and the bias) are first
+ * copied into `workspace` with every extent rounded up to 8 elements and the tails zero-filled,
+ * the product is computed there by the ordinary kernels (same schedules, same k order; the extra
+ * k terms are exact zeros, so every valid element equals what an aligned call on the same values
+ * returns), and the valid M x N part is copied to C element by element; bytes of C outside the
+ * valid elements (row padding) are not touched.  Three small copy kernels besides the product:
+ * meant for odd shapes, not for speed.
+ *   A, B, C: DEVICE pointers aligned to their element size; lda, ldb, ldc, strides in elements,
+ *     any value allowed by the shape (lda >= K or M, ...); batch = 1 with strides 0 is a GEMM.
+ *   ep: host, may be NULL; ep->bias: DEVICE pointer to N fp32 values, 4-byte aligned.
+ *   sched: a schedule for the padded problem (M, N, K rounded up to 8), or NULL = the library's pick.
+ *   workspace: DEVICE memory, 16-byte aligned, at least alcop_unaligned_workspace_bytes(batch, M, N,
+ *     K, out) bytes (that function returns 0 for arguments no call accepts); owned by the caller,
+ *     overwritten by the call.  Calls that share a workspace must be ordered on one stream.
+ * Errors as for alcop_bmm; ALCOP_ERR_SIZE also if the workspace is too small.
+ */
+size_t alcop_unaligned_workspace_bytes(int batch, int M, int N, int K, alcop_dtype out);
+int alcop_bmm_unaligned(const void* A, const void* B, void* C, int batch, int M, int N, int K,
+                        long lda, long ldb, long ldc, long strideA, long strideB, long strideC,
+                        int transA, int transB, alcop_dtype in, alcop_dtype out,
+                        const alcop_epilogue* ep /* host, may be NULL */,
+                        const alcop_sched* sched /* host */, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The same for a convolution whose channel counts are not multiples of 8 (an RGB stem: C = 3) or
+ * whose tensors are not 16-byte aligned: x (NHWC) is copied to C rounded up to 8 channels, the
+ * weights ([R][S][C][K]) to C and K rounded up, the convolution runs on the padded tensors
+ * (zero channels add exact zeros) and the K valid channels of every output pixel are copied to
+ * y (NPQK, dense).  Geometry, dilation and ep as for alcop_conv2d_igemm_dilated; sched: a
+ * schedule for the padded problem or NULL.  workspace: at least
+ * alcop_conv2d_unaligned_workspace_bytes(...) bytes, otherwise as above.
+ */
+size_t alcop_conv2d_unaligned_workspace_bytes(int N, int H, int W, int C, int K, int R, int S,
+                                              int stride_h, int stride_w, int pad_h, int pad_w,
+                                              int dil_h, int dil_w, alcop_dtype out);
+int alcop_conv2d_igemm_unaligned(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                                 int K, int R, int S, int stride_h, int stride_w, int pad_h,
+                                 int pad_w, int dil_h, int dil_w, alcop_dtype in, alcop_dtype out,
+                                 const alcop_epilogue* ep /* host, may be NULL */,
+                                 const alcop_sched* sched /* host */, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+
+/*
  * Split-K: the reduction axis is cut into `split` slices of whole k-tiles, every slice is a block
  * of its own (grid.z), and a second kernel adds the slices' fp32 partial tiles in ascending
  * order, applies f(.) and converts to the output type.  For outputs with few tiles and a long

@@ -26,6 +26,8 @@ EXPORTS = [
     "alcop_model_predict", "alcop_tune", "alcop_time", "alcop_strerror", "alcop_version",
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
     "alcop_corrector_features", "alcop_corrector_fit", "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_gemm_splitk_static", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_conv2d_igemm_dilated", "alcop_sched_variants", "alcop_sched_ranked",
+    "alcop_unaligned_workspace_bytes", "alcop_bmm_unaligned", "alcop_conv2d_unaligned_workspace_bytes",
+    "alcop_conv2d_igemm_unaligned",
 ]
 
 
@@ -127,6 +129,14 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
     L.alcop_gemm_splitk_static.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, ep, sp, i, vp]
     L.alcop_conv2d_igemm_dilated.restype = i
     L.alcop_conv2d_igemm_dilated.argtypes = [vp, vp, vp] + [i] * 14 + [i, i, ep, sp, vp]
+    L.alcop_unaligned_workspace_bytes.restype = sz
+    L.alcop_unaligned_workspace_bytes.argtypes = [i, i, i, i, i]
+    L.alcop_bmm_unaligned.restype = i
+    L.alcop_bmm_unaligned.argtypes = [vp, vp, vp, i, i, i, i, l, l, l, l, l, l, i, i, i, i, ep, sp, vp, sz, vp]
+    L.alcop_conv2d_unaligned_workspace_bytes.restype = sz
+    L.alcop_conv2d_unaligned_workspace_bytes.argtypes = [i] * 14
+    L.alcop_conv2d_igemm_unaligned.restype = i
+    L.alcop_conv2d_igemm_unaligned.argtypes = [vp, vp, vp] + [i] * 13 + [i, i, ep, sp, vp, sz, vp]
     L.alcop_conv2d_igemm_splitk.restype = i
     L.alcop_conv2d_igemm_splitk.argtypes = [vp, vp, vp] + [i] * 11 + [i, i, sp, i, vp, sz, vp]
     L.alcop_tune_splitk.restype = i
@@ -421,6 +431,55 @@ def alcop_conv2d_igemm_dilated(x, w, y, stride=(1, 1), pad=(0, 0), dilation=(1, 
                                           int(krsc), _dtype_code(x), _dtype_code(y), ctypes.byref(e),
                                           _sp(sched), _stream(stream))
     _check(rc, "alcop_conv2d_igemm_dilated")
+    return y
+
+
+def alcop_unaligned_workspace_bytes(batch, M, N, K, out_dtype) -> int:
+    return lib().alcop_unaligned_workspace_bytes(batch, M, N, K, out_dtype)
+
+
+def alcop_bmm_unaligned(A, B, C, workspace, alpha=1.0, bias=None, act=0, sched=None, transA=False,
+                        transB=False, stream=None):
+    """C = act(alpha * A.B + bias[j]) for operands of any extent and element-aligned placement
+    (2-D: a GEMM; 3-D: batched); they are padded into `workspace` (a CUDA byte tensor of at least
+    alcop_unaligned_workspace_bytes(...) bytes) and multiplied there."""
+    b, M, N, K = _mm_shapes(A, B, C, transA, transB, bias)
+    _same_place(A, workspace)
+    if not workspace.is_contiguous():
+        raise ValueError("workspace must be contiguous")
+    e = _epilogue(alpha, bias, act)
+    if A.dim() == 3:
+        ld = (A.stride(1), B.stride(1), C.stride(1), A.stride(0), B.stride(0), C.stride(0))
+    else:
+        ld = (A.stride(0), B.stride(0), C.stride(0), 0, 0, 0)
+    rc = lib().alcop_bmm_unaligned(_ptr(A), _ptr(B), _ptr(C), b, M, N, K, *ld, int(transA), int(transB),
+                                   _dtype_code(A), _dtype_code(C), ctypes.byref(e), _sp(sched),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream(stream))
+    _check(rc, "alcop_bmm_unaligned")
+    return C
+
+
+def alcop_conv2d_unaligned_workspace_bytes(N, H, W, C, K, R, S, stride, pad, dilation, out_dtype) -> int:
+    return lib().alcop_conv2d_unaligned_workspace_bytes(N, H, W, C, K, R, S, stride[0], stride[1], pad[0],
+                                                        pad[1], dilation[0], dilation[1], out_dtype)
+
+
+def alcop_conv2d_igemm_unaligned(x, w, y, workspace, stride=(1, 1), pad=(0, 0), dilation=(1, 1), alpha=1.0,
+                                 bias=None, act=0, sched=None, stream=None):
+    """y = act(alpha * conv(x, w) + bias[k]) for any channel counts (x NHWC, w RSCK, y NPQK); the
+    tensors are padded to 8 channels in `workspace` and convolved there."""
+    N, H, W, Cc, K, R, S = _conv_shapes(x, w, y, stride, pad, False, bias, dilation)
+    _same_place(x, workspace)
+    if not workspace.is_contiguous():
+        raise ValueError("workspace must be contiguous")
+    e = _epilogue(alpha, bias, act)
+    rc = lib().alcop_conv2d_igemm_unaligned(_ptr(x), _ptr(w), _ptr(y), N, H, W, Cc, K, R, S, stride[0],
+                                            stride[1], pad[0], pad[1], dilation[0], dilation[1],
+                                            _dtype_code(x), _dtype_code(y), ctypes.byref(e), _sp(sched),
+                                            _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                            _stream(stream))
+    _check(rc, "alcop_conv2d_igemm_unaligned")
     return y
 
 

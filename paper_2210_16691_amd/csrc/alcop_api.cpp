@@ -737,6 +737,63 @@ int time_sched(const Call& c, const alcop_sched& s, const KernelEntry* e, int wa
   return rc;
 }
 
+
+// ---- operands the loops cannot take as they are: padded images in a workspace (alcop_pack.hip.h)
+inline long r8(long x) { return (x + 7) & ~7L; }
+inline size_t r256(double bytes) { return ((size_t)bytes + 255) & ~(size_t)255; }
+inline int out_size(alcop_dtype out) { return out == ALCOP_F32 ? 4 : 2; }
+
+// Sections of the workspace: padded A, padded B, padded C, padded bias.  Returns the total, or 0
+// if a section would reach 2 GiB (the kernels' 32-bit offsets) or the total overflows.
+size_t unaligned_layout(double a_elems, double b_elems, double c_elems, long n8, alcop_dtype out,
+                        size_t off[4])
+{
+  const double a = 2.0 * a_elems, b = 2.0 * b_elems, c = (double)out_size(out) * c_elems;
+  if (a >= 2147483648.0 || b >= 2147483648.0 || c >= 4294967296.0) return 0;
+  off[0] = 0;
+  off[1] = off[0] + r256(a);
+  off[2] = off[1] + r256(b);
+  off[3] = off[2] + r256(c);
+  return off[3] + r256(4.0 * (double)n8);
+}
+
+PackParams pack2d(const void* src, void* dst, int rows, int cols, long s_batch, long s_row, int rows_d,
+                  int cols_d, long d_batch, long d_row, int esize)
+{
+  PackParams p;
+  p.src = src;
+  p.dst = dst;
+  p.rows = rows;
+  p.cols = cols;
+  p.s_batch = s_batch;
+  p.s_row = s_row;
+  p.rows_d = rows_d;
+  p.cols_d = cols_d;
+  p.d_batch = d_batch;
+  p.d_row = d_row;
+  p.esize = esize;
+  return p;
+}
+
+bool elem_aligned(const void* p, int esize) { return (reinterpret_cast<uintptr_t>(p) & (uintptr_t)(esize - 1)) == 0; }
+
+// Padded bias (N8 floats, zero tail) if the epilogue has one; fills the inner call's epilogue.
+int pack_epilogue(const alcop_epilogue* ep, int N, char* ws_bias, Call* inner, hipStream_t st)
+{
+  if (!ep) return ALCOP_OK;
+  inner->alpha = ep->alpha;
+  inner->act = ep->act;
+  if (ep->act != 0 && ep->act != 1) return ALCOP_ERR_UNSUPPORTED;
+  if (ep->bias) {
+    if (!elem_aligned(ep->bias, 4)) return ALCOP_ERR_ALIGN;
+    const int n8 = (int)r8(N);
+    if (launch_pack(pack2d(ep->bias, ws_bias, 1, N, 0, 0, 1, n8, 0, n8, 4), 1, st) != hipSuccess)
+      return ALCOP_ERR_LAUNCH;
+    inner->bias = ws_bias;
+  }
+  return ALCOP_OK;
+}
+
 }  // namespace
 }  // namespace alcop
 
@@ -980,6 +1037,130 @@ int alcop_conv2d_igemm_fused(const void* x, const void* w, void* y, int N, int H
     c.act = ep->act;
   }
   return run(c, sched, hip_stream);
+}
+
+size_t alcop_unaligned_workspace_bytes(int batch, int M, int N, int K, alcop_dtype out)
+{
+  if (batch <= 0 || M <= 0 || N <= 0 || K <= 0) return 0;
+  if (out != ALCOP_F16 && out != ALCOP_BF16 && out != ALCOP_F32) return 0;
+  const double b = batch, m8 = (double)r8(M), n8 = (double)r8(N), k8 = (double)r8(K);
+  size_t off[4];
+  return unaligned_layout(b * m8 * k8, b * k8 * n8, b * m8 * n8, r8(N), out, off);
+}
+
+int alcop_bmm_unaligned(const void* A, const void* B, void* C, int batch, int M, int N, int K, long lda,
+                        long ldb, long ldc, long strideA, long strideB, long strideC, int transA,
+                        int transB, alcop_dtype in, alcop_dtype out, const alcop_epilogue* ep,
+                        const alcop_sched* sched, void* workspace, size_t workspace_bytes,
+                        void* hip_stream)
+{
+  if (!A || !B || !C || !workspace) return ALCOP_ERR_NULL;
+  if (in != ALCOP_F16 && in != ALCOP_BF16) return ALCOP_ERR_DTYPE;
+  if (out != ALCOP_F16 && out != ALCOP_BF16 && out != ALCOP_F32) return ALCOP_ERR_DTYPE;
+  if (batch <= 0 || batch > 65535 || M <= 0 || N <= 0 || K <= 0) return ALCOP_ERR_SHAPE;
+  transA = transA ? 1 : 0;
+  transB = transB ? 1 : 0;
+  if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return ALCOP_ERR_SHAPE;
+  if (strideA < 0 || strideB < 0 || strideC < 0) return ALCOP_ERR_SHAPE;
+  const int osz = out_size(out);
+  if (!elem_aligned(A, 2) || !elem_aligned(B, 2) || !elem_aligned(C, osz) || !aligned16(workspace))
+    return ALCOP_ERR_ALIGN;
+  const int m8 = (int)r8(M), n8 = (int)r8(N), k8 = (int)r8(K);
+  size_t off[4];
+  const size_t need = unaligned_layout((double)batch * m8 * k8, (double)batch * k8 * n8,
+                                       (double)batch * m8 * n8, n8, out, off);
+  if (need == 0 || workspace_bytes < need) return ALCOP_ERR_SIZE;
+  char* ws = (char*)workspace;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // padded operands, each batch entry a dense matrix
+  const int a_rows = transA ? K : M, a_cols = transA ? M : K, a_rd = transA ? k8 : m8, a_cd = transA ? m8 : k8;
+  const int b_rows = transB ? N : K, b_cols = transB ? K : N, b_rd = transB ? n8 : k8, b_cd = transB ? k8 : n8;
+  Call c = gemm_call(batch > 1 ? ALCOP_OP_BMM : ALCOP_OP_GEMM, ws + off[0], ws + off[1], ws + off[2],
+                     batch, m8, n8, k8, a_cd, b_cd, n8, (long)m8 * k8, (long)k8 * n8, (long)m8 * n8,
+                     transA, transB, in, out);
+  int rc = pack_epilogue(ep, N, ws + off[3], &c, st);
+  if (rc) return rc;
+  if (launch_pack(pack2d(A, ws + off[0], a_rows, a_cols, strideA, lda, a_rd, a_cd, (long)m8 * k8, a_cd, 2),
+                  batch, st) != hipSuccess ||
+      launch_pack(pack2d(B, ws + off[1], b_rows, b_cols, strideB, ldb, b_rd, b_cd, (long)k8 * n8, b_cd, 2),
+                  batch, st) != hipSuccess)
+    return ALCOP_ERR_LAUNCH;
+  rc = run(c, sched, hip_stream);
+  if (rc) return rc;
+  if (launch_unpack(pack2d(ws + off[2], C, M, N, (long)m8 * n8, n8, m8, n8, strideC, ldc, osz), batch, st) !=
+      hipSuccess)
+    return ALCOP_ERR_LAUNCH;
+  return ALCOP_OK;
+}
+
+// Output extent of the convolution, or false if the arguments do not describe one.
+static bool conv_extent(int N, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw,
+                        int dh, int dw, long* P, long* Q)
+{
+  if (N <= 0 || H <= 0 || W <= 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0 || sh <= 0 || sw <= 0 ||
+      ph < 0 || pw < 0 || dh <= 0 || dw <= 0)
+    return false;
+  const long eh = (long)dh * (R - 1) + 1, ew = (long)dw * (S - 1) + 1;
+  if (H + 2L * ph < eh || W + 2L * pw < ew) return false;
+  *P = (H + 2L * ph - eh) / sh + 1;
+  *Q = (W + 2L * pw - ew) / sw + 1;
+  return true;
+}
+
+size_t alcop_conv2d_unaligned_workspace_bytes(int N, int H, int W, int C, int K, int R, int S,
+                                              int stride_h, int stride_w, int pad_h, int pad_w,
+                                              int dil_h, int dil_w, alcop_dtype out)
+{
+  long P, Q;
+  if (!conv_extent(N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, &P, &Q)) return 0;
+  if (out != ALCOP_F16 && out != ALCOP_BF16 && out != ALCOP_F32) return 0;
+  const double c8 = (double)r8(C), k8 = (double)r8(K);
+  size_t off[4];
+  return unaligned_layout((double)N * H * W * c8, (double)R * S * c8 * k8, (double)N * P * Q * k8, r8(K),
+                          out, off);
+}
+
+int alcop_conv2d_igemm_unaligned(const void* x, const void* w, void* y, int N, int H, int W, int C,
+                                 int K, int R, int S, int stride_h, int stride_w, int pad_h,
+                                 int pad_w, int dil_h, int dil_w, alcop_dtype in, alcop_dtype out,
+                                 const alcop_epilogue* ep, const alcop_sched* sched, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream)
+{
+  if (!x || !w || !y || !workspace) return ALCOP_ERR_NULL;
+  if (in != ALCOP_F16 && in != ALCOP_BF16) return ALCOP_ERR_DTYPE;
+  if (out != ALCOP_F16 && out != ALCOP_BF16 && out != ALCOP_F32) return ALCOP_ERR_DTYPE;
+  long P, Q;
+  if (!conv_extent(N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, &P, &Q))
+    return ALCOP_ERR_SHAPE;
+  const int osz = out_size(out);
+  if (!elem_aligned(x, 2) || !elem_aligned(w, 2) || !elem_aligned(y, osz) || !aligned16(workspace))
+    return ALCOP_ERR_ALIGN;
+  const int c8 = (int)r8(C), k8 = (int)r8(K);
+  const long pixels = (long)N * H * W, outputs = (long)N * P * Q;
+  if (pixels > 0x7fffffffL || outputs > 0x7fffffffL) return ALCOP_ERR_SHAPE;
+  size_t off[4];
+  const size_t need = unaligned_layout((double)pixels * c8, (double)R * S * c8 * k8, (double)outputs * k8,
+                                       k8, out, off);
+  if (need == 0 || workspace_bytes < need) return ALCOP_ERR_SIZE;
+  char* ws = (char*)workspace;
+  hipStream_t st = (hipStream_t)hip_stream;
+  Call c;
+  int rc = conv_call(&c, ws + off[0], ws + off[1], ws + off[2], N, H, W, c8, k8, R, S, stride_h, stride_w,
+                     pad_h, pad_w, in, out, 0, dil_h, dil_w);
+  if (rc) return rc;
+  rc = pack_epilogue(ep, K, ws + off[3], &c, st);
+  if (rc) return rc;
+  // x: pixels x C -> pixels x C8; w: (R*S) matrices of C x K -> C8 x K8
+  if (launch_pack(pack2d(x, ws + off[0], (int)pixels, C, 0, C, (int)pixels, c8, 0, c8, 2), 1, st) != hipSuccess ||
+      launch_pack(pack2d(w, ws + off[1], C, K, (long)C * K, K, c8, k8, (long)c8 * k8, k8, 2), R * S, st) !=
+          hipSuccess)
+    return ALCOP_ERR_LAUNCH;
+  rc = run(c, sched, hip_stream);
+  if (rc) return rc;
+  if (launch_unpack(pack2d(ws + off[2], y, (int)outputs, K, 0, k8, (int)outputs, k8, 0, K, osz), 1, st) !=
+      hipSuccess)
+    return ALCOP_ERR_LAUNCH;
+  return ALCOP_OK;
 }
 
 int alcop_sched_supported(const alcop_problem* prob, const alcop_sched* sched)

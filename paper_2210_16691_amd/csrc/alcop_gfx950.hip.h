@@ -119,6 +119,11 @@ struct Gfx950 {
   {
     return *(const f32x4*)ptr;
   }
+  // element-wise accesses of the pack / unpack kernels (any element-aligned address)
+  __device__ static __forceinline__ uint16_t global_load_u16(const void* ptr) { return *(const uint16_t*)ptr; }
+  __device__ static __forceinline__ uint32_t global_load_u32(const void* ptr) { return *(const uint32_t*)ptr; }
+  __device__ static __forceinline__ void global_store_u16(void* ptr, uint16_t v) { *(uint16_t*)ptr = v; }
+  __device__ static __forceinline__ void global_store_u32(void* ptr, uint32_t v) { *(uint32_t*)ptr = v; }
   // fp32 -> output element, round to nearest even
   template <class OT>
   __device__ static __forceinline__ OT cvt(float v)

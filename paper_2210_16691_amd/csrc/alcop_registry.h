@@ -4,6 +4,7 @@
 #include <vector>
 
 #include "alcop_kernel.hip.h"
+#include "alcop_pack.hip.h"
 #include "alcop_splitk.hip.h"
 
 namespace alcop {
@@ -38,6 +39,10 @@ void register_splitk_conv(std::vector<KernelEntry>&);
 
 // Second step of a split-K product (alcop_splitk.hip.h).
 hipError_t launch_splitk_reduce(const ReduceParams& p, dim3 grid, hipStream_t st);
+
+// Copies into and out of the padded workspace images (alcop_pack.hip.h); grid.y = batch entries.
+hipError_t launch_pack(const PackParams& p, int batch, hipStream_t st);
+hipError_t launch_unpack(const PackParams& p, int batch, hipStream_t st);
 
 // Device address and size of the library's own scratch array on the current device (set up on
 // the first call per device; allocates nothing afterwards).  Its size is part of the interface

@@ -491,6 +491,30 @@ struct Emu {
       fail("global load outside every operand (thread %d)", blk()->cur);
     return v;
   }
+  template <class T>
+  static T global_load_elem(const void* ptr)
+  {
+    T v = 0;
+    if ((uintptr_t)ptr % sizeof(T)) fail("element load from a misaligned address (thread %d)", blk()->cur);
+    if (in_buffer(ptr, sizeof(T), false))
+      memcpy(&v, ptr, sizeof(T));
+    else
+      fail("element load outside every operand: block %u,%u thread %d", blk()->bx, blk()->by, blk()->cur);
+    return v;
+  }
+  template <class T>
+  static void global_store_elem(void* ptr, T v)
+  {
+    if ((uintptr_t)ptr % sizeof(T)) fail("element store to a misaligned address (thread %d)", blk()->cur);
+    if (in_buffer(ptr, sizeof(T), true))
+      memcpy(ptr, &v, sizeof(T));
+    else
+      fail("element store outside the output: block %u,%u thread %d", blk()->bx, blk()->by, blk()->cur);
+  }
+  static uint16_t global_load_u16(const void* ptr) { return global_load_elem<uint16_t>(ptr); }
+  static uint32_t global_load_u32(const void* ptr) { return global_load_elem<uint32_t>(ptr); }
+  static void global_store_u16(void* ptr, uint16_t v) { global_store_elem<uint16_t>(ptr, v); }
+  static void global_store_u32(void* ptr, uint32_t v) { global_store_elem<uint32_t>(ptr, v); }
   template <class OT>
   static OT cvt(float v)
   {

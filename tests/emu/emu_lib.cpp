@@ -217,6 +217,22 @@ hipError_t launch_splitk_reduce(const ReduceParams& p, dim3 grid, hipStream_t)
   emu::run_grid(&reduce_entry, &p, REDUCE_THREADS, 0, grid.x, grid.y, grid.z);
   return hipSuccess;
 }
+static void pack_entry(const void* p) { alcop_pack<emu::Emu>(*(const PackParams*)p); }
+static void unpack_entry(const void* p) { alcop_unpack<emu::Emu>(*(const PackParams*)p); }
+hipError_t launch_pack(const PackParams& p, int batch, hipStream_t)
+{
+  const long threads = (long)p.rows_d * (p.cols_d / (16 / p.esize));
+  emu::run_grid(&pack_entry, &p, PACK_THREADS, 0, (unsigned)((threads + PACK_THREADS - 1) / PACK_THREADS),
+                (unsigned)batch, 1);
+  return hipSuccess;
+}
+hipError_t launch_unpack(const PackParams& p, int batch, hipStream_t)
+{
+  const long threads = (long)p.rows * (p.cols_d / (16 / p.esize));
+  emu::run_grid(&unpack_entry, &p, PACK_THREADS, 0, (unsigned)((threads + PACK_THREADS - 1) / PACK_THREADS),
+                (unsigned)batch, 1);
+  return hipSuccess;
+}
 // host stand-in for the library's device scratch array
 hipError_t splitk_scratch(void** ptr, size_t* bytes)
 {
