@@ -34,6 +34,7 @@ const std::vector<KernelEntry>& registry()
     register_conv_patch(t);
     register_bk128(t);
     register_deep(t);
+    register_wide(t);
     register_pf(t);
     register_stream(t);
     register_splitk_gemm(t);

@@ -100,12 +100,18 @@ template <int LAY_, int BX_, int WX_, int BK_, int NT_>
 struct Opnd {
   static constexpr int LAY = LAY_, BX = BX_, WX = WX_, BK = BK_, NT = NT_;
   static constexpr int BYTES = BX * BK * 2;
-  static constexpr int CPR = LAY == LAY_K ? BK / 8 : BX / 8;   // 16-byte chunks per LDS row
+  // An M/N-contiguous tile whose width is a multiple of 64 but not a power of two (192 = 3 x 64)
+  // is kept in LDS as BX / 64 images of 64 columns each, one after the other; each image has
+  // the layout and swizzle of a 64-wide tile, and one block-wide load fills exactly one image.
+  static constexpr bool PARTS = LAY == LAY_MN && BX % 64 == 0 && (BX & (BX - 1)) != 0;
+  static constexpr int PBX = PARTS ? 64 : BX;                  // columns of one LDS image
+  static constexpr int ROWB = LAY == LAY_K ? BK * 2 : PBX * 2; // bytes of one LDS row
+  static constexpr int CPR = ROWB / 16;                        // 16-byte chunks per LDS row
   static constexpr int RSTEP = NT / CPR;                       // LDS rows one block-wide load covers
   static constexpr int NL = BYTES / (NT * 16);                 // loads per thread and k-tile
   static constexpr int TX = WX / 32;                           // 32-wide sub-tiles per wave
   // swizzle of the M/N-contiguous layout
-  static constexpr int UPR = BX / 32;                          // 64-byte units per row
+  static constexpr int UPR = PBX / 32;                         // 64-byte units per row
   static constexpr int RPB = (4 / UPR) > 1 ? (4 / UPR) : 1;    // rows per 256-byte bank line
   static constexpr int GM = UPR < 4 ? UPR : 4;
   static constexpr int NRD = LAY == LAY_K ? BK / 16 : TX;      // lane-address registers of the reader
@@ -113,6 +119,7 @@ struct Opnd {
   // 128-byte lines (or parts of lines) in the k-slice of one tile, for the L2 touches
   static constexpr int LINES = LAY == LAY_K ? BX : BK * ((BX * 2) / 128);
   static_assert(BYTES % (NT * 16) == 0, "loads per thread");
+  static_assert(!PARTS || NT == BK * CPR, "one block-wide load per 64-column image");
   // K-contiguous layout: the LDS has 64 banks of 4 bytes, so RPL = 256 / (row bytes) rows share
   // one 256-byte bank line (4, 2, 1 rows for BK = 32, 64, 128).  A 16-byte read instruction is
   // served 16 lanes (= 16 consecutive rows of one chunk column) per clock; they hit 16 distinct
@@ -176,6 +183,7 @@ struct KCfg {
   // and whose filter taps are formed by shifted LDS reads: only the weights stream through the ring
   static_assert(AM != 3 || (SK == 0 && BL == 0), "patch convolution: RSCK weights, no split-K");
   static_assert(!PF || (AM == 0 && SK == 0 && FUSE), "L2 touches: fused matrix-operand kernels only");
+  static_assert(!PF || !(OA::PARTS || OB::PARTS), "L2 touches: tile widths that are powers of two");
   static_assert(!(AM != 0 && AL == 1), "the convolution gather produces a K-contiguous A tile");
   static_assert(WAIT <= 63, "vmcnt is a 6-bit counter");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS ring exceeds 160 KB");
@@ -227,7 +235,8 @@ __device__ __forceinline__ LoadState<HW> setup_loader(const void* ptr, int t, in
     const char* base = (const char*)ptr + (long)t * O::BX * 2;
     st.rsrc = HW::make_rsrc(base, ((K - 1) * ld + valid) * 2);
     st.voff = (uint32_t)(r * ld * 2 + c * 16);
-    st.step = (uint32_t)(O::RSTEP * ld * 2);
+    // the next load: RSTEP rows further down, or (64-column images) the same rows of the next image
+    st.step = O::PARTS ? (uint32_t)(O::PBX * 2) : (uint32_t)(O::RSTEP * ld * 2);
     st.kstep = (uint32_t)(O::BK * ld * 2);
     st.voff_t = st.voff;   // rows k >= K lie beyond the descriptor
   }
@@ -253,8 +262,9 @@ __device__ __forceinline__ void setup_reader(int lane, int wx, uint32_t tile_off
 #pragma unroll
     for (int t = 0; t < O::NRD; t++) {
       const int n = wx * O::WX + t * 32 + 16 * (G & 1) + 4 * (s & 3);
-      const int c = (n >> 3) ^ O::swz(k);
-      rd[t] = tile_off + (uint32_t)(k * (O::BX * 2) + c * 16 + (n & 7) * 2);
+      const int img = n / O::PBX, nl = n % O::PBX;          // image 0 and n itself unless PARTS
+      const int c = (nl >> 3) ^ O::swz(k);
+      rd[t] = tile_off + (uint32_t)(img * (O::BK * O::ROWB) + k * O::ROWB + c * 16 + (n & 7) * 2);
     }
   }
 }
@@ -268,7 +278,7 @@ __device__ __forceinline__ void read_instr(const uint32_t (&cur)[O::NRD], int ki
     frag[r] = HW::lds_read16(cur[ki] + r * (32 * O::BK * 2));
   } else {
     const int t = r >> 1, h = r & 1;
-    const u32x2 v = HW::lds_read_tr8(cur[t] + ki * (16 * O::BX * 2) + h * (4 * O::BX * 2));
+    const u32x2 v = HW::lds_read_tr8(cur[t] + ki * (16 * O::ROWB) + h * (4 * O::ROWB));
     frag[t][2 * h] = v[0];
     frag[t][2 * h + 1] = v[1];
   }
@@ -775,9 +785,19 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
                          HW::template cvt<OT>(v[2]), HW::template cvt<OT>(v[3])};
           HW::lds_write(ebase + (lane & 31) * RS + (i * 32 + 8 * vq + 4 * (lane >> 5)) * OB, h);
         }
+      // a row is LPR lanes long; when that does not divide 64 (a wave tile 96 wide) the last
+      // lanes of an instruction idle and the last instruction covers fewer rows
+      constexpr bool EVEN = 64 % LPR == 0 && 32 % RPI == 0;
+      constexpr int NIT = (32 + RPI - 1) / RPI;
 #pragma unroll
-      for (int t = 0; t < 32 / RPI; t++) {
-        const int r = t * RPI + lane / LPR, c16 = lane % LPR;
+      for (int t = 0; t < NIT; t++) {
+        int r = t * RPI + lane / LPR;
+        const int c16 = lane % LPR;
+        bool lane_ok = true;
+        if constexpr (!EVEN) {
+          lane_ok = lane < RPI * LPR && r < 32;
+          if (!lane_ok) r = 0;            // every lane takes part in the read; idle ones store nothing
+        }
         const u32x4 v = HW::lds_read16(ebase + r * RS + c16 * 16);
         int m = m0 + j * 32 + r;
         const int n = n0 + c16 * (16 / OB);
@@ -789,7 +809,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
           row_ok = pp < p.cP && qq < p.cQ;
           m = (p_img * p.cP + pp) * p.cQ + qq;
         }
-        if (row_ok && n < p.N)
+        if (lane_ok && row_ok && n < p.N)
           HW::global_store16(Cb + ((long)m * p.ldc + n) * OB, v);
       }
     }

@@ -32,6 +32,7 @@ void register_conv_anyc(std::vector<KernelEntry>&);
 void register_conv_patch(std::vector<KernelEntry>&);
 void register_bk128(std::vector<KernelEntry>&);
 void register_deep(std::vector<KernelEntry>&);
+void register_wide(std::vector<KernelEntry>&);
 void register_pf(std::vector<KernelEntry>&);
 void register_stream(std::vector<KernelEntry>&);
 void register_splitk_gemm(std::vector<KernelEntry>&);

@@ -341,13 +341,23 @@ __global__ void __launch_bounds__(C::NT) alcop_stream(const Params p)
                              HW::template cvt<OT>(v[2]), HW::template cvt<OT>(v[3])};
               HW::lds_write(ebase + (lane & 31) * RS + (i * 32 + 8 * vq + 4 * (lane >> 5)) * OBY, h);
             }
+          // a row is LPR lanes long; when that does not divide 64 (a wave tile 96 wide) the last
+          // lanes of an instruction idle and the last instruction covers fewer rows
+          constexpr bool EVEN = 64 % LPR == 0 && 32 % RPI == 0;
+          constexpr int NIT = (32 + RPI - 1) / RPI;
 #pragma unroll
-          for (int t = 0; t < 32 / RPI; t++) {
-            const int r = t * RPI + lane / LPR, c16 = lane % LPR;
+          for (int t = 0; t < NIT; t++) {
+            int r = t * RPI + lane / LPR;
+            const int c16 = lane % LPR;
+            bool lane_ok = true;
+            if constexpr (!EVEN) {
+              lane_ok = lane < RPI * LPR && r < 32;
+              if (!lane_ok) r = 0;        // every lane takes part in the read; idle ones store nothing
+            }
             const u32x4 v = HW::lds_read16(ebase + r * RS + c16 * 16);
             const int m = m0 + jj * 32 + r;
             const int n = n0 + c16 * (16 / OBY);
-            if (m < p.M && n < p.N) HW::global_store16(Cb + ((long)m * p.ldc + n) * OBY, v);
+            if (lane_ok && m < p.M && n < p.N) HW::global_store16(Cb + ((long)m * p.ldc + n) * OBY, v);
           }
         }
       };

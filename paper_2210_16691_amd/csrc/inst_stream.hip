@@ -25,6 +25,9 @@ void register_stream(std::vector<KernelEntry>& t)
   // bf16
   ALCOP_BOTH_BK(ALCOP_STREAM_STAGES, t, 1, 128, 128, 64, 64, 0, 0)
   ALCOP_BOTH_BK(ALCOP_STREAM_STAGES, t, 1, 64, 64, 32, 32, 0, 0)
+  // tiles 192 wide along n (three 64-column LDS images; one producer load per image needs bk = 32)
+  ALCOP_STREAM_STAGES(t, 1, 128, 192, 32, 64, 96, 0, 0)
+  ALCOP_STREAM_STAGES(t, 0, 128, 192, 32, 64, 96, 0, 0)
   // convolution gather, RSCK weights
   ALCOP_BOTH_BK(ALCOP_STREAM_STAGES, t, 0, 128, 64, 64, 32, 0, 1)
   ALCOP_BOTH_BK(ALCOP_STREAM_STAGES, t, 0, 64, 64, 32, 32, 0, 1)

@@ -34,7 +34,7 @@ def _compile(job) -> str:
 def build() -> str:
     os.makedirs(OUT, exist_ok=True)
     emu = os.path.join(HERE, "emu_lib.cpp")
-    jobs = [(emu, os.path.join(OUT, "emu_part%d.o" % p), ["-DEMU_PART=%d" % p]) for p in range(7)]
+    jobs = [(emu, os.path.join(OUT, "emu_part%d.o" % p), ["-DEMU_PART=%d" % p]) for p in range(8)]
     jobs.append((emu, os.path.join(OUT, "emu_main.o"), ["-DEMU_PART=-1"]))
     for name in ("alcop_api.cpp", "alcop_model.cpp"):
         jobs.append((os.path.join(CSRC, name), os.path.join(OUT, name + ".o"), []))

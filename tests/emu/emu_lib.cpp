@@ -153,6 +153,20 @@ void emu_part_6(std::vector<KernelEntry>& t)
   add_stream<0, 64, 64, 64, 32, 32, 3, 1, 0, 0, 0>(t);
   add_stream<0, 128, 64, 64, 64, 32, 3, 0, 1, 0, 0>(t);
 }
+#elif EMU_PART == 7
+void emu_part_7(std::vector<KernelEntry>& t)
+{
+  // tiles 192 wide along a contiguous m / n axis: three 64-column LDS images
+  add<0, 256, 192, 32, 128, 96, 3, 2, 1, 0, 0>(t);
+  add<0, 256, 192, 32, 128, 96, 1, 1, 0, 0, 0>(t);
+  add<1, 256, 192, 32, 128, 96, 4, 2, 1, 0, 0>(t);     // bf16
+  add<0, 256, 192, 64, 64, 96, 2, 2, 1, 0, 0>(t);      // 8 waves, k-tile of 64
+  add<0, 256, 192, 32, 128, 96, 3, 3, 1, 0, 0>(t);     // deep register pipeline
+  add<0, 192, 256, 32, 96, 128, 3, 2, 1, 0, 0, 1>(t);  // A stored K x M, 192 rows of C per tile
+  add<0, 256, 192, 32, 128, 96, 2, 2, 1, 1, 0>(t);     // B stored N x K: plain rows, 192 of them
+  add_stream<0, 128, 192, 32, 64, 96, 3, 0, 0>(t);     // persistent kernels
+  add_stream<1, 128, 192, 32, 64, 96, 4, 0, 0, 0, 0>(t);
+}
 #elif EMU_PART == 3
 void emu_part_3(std::vector<KernelEntry>& t)
 {
@@ -188,6 +202,7 @@ void emu_part_3(std::vector<KernelEntry>&);
 void emu_part_4(std::vector<KernelEntry>&);
 void emu_part_5(std::vector<KernelEntry>&);
 void emu_part_6(std::vector<KernelEntry>&);
+void emu_part_7(std::vector<KernelEntry>&);
 void register_f16_kn_mid(std::vector<KernelEntry>& t)
 {
   emu_part_0(t);
@@ -197,6 +212,7 @@ void register_f16_kn_mid(std::vector<KernelEntry>& t)
   emu_part_4(t);
   emu_part_5(t);
   emu_part_6(t);
+  emu_part_7(t);
 }
 void register_splitk_gemm(std::vector<KernelEntry>&) {}
 void register_splitk_conv(std::vector<KernelEntry>&) {}
@@ -205,6 +221,7 @@ void register_conv_anyc(std::vector<KernelEntry>&) {}
 void register_conv_patch(std::vector<KernelEntry>&) {}
 void register_bk128(std::vector<KernelEntry>&) {}
 void register_deep(std::vector<KernelEntry>&) {}
+void register_wide(std::vector<KernelEntry>&) {}
 void register_pf(std::vector<KernelEntry>&) {}
 void register_stream(std::vector<KernelEntry>&) {}
 

@@ -685,3 +685,47 @@ def test_stream_schedules_are_refused_where_they_do_not_apply():
         with pytest.raises(al.AlcopError) as e:
             emu.call(al.alcop_gemm, A, B, C, bad, reads=[A, B], writes=[C])
         assert e.value.code == al.ERR_SCHED
+
+
+# ---- tiles 192 wide: three 64-column LDS images per stage ------------------------------------
+@pytest.mark.parametrize("dt,transA,transB", [("f16", 0, 0), ("bf16", 0, 0), ("f16", 1, 0), ("f16", 0, 1)])
+def test_tiles_192_wide_exact_and_in_bounds(dt, transA, transB):
+    prob = al.problem(al.OP_GEMM, 512, 768, 512, ADT[dt], ADT[dt], transB=bool(transB), transA=bool(transA))
+    scheds = [s for s in emu.space(prob) if 192 in (s.bm, s.bn)]
+    assert scheds
+    for n, s in enumerate(scheds):
+        # full tile; ragged in m and n (the last image partly, then wholly, beyond N); one k-tile,
+        # several and a partial one; a second tile in each direction
+        for M, N, K in ((s.bm, s.bn, s.bk), (s.bm - 24, s.bn - 40, 3 * s.bk + 8), (s.bm + 8, s.bn - 72, 5 * s.bk),
+                        (s.bm + 40, 2 * s.bn - 8, 2 * s.bk + 16)):
+            if transA:
+                M = (M + 7) // 8 * 8
+            for policy in (emu.POLICIES[n % 4], emu.POLICIES[(n + 2) % 4]):
+                errs, ok = _gemm_case(dt, transA, transB, s, M, N, K, policy, out="f32" if n % 2 else dt, seed=40 + n)
+                assert not errs, (repr(s), (M, N, K), policy, errs[:4])
+                assert ok, (repr(s), (M, N, K), policy)
+
+
+def test_tiles_192_wide_persistent_kernel_several_tiles_per_block(monkeypatch):
+    prob = al.problem(al.OP_GEMM, 512, 768, 512, al.F16, al.F16)
+    scheds = [s for s in emu.space(prob) if s.bn == 192 and s.variant == 2]
+    assert scheds
+    for s in scheds:
+        for blocks in ("1", "2", "5"):
+            monkeypatch.setenv("ALCOP_STREAM_BLOCKS", blocks)
+            errs, ok = _gemm_case("f16", 0, 0, s, 2 * s.bm + 24, 3 * s.bn - 40, 3 * s.bk + 8, (1, 1), out="f32", seed=77)
+            assert not errs, (repr(s), blocks, errs[:4])
+            assert ok, (repr(s), blocks)
+
+
+def test_tiles_192_wide_fused_epilogue_batched():
+    b, M, N, K = 2, 300, 200, 104
+    A = wl.small_ints((b, M, K), "f16", 4101)
+    B = wl.small_ints((b, K, N), "f16", 4102)
+    bias = (torch.arange(N, dtype=torch.float32) % 7) - 3
+    ref = oracle.epilogue(oracle.bmm(wl.bits(A), wl.bits(B), oracle.F16), 0.5, bias.double().numpy(), 1)
+    for s in (al.sched(256, 192, 32, 128, 96, 3, 2, 1), al.sched(256, 192, 64, 64, 96, 2, 2, 1)):
+        C = torch.full((b, M, N), float("nan"), dtype=torch.float16)
+        errs = emu.call(al.alcop_bmm_fused, A, B, C, 0.5, bias, 1, s, reads=[A, B, bias], writes=[C], policy=(1, 1))
+        assert not errs, (repr(s), errs[:4])
+        assert _exact(C, ref), repr(s)
