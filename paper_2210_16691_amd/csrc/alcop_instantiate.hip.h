@@ -31,7 +31,7 @@ constexpr bool instance_feasible(int bm, int bn, int bk, int wm, int wn, int s, 
   const int nt = (bm / wm) * (bn / wn) * 64;
   const int a = bm * bk * 2, b = bn * bk * 2;
   if (a % (nt * 16) || b % (nt * 16)) return false;
-  if (s * (a + b) + (nt / 64) * 256 > 160 * 1024) return false;
+  if (s * (a + b) + (pf ? (nt / 64) * 256 : 0) > 160 * 1024) return false;
   if (f && (r < 2 || s < 2)) return false;
   if (r > 2 && (!f || (r - 1) * 16 > bk)) return false;
   const int l = (a + b) / (nt * 16) + pf;

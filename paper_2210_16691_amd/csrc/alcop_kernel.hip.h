@@ -157,7 +157,9 @@ struct KCfg {
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int RING_BYTES = S * STAGE_BYTES;
   static constexpr int EPI_WAVE_BYTES = 32 * (WN * 4 + 16);     // epilogue band, fp32 worst case
-  static constexpr int MAIN_BYTES = RING_BYTES + NWAVES * 256;  // + landing pad of the L2 touches
+  // the kernels with L2 touches add a landing pad per wave; without it two stages of a 40 KB
+  // stage are exactly 80 KB and two blocks share a compute unit
+  static constexpr int MAIN_BYTES = RING_BYTES + (PF_ ? NWAVES * 256 : 0);
   static constexpr int LDS_BYTES =
       MAIN_BYTES > NWAVES * EPI_WAVE_BYTES ? MAIN_BYTES : NWAVES * EPI_WAVE_BYTES;
   static constexpr int NLA = AM == 3 ? 0 : OA::NL, NLB = OB::NL;
