@@ -403,7 +403,10 @@ int alcop_model_predict(const alcop_problem* prob /* host */, const alcop_sched*
  * are overwritten), synchronises the stream, times each trial with HIP events.
  *   top_k > 0: time the top_k feasible schedules by predicted latency, at most max(2, top_k / 4)
  *   of them from one (tile, wave tile, variant) family (the pipelining variants of one tile are
- *   predicted within a few percent of each other and would otherwise fill the budget);
+ *   predicted within a few percent of each other and would otherwise fill the budget); with
+ *   top_k >= 8 the last trials of the budget go to the one-stage schedule of the two best-ranked
+ *   tile families of the default kernels, unless the budget holds one already (pipelining slows
+ *   some operators down, Sec. 6.2, and a static model cannot be trusted to know which);
  *   top_k == 0: time all feasible schedules (exhaustive / grid search, the 100 % reference of
  *   Sec. 6.4).
  *   model: 0 / 1 as in alcop_model_predict (fixed ranking by that model);
@@ -451,7 +454,7 @@ int alcop_corrector_fit(const double* x /* host */, const double* measured_us /*
 /*
  * The order in which alcop_tune(top_k, model 0 or 1) tries the schedules of a problem (those that
  * only the call's geometry could still prune included): by predicted latency with the per-family
- * cap described there.  Host only.  Writes up to cap schedules, returns their total number.
+ * cap and the one-stage trials described there.  Host only.  Writes up to cap schedules, returns their total number.
  */
 int alcop_sched_ranked(const alcop_problem* prob /* host */, int model, int variants, int top_k,
                        alcop_sched* out /* host */, int cap);

@@ -642,6 +642,36 @@ void spread_over_tiles(std::vector<Cand>& ranked, int top_k)
       tail.push_back(cd);
     }
   }
+  // Insurance against the case the paper reports in Sec. 6.2 (pipelining slows some operators
+  // down): with a budget of 8 or more, the budget's last trials go to the unpipelined (one-stage)
+  // schedule of the two best-ranked tile-at-a-time tile families, unless it holds one already.
+  if (top_k >= 8) {
+    std::vector<std::tuple<int, int, int, int, int, int>> fams;
+    for (const Cand& cd : head) {
+      const alcop_sched& s = cd.s;
+      if (s.variant != 0) continue;
+      const auto f = std::make_tuple(s.bm, s.bn, s.bk, s.wm, s.wn, s.variant);
+      if (std::find(fams.begin(), fams.end(), f) == fams.end()) fams.push_back(f);
+      if (fams.size() == 2) break;
+    }
+    std::vector<Cand> ins;
+    for (const auto& f : fams) {
+      auto of_family = [&](const Cand& cd) {
+        const alcop_sched& s = cd.s;
+        return std::make_tuple(s.bm, s.bn, s.bk, s.wm, s.wn, s.variant) == f && s.stages == 1;
+      };
+      if (std::any_of(head.begin(), head.end(), of_family)) continue;
+      auto it = std::find_if(tail.begin(), tail.end(), of_family);
+      if (it == tail.end()) continue;
+      ins.push_back(*it);
+      tail.erase(it);
+    }
+    if (ins.size() < head.size()) {
+      tail.insert(tail.begin(), head.end() - (long)ins.size(), head.end());
+      head.resize(head.size() - ins.size());
+      head.insert(head.end(), ins.begin(), ins.end());
+    }
+  }
   head.insert(head.end(), tail.begin(), tail.end());
   ranked.swap(head);
 }
