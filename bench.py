@@ -294,6 +294,7 @@ def ablation_report(wl, torch, dev):
              ("no_mfma", diag.NO_MFMA), ("no_barrier", diag.NO_BARRIER),
              ("no_dma_no_lds_reads", diag.NO_DMA | diag.NO_LDS_READ),
              ("dma_only", diag.NO_LDS_READ | diag.NO_MFMA), ("no_store", diag.NO_STORE),
+             ("no_lds_swizzle", diag.NO_SWIZZLE),
              ("launch_prologue_barriers_epilogue", diag.NO_DMA | diag.NO_LDS_READ | diag.NO_MFMA),
              ("the_same_without_stores", diag.NO_DMA | diag.NO_LDS_READ | diag.NO_MFMA | diag.NO_STORE)]
     rep = {"empty_kernel_us": {"%dx%d" % (b, t): round(diag.alcop_diag_launch_floor(b, t, 1000), 2)

@@ -26,7 +26,9 @@ enum {
   ALCOP_DIAG_NO_LDS_READ = 2, /* no fragment reads: the matrix cores consume undefined registers */
   ALCOP_DIAG_NO_MFMA = 4,     /* no matrix instructions                                          */
   ALCOP_DIAG_NO_BARRIER = 8,  /* no block-wide barrier (waits on the counters stay)              */
-  ALCOP_DIAG_NO_STORE = 16    /* no global stores of C (conversion and LDS staging stay)         */
+  ALCOP_DIAG_NO_STORE = 16,   /* no global stores of C (conversion and LDS staging stay)         */
+  ALCOP_DIAG_NO_SWIZZLE = 32  /* LDS tile images not permuted: every operation stays and the    */
+                              /* result is right, but the fragment reads meet bank conflicts    */
 };
 
 /* Number of kernel configurations built in, and a description of configuration i
@@ -40,7 +42,7 @@ const char* alcop_diag_config_name(int i);
  * pointers owned by the caller, 16-byte aligned, M, N multiples of the tile and K of the k-tile.
  * `iters` back-to-back launches after 20 warm-up launches, 3 repeats; writes the best mean
  * microseconds per launch.  Only the combinations 0, 1, 2, 4, 8, 16, 1|2, 2|4, 1|2|4 (what is
- * left is launch, prologue, barriers and epilogue) and 1|2|4|16 are built.
+ * left is launch, prologue, barriers and epilogue), 1|2|4|16 and 32 are built.
  * Returns 0, or -1 (bad argument / combination not built), -2 (HIP error).
  */
 int alcop_diag_time(int config, int drop, const void* A, const void* B, void* C, int M, int N,

@@ -23,6 +23,7 @@ namespace alcop {
 
 struct Gfx950 {
   using Rsrc = __amdgpu_buffer_rsrc_t;
+  static constexpr bool kSwizzle = true;   // LDS tile images are bank-conflict-free permutations
 
   // lane within the wavefront, and the wavefront's index within the block (a scalar)
   __device__ static __forceinline__ int lane_id() { return threadIdx.x & 63; }

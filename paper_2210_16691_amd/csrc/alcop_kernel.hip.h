@@ -127,9 +127,12 @@ struct Opnd {
   // chunks: physical chunk = logical chunk XOR ((row / RPL) mod CPR).
   static constexpr int RPL = (128 / BK) > 1 ? (128 / BK) : 1;
   static_assert(LAY == LAY_K ? (RSTEP % (RPL * CPR) == 0) : (RSTEP % (4 * RPB) == 0), "swizzle period");
-  // logical 16-byte chunk -> physical chunk within LDS row `row`
+  // logical 16-byte chunk -> physical chunk within LDS row `row` (HW::kSwizzle = false, a
+  // measurement aid, leaves the tile image unpermuted: same results, bank conflicts)
+  template <class HW>
   __device__ static __forceinline__ int swz(int row)
   {
+    if constexpr (!HW::kSwizzle) return 0;
     return LAY == LAY_K ? ((row / RPL) % CPR) : (((row / RPB) % GM) << 2);
   }
 };
@@ -224,7 +227,7 @@ __device__ __forceinline__ LoadState<HW> setup_loader(const void* ptr, int t, in
 {
   LoadState<HW> st;
   const int r = q0 / O::CPR, ph = q0 % O::CPR;
-  const int c = ph ^ O::swz(r);
+  const int c = ph ^ O::template swz<HW>(r);
   const int valid = (extent - t * O::BX) < O::BX ? (extent - t * O::BX) : O::BX;
   if constexpr (O::LAY == LAY_K) {
     const char* base = (const char*)ptr + (long)t * O::BX * ld * 2;
@@ -247,7 +250,7 @@ __device__ __forceinline__ LoadState<HW> setup_loader(const void* ptr, int t, in
 
 // Consumer set-up: lane addresses (relative to the stage base) of the operand fragment that
 // feeds v_mfma_f32_32x32x16: lane l = row/column l%32 of a 32-wide sub-tile, k = 8*(l/32)..+7.
-template <class O>
+template <class O, class HW>
 __device__ __forceinline__ void setup_reader(int lane, int wx, uint32_t tile_off,
                                              uint32_t (&rd)[O::NRD])
 {
@@ -255,7 +258,7 @@ __device__ __forceinline__ void setup_reader(int lane, int wx, uint32_t tile_off
     const int row = wx * O::WX + (lane & 31);
 #pragma unroll
     for (int ki = 0; ki < O::NRD; ki++)
-      rd[ki] = tile_off + (uint32_t)(row * (O::BK * 2) + (((2 * ki + (lane >> 5)) ^ O::swz(row)) * 16));
+      rd[ki] = tile_off + (uint32_t)(row * (O::BK * 2) + (((2 * ki + (lane >> 5)) ^ O::template swz<HW>(row)) * 16));
   } else {
     // transposing read: 16-lane group G reads 4 k-rows x 16 columns; lane s of the group
     // supplies row s/4, columns 4*(s%4)..+3 and receives column s, rows 0..3.
@@ -265,7 +268,7 @@ __device__ __forceinline__ void setup_reader(int lane, int wx, uint32_t tile_off
     for (int t = 0; t < O::NRD; t++) {
       const int n = wx * O::WX + t * 32 + 16 * (G & 1) + 4 * (s & 3);
       const int img = n / O::PBX, nl = n % O::PBX;          // image 0 and n itself unless PARTS
-      const int c = (nl >> 3) ^ O::swz(k);
+      const int c = (nl >> 3) ^ O::template swz<HW>(k);
       rd[t] = tile_off + (uint32_t)(img * (O::BK * O::ROWB) + k * O::ROWB + c * 16 + (n & 7) * 2);
     }
   }
@@ -397,7 +400,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       // k-contiguous tile); rows are positions of the padded image, zero outside the image
       const int q = q0 + i * C::NT;
       const int row = q / OA::CPR;
-      const int c = (q % OA::CPR) ^ OA::swz(row);
+      const int c = (q % OA::CPR) ^ OA::template swz<HW>(row);
       const int jj = p_j0 + row;
       const int ihp = jj / p.cWp;
       const int ih = ihp - p.cph, iw = jj - ihp * p.cWp - p.cpw;
@@ -411,7 +414,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
     la.rsrc = HW::make_rsrc(p.A, (int)p.a_span);
     la.voff = la.voff_t = la.step = la.kstep = 0;
     const int r = q0 / OA::CPR, ph = q0 % OA::CPR;
-    const int c = ph ^ OA::swz(r);
+    const int c = ph ^ OA::template swz<HW>(r);
     if constexpr (C::AM == 2) {
       // C is any multiple of 8: a chunk of 8 channels still lies inside one tap, but the chunks
       // of a k-tile may belong to different taps, so (r, s, c0) are per lane and start at the
@@ -536,8 +539,8 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
   // addresses are fixed per kernel; cur* = slot base + lane address is refreshed once per
   // k-tile so that every read is "register + immediate".
   uint32_t rdA[OA::NRD], rdB[OB::NRD];
-  setup_reader<OA>(lane, wm, 0, rdA);
-  setup_reader<OB>(lane, wn, A_BYTES, rdB);
+  setup_reader<OA, HW>(lane, wm, 0, rdA);
+  setup_reader<OB, HW>(lane, wn, A_BYTES, rdB);
   uint32_t curA[OA::NRD], curB[OB::NRD];
   int tap_r = 0, tap_s = 0, tap_n = 0;        // AM == 3: filter tap of the k-tile read next
   auto set_read_slot = [&](uint32_t sbase) {
@@ -548,7 +551,7 @@ __global__ void __launch_bounds__(C::NT) alcop_mainloop(const Params p)
       const int row = wm * WM + (lane & 31) + shift;
 #pragma unroll
       for (int ki = 0; ki < OA::NRD; ki++)
-        curA[ki] = patch_base + (uint32_t)(row * (BK * 2) + (((2 * ki + (lane >> 5)) ^ OA::swz(row)) * 16));
+        curA[ki] = patch_base + (uint32_t)(row * (BK * 2) + (((2 * ki + (lane >> 5)) ^ OA::template swz<HW>(row)) * 16));
       tap_n++;
       if (++tap_s == p.cS) { tap_s = 0; tap_r++; }
     } else {

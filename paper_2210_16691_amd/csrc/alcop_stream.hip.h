@@ -146,7 +146,7 @@ __global__ void __launch_bounds__(C::NT) alcop_stream(const Params p)
       } else {
         rsA = HW::make_rsrc(p.A, (int)p.a_span);
         const int r = q0 / OA::CPR, ph = q0 % OA::CPR;
-        const int c = ph ^ OA::swz(r);
+        const int c = ph ^ OA::template swz<HW>(r);
 #pragma unroll
         for (int i = 0; i < NLA; i++) {
           const int m = tm * BM + r + i * OA::RSTEP;
@@ -217,8 +217,8 @@ __global__ void __launch_bounds__(C::NT) alcop_stream(const Params p)
     // =============================== consumer wave ===========================================
     const int wm = wave % C::WAVES_M, wn = wave / C::WAVES_M;
     uint32_t rdA[OA::NRD], rdB[OB::NRD];
-    setup_reader<OA>(lane, wm, 0, rdA);
-    setup_reader<OB>(lane, wn, A_BYTES, rdB);
+    setup_reader<OA, HW>(lane, wm, 0, rdA);
+    setup_reader<OB, HW>(lane, wn, A_BYTES, rdB);
     uint32_t curA[OA::NRD], curB[OB::NRD];
     constexpr int NRI = OA::NRI + OB::NRI;
     auto read_one = [&](int ki, int r, u32x4(&fa)[TM], u32x4(&fb)[TN]) __attribute__((always_inline)) {

@@ -12,6 +12,7 @@ namespace {
 
 template <int DROP>
 struct Ablated : Gfx950 {
+  static constexpr bool kSwizzle = !(DROP & ALCOP_DIAG_NO_SWIZZLE);
   __device__ static __forceinline__ void dma16(Rsrc rsrc, uint32_t voff, uint32_t lds_dst)
   {
     if constexpr (!(DROP & ALCOP_DIAG_NO_DMA)) Gfx950::dma16(rsrc, voff, lds_dst);
@@ -97,6 +98,7 @@ hipError_t launch_cfg(int drop, const Params& p, dim3 grid)
     case 7: return launch_one<C, 7>(p, grid);
     case 16: return launch_one<C, 16>(p, grid);
     case 23: return launch_one<C, 23>(p, grid);
+    case 32: return launch_one<C, 32>(p, grid);
     default: return hipErrorInvalidValue;
   }
 }
@@ -135,7 +137,7 @@ int alcop_diag_time(int config, int drop, const void* A, const void* B, void* C,
   if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15) return -1;
   if ((double)M * K * 2 >= 2147483648.0 || (double)K * N * 2 >= 2147483648.0) return -1;
   if (drop != 0 && drop != 1 && drop != 2 && drop != 4 && drop != 8 && drop != 3 && drop != 6 && drop != 7 &&
-      drop != 16 && drop != 23)
+      drop != 16 && drop != 23 && drop != 32)
     return -1;
   Params p;
   std::memset(&p, 0, sizeof(p));

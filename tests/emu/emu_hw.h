@@ -281,6 +281,7 @@ struct Rsrc {
 };
 
 struct Emu {
+  static constexpr bool kSwizzle = true;
   using Rsrc = emu::Rsrc;
 
   static int lane_id() { return blk()->cur & 63; }
