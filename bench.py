@@ -134,7 +134,7 @@ def main():
                           "gbs_algorithmic": round(byts / us / 1e3, 1), "steps": a.steps}))
         return
 
-    if a.workload not in ("gemm2048", "gemm8192", "ffn1", "ffn2"):
+    if a.workload not in ("gemm2048", "gemm4096", "gemm8192", "ffn1", "ffn2"):
         sys.exit("bench.py: the tuned headline run supports the GEMM configurations; use --sched for " + a.workload)
     cfg, A, B = wl.make_inputs(a.workload)
     M, N, K = cfg["M"], cfg["N"], cfg["K"]
@@ -461,7 +461,7 @@ def other_shapes(al, wl, torch, dev, variants=False):
     """Tuned (top-10 by the model) time of the remaining configurations; context for the headline."""
     res = {}
     stream = torch.cuda.current_stream()
-    for name in ("ffn1", "ffn2", "gemm8192", "bmm_qk", "bmm_pv", "conv56", "conv14", "mm_rn50_fc",
+    for name in ("ffn1", "ffn2", "gemm4096", "gemm8192", "bmm_qk", "bmm_pv", "conv56", "conv14", "mm_rn50_fc",
                  "bmm_gpt2_qk"):
         cfg, A, B = wl.make_inputs(name)
         Ad, Bd = A.to(dev), B.to(dev)
@@ -509,13 +509,13 @@ def vendor_context(wl, torch, dev):
     """torch.matmul (the vendor GEMM library behind it) on the same operands, timed the same way:
     context for the roofline fractions, not a target and not part of the path."""
     res = {}
-    for name in ("gemm2048", "ffn1", "ffn2", "gemm8192", "bmm_qk", "bmm_pv", "mm_rn50_fc"):
+    for name in ("gemm2048", "ffn1", "ffn2", "gemm4096", "gemm8192", "bmm_qk", "bmm_pv", "mm_rn50_fc"):
         try:
             cfg, A, B = wl.make_inputs(name)
             Ad, Bd = A.to(dev), B.to(dev)
             if cfg["kind"] == "bmm" and cfg["transB"]:
                 Bd = Bd.transpose(1, 2)
-            iters = 10 if name == "gemm8192" else 200
+            iters = 10 if name == "gemm8192" else (50 if name == "gemm4096" else 200)
             for _ in range(5):
                 torch.matmul(Ad, Bd)
             e0 = torch.cuda.Event(enable_timing=True)

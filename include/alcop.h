@@ -405,7 +405,7 @@ int alcop_model_predict(const alcop_problem* prob /* host */, const alcop_sched*
  *   of them from one (tile, wave tile, variant) family (the pipelining variants of one tile are
  *   predicted within a few percent of each other and would otherwise fill the budget); with
  *   top_k >= 8 the last trials of the budget go to the one-stage schedule of the two best-ranked
- *   tile families of the default kernels, unless the budget holds one already (pipelining slows
+ *   tile families of the tile-at-a-time kernels, unless the budget holds one already (pipelining slows
  *   some operators down, Sec. 6.2, and a static model cannot be trusted to know which);
  *   top_k == 0: time all feasible schedules (exhaustive / grid search, the 100 % reference of
  *   Sec. 6.4).

@@ -649,7 +649,7 @@ void spread_over_tiles(std::vector<Cand>& ranked, int top_k)
     std::vector<std::tuple<int, int, int, int, int, int>> fams;
     for (const Cand& cd : head) {
       const alcop_sched& s = cd.s;
-      if (s.variant != 0) continue;
+      if (s.variant == 2) continue;   // persistent kernels have no one-stage form
       const auto f = std::make_tuple(s.bm, s.bn, s.bk, s.wm, s.wn, s.variant);
       if (std::find(fams.begin(), fams.end(), f) == fams.end()) fams.push_back(f);
       if (fams.size() == 2) break;

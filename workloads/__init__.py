@@ -79,6 +79,8 @@ CONFIGS = {
     "ffn1": dict(kind="gemm", M=4096, N=3072, K=768, dtype="bf16", out="bf16", dist="uniform"),
     "ffn2": dict(kind="gemm", M=4096, N=768, K=3072, dtype="bf16", out="bf16", dist="uniform"),
     "gemm8192": dict(kind="gemm", M=8192, N=8192, K=8192, dtype="bf16", out="bf16", dist="uniform"),
+    # between the two squares, in fp16: one 256 x 256 tile per compute unit
+    "gemm4096": dict(kind="gemm", M=4096, N=4096, K=4096, dtype="f16", out="f16", dist="uniform"),
     # the shape the paper names as its best case (small output, long reduction: MM_RN50_FC, Sec. 6.1)
     # and a short-reduction batched matmul of the kind it names as its worst (GPT-2 style Q.K^T)
     "mm_rn50_fc": dict(kind="gemm", M=1024, N=64, K=2048, dtype="f16", out="f16", dist="uniform"),
@@ -93,7 +95,7 @@ CONFIGS = {
 
 
 _SEED_ORDER = ["bmm_pv", "bmm_qk", "conv14", "conv56", "ffn1", "ffn2", "gemm2048", "gemm256",
-               "gemm256_int", "gemm8192", "mm_rn50_fc", "bmm_gpt2_qk"]
+               "gemm256_int", "gemm8192", "mm_rn50_fc", "bmm_gpt2_qk", "gemm4096"]
 
 
 def _seed(name: str, idx: int) -> int:
