@@ -205,3 +205,17 @@ def test_config_gemm8192_sampled_rows():
         torch.cuda.synchronize()
         assert bool(torch.isfinite(C).all())
         assert_close(to_f64(C[torch.from_numpy(rows).to(DEV)]), ref, "gemm8192 " + repr(s))
+
+
+def test_config_gemm4096_sampled_rows():
+    # fp16 in and out, one 256 x 256 tile per compute unit: 512 seeded rows of C against the oracle
+    cfg, A, B = wl.make_inputs("gemm4096")
+    rows = np.sort(np.random.default_rng(4096).choice(4096, size=512, replace=False))
+    ref = oracle.gemm(wl.bits(A[torch.from_numpy(rows)]), wl.bits(B), oracle.F16)
+    Ad, Bd = A.to(DEV), B.to(DEV)
+    for s in [None, al.sched(256, 256, 64, 128, 128, 2, 3, 1), al.sched(128, 128, 64, 64, 64, 3, 2, 0, 1, 0, 2)]:
+        C = torch.full((4096, 4096), float("nan"), dtype=torch.float16, device=DEV)
+        al.alcop_gemm(Ad, Bd, C, s)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(C).all())
+        assert_close(to_f64(C[torch.from_numpy(rows).to(DEV)]), ref, "gemm4096 " + repr(s))
