@@ -342,3 +342,44 @@ def test_ranked_order_is_the_model_order_with_a_cap_per_tile_family():
     # no budget: the plain model order
     plain = al.alcop_sched_ranked(prob, 0, False, 0)
     assert [pred(s) for s in plain] == sorted(pred(s) for s in plain)
+
+
+def test_unaligned_entry_points_reject_bad_arguments_without_a_launch():
+    L = al.lib()
+    fake = ctypes.c_void_p(0x10000)           # never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x10001)
+    ws = ctypes.c_void_p(0x20000)
+    need = al.alcop_unaligned_workspace_bytes(2, 9, 10, 11, al.F32)
+    # three padded images: 2 x 16 x 16 halves twice, 2 x 16 x 16 floats, and 16 floats of bias
+    assert need == 1024 + 1024 + 2048 + 256
+
+    def bmm(A, B, C, batch, M, N, K, lda, ldb, ldc, it, ot, w, wbytes, tA=0, tB=0):
+        return L.alcop_bmm_unaligned(A, B, C, batch, M, N, K, lda, ldb, ldc, 200, 200, 200, tA, tB, it, ot,
+                                     None, None, w, wbytes, None)
+    assert bmm(None, fake, fake, 2, 9, 10, 11, 11, 10, 10, al.F16, al.F32, ws, need) == al.ERR_NULL
+    assert bmm(fake, fake, fake, 2, 9, 10, 11, 11, 10, 10, al.F16, al.F32, None, need) == al.ERR_NULL
+    assert bmm(fake, fake, fake, 2, 9, 10, 11, 11, 10, 10, al.F32, al.F32, ws, need) == al.ERR_DTYPE
+    assert bmm(fake, fake, fake, 2, 9, 10, 11, 11, 10, 10, al.F16, 5, ws, need) == al.ERR_DTYPE
+    assert bmm(fake, fake, fake, 2, 0, 10, 11, 11, 10, 10, al.F16, al.F32, ws, need) == al.ERR_SHAPE
+    assert bmm(fake, fake, fake, 2, 9, 10, 11, 10, 10, 10, al.F16, al.F32, ws, need) == al.ERR_SHAPE   # lda < K
+    assert bmm(fake, fake, fake, 2, 9, 10, 11, 11, 10, 9, al.F16, al.F32, ws, need) == al.ERR_SHAPE    # ldc < N
+    assert bmm(fake, fake, fake, 2, 9, 10, 11, 8, 10, 10, al.F16, al.F32, ws, need, tA=1) == al.ERR_SHAPE  # A stored K x M: lda < M
+    assert bmm(odd, fake, fake, 2, 9, 10, 11, 11, 10, 10, al.F16, al.F32, ws, need) == al.ERR_ALIGN
+    assert bmm(fake, fake, ctypes.c_void_p(0x10002), 2, 9, 10, 11, 11, 10, 10, al.F16, al.F32, ws, need) == al.ERR_ALIGN
+    assert bmm(fake, fake, fake, 2, 9, 10, 11, 11, 10, 10, al.F16, al.F32, ctypes.c_void_p(0x20008), need) == al.ERR_ALIGN
+    assert bmm(fake, fake, fake, 2, 9, 10, 11, 11, 10, 10, al.F16, al.F32, ws, need - 1) == al.ERR_SIZE
+    assert bmm(fake, fake, fake, 70000, 9, 10, 11, 11, 10, 10, al.F16, al.F32, ws, 1 << 40) == al.ERR_SHAPE
+
+    def conv(x, w, y, C, K, wsp, wbytes, it=al.F16, stride=1, dil=1, H=6):
+        return L.alcop_conv2d_igemm_unaligned(x, w, y, 2, H, 6, C, K, 3, 3, stride, stride, 1, 1, dil, dil, it, al.F16,
+                                              None, None, wsp, wbytes, None)
+    cneed = al.alcop_conv2d_unaligned_workspace_bytes(2, 6, 6, 3, 5, 3, 3, (1, 1), (1, 1), (1, 1), al.F16)
+    # x: 72 pixels x 8 channels, w: 9 x 8 x 8, y: 72 x 8 (halves), bias 8 floats; 256-byte sections
+    assert cneed == 1280 + 1280 + 1280 + 256
+    assert conv(None, fake, fake, 3, 5, ws, cneed) == al.ERR_NULL
+    assert conv(fake, fake, fake, 3, 5, ws, cneed, it=al.F32) == al.ERR_DTYPE
+    assert conv(fake, fake, fake, 0, 5, ws, cneed) == al.ERR_SHAPE
+    assert conv(fake, fake, fake, 3, 5, ws, cneed, stride=0) == al.ERR_SHAPE
+    assert conv(fake, fake, fake, 3, 5, ws, cneed, dil=4, H=2) == al.ERR_SHAPE      # the dilated filter exceeds the padded image
+    assert conv(odd, fake, fake, 3, 5, ws, cneed) == al.ERR_ALIGN
+    assert conv(fake, fake, fake, 3, 5, ws, cneed - 1) == al.ERR_SIZE
