@@ -112,3 +112,22 @@ def test_batched_products(transB, shape):
         torch.cuda.synchronize()
         assert_close(to_f64(outs[0][1]), ref, repr(outs[0][0]))
         _same_bits(outs, "bmm transB=%d tile %r" % (transB, tile))
+
+
+def test_lds_swizzle_is_a_pure_permutation_same_bits_without_it():
+    # the measurement library's no-swizzle variant leaves the LDS tile images unpermuted; loader and
+    # reader agree on any permutation, so the product must come out bit for bit the same
+    from paper_2210_16691_amd import diag
+    names = diag.configs()
+    for want, dt in (("f16 128x128x64 w64x64 S4 R2 F1", "f16"), ("bf16 256x256x32 w128x64 S3 R2 F1", "bf16")):
+        i = names.index(want)
+        A = wl.uniform((512, 256), dt, 9101).to(DEV)
+        B = wl.uniform((256, 512), dt, 9102).to(DEV)
+        C0 = torch.full((512, 512), float("nan"), dtype=A.dtype, device=DEV)
+        C1 = torch.full((512, 512), float("nan"), dtype=A.dtype, device=DEV)
+        diag.alcop_diag_time(i, diag.FULL, A, B, C0, 2)
+        diag.alcop_diag_time(i, diag.NO_SWIZZLE, A, B, C1, 2)
+        torch.cuda.synchronize()
+        assert torch.equal(C0.view(torch.int16), C1.view(torch.int16)), want
+        ref = oracle.gemm(wl.bits(A.cpu()), wl.bits(B.cpu()), oracle.F16 if dt == "f16" else oracle.BF16)
+        assert_close(to_f64(C1), ref, want)
