@@ -491,6 +491,15 @@ int alcop_time(const alcop_problem* prob /* host */, const void* A, const void* 
                int warmup, int iters, double* mean_us /* host */, void* hip_stream);
 
 /* Static string for a status code. */
+/*
+ * Optional: does now, on the current device, what the first call of each entry point would do
+ * besides launching (opting every kernel in to its LDS size, looking up the device array of
+ * alcop_gemm_splitk_static, reading the compute-unit count).  After it, a first call is as cheap
+ * as any other and may be recorded into a HIP graph without an eager call before the capture.
+ * Launches nothing, allocates nothing.  Returns ALCOP_OK or ALCOP_ERR_LAUNCH (no usable device).
+ */
+int alcop_init(void);
+
 const char* alcop_strerror(int code);
 
 /* Library version, and the GPU architecture string it was compiled for ("gfx950"). */

@@ -27,7 +27,7 @@ EXPORTS = [
     "alcop_sched_auto", "alcop_cache_save", "alcop_cache_load",
     "alcop_corrector_features", "alcop_corrector_fit", "alcop_splitk_workspace_bytes", "alcop_gemm_splitk", "alcop_gemm_splitk_static", "alcop_conv2d_igemm_splitk", "alcop_splitk_auto", "alcop_splitk_space", "alcop_tune_splitk", "alcop_conv2d_igemm_krsc", "alcop_conv2d_igemm_fused", "alcop_conv2d_igemm_dilated", "alcop_sched_variants", "alcop_sched_ranked",
     "alcop_unaligned_workspace_bytes", "alcop_bmm_unaligned", "alcop_conv2d_unaligned_workspace_bytes",
-    "alcop_conv2d_igemm_unaligned",
+    "alcop_conv2d_igemm_unaligned", "alcop_init",
 ]
 
 
@@ -146,6 +146,8 @@ def _declare(L: ctypes.CDLL) -> ctypes.CDLL:
     L.alcop_splitk_space.argtypes = [pp, sp, i]
     L.alcop_splitk_auto.restype = i
     L.alcop_splitk_auto.argtypes = [pp, i, sp, ip, dp]
+    L.alcop_init.restype = i
+    L.alcop_init.argtypes = []
     L.alcop_strerror.restype = ctypes.c_char_p
     L.alcop_strerror.argtypes = [i]
     L.alcop_version.restype = ctypes.c_char_p
@@ -161,6 +163,11 @@ def lib() -> ctypes.CDLL:
             raise ImportError("libalcop.so is not built: run `python -m paper_2210_16691_amd.build`")
         _lib = _declare(ctypes.CDLL(LIB_PATH))
     return _lib
+
+
+def alcop_init() -> None:
+    """Does ahead of time what the first call of each entry point would do besides launching."""
+    _check(lib().alcop_init(), "alcop_init")
 
 
 def strerror(code: int) -> str:

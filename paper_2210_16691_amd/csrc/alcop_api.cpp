@@ -1070,6 +1070,19 @@ int alcop_conv2d_igemm_fused(const void* x, const void* w, void* y, int N, int H
   return run(c, sched, hip_stream);
 }
 
+int alcop_init(void)
+{
+  // everything a first call would do besides launching: the LDS opt-in of every kernel, the
+  // address of the allocation-free entry point's device array, the compute-unit count
+  for (const KernelEntry& e : registry())
+    if (e.prepare && e.prepare() != hipSuccess) return ALCOP_ERR_LAUNCH;
+  void* scratch = nullptr;
+  size_t bytes = 0;
+  if (splitk_scratch(&scratch, &bytes) != hipSuccess) return ALCOP_ERR_LAUNCH;
+  (void)compute_units();
+  return ALCOP_OK;
+}
+
 size_t alcop_unaligned_workspace_bytes(int batch, int M, int N, int K, alcop_dtype out)
 {
   if (batch <= 0 || M <= 0 || N <= 0 || K <= 0) return 0;

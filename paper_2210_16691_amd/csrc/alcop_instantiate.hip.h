@@ -7,12 +7,12 @@
 
 namespace alcop {
 
+// LDS rings above the default 64 KB per-block limit need an explicit opt-in (the patch
+// convolution sizes its LDS per call, up to the 160 KB a block can have).  Once per kernel and
+// process; concurrent first callers wait for the one that sets it.
 template <class C>
-hipError_t launch_instance(const Params& p, dim3 grid, hipStream_t st)
+hipError_t prepare_instance()
 {
-  // LDS rings above the default 64 KB per-block limit need an explicit opt-in (the patch
-  // convolution sizes its LDS per call, up to the 160 KB a block can have).  Once per kernel
-  // and process; concurrent first launches wait for the one that sets it.
   static std::once_flag once;
   static hipError_t attr_rc = hipSuccess;
   std::call_once(once, [] {
@@ -20,7 +20,14 @@ hipError_t launch_instance(const Params& p, dim3 grid, hipStream_t st)
                                   hipFuncAttributeMaxDynamicSharedMemorySize,
                                   C::AM == 3 ? 160 * 1024 : C::LDS_BYTES);
   });
-  if (attr_rc != hipSuccess) return attr_rc;
+  return attr_rc;
+}
+
+template <class C>
+hipError_t launch_instance(const Params& p, dim3 grid, hipStream_t st)
+{
+  const hipError_t rc = prepare_instance<C>();
+  if (rc != hipSuccess) return rc;
   alcop_mainloop<C, Gfx950><<<grid, dim3(C::NT), dynamic_lds_bytes<C>(p), st>>>(p);
   return hipGetLastError();
 }
@@ -46,7 +53,7 @@ void add_instance(std::vector<KernelEntry>& t)
   if constexpr (instance_feasible(BM, BN, BK, WM, WN, S, R, F, PF)) {
     using C = KCfg<DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF>;
     t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, R, F, BL, AM, AL, SK, PF, 0, C::LDS_BYTES, C::NT,
-                            C::L, C::PATCH_OFF, &launch_instance<C>});
+                            C::L, C::PATCH_OFF, &launch_instance<C>, &prepare_instance<C>});
   }
 }
 

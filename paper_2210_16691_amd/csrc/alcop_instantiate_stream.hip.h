@@ -8,7 +8,7 @@ namespace alcop {
 
 // Persistent producer / consumer kernels (schedule variant 2).
 template <class C>
-hipError_t launch_stream(const Params& p, dim3 grid, hipStream_t st)
+hipError_t prepare_stream()
 {
   static std::once_flag once;
   static hipError_t attr_rc = hipSuccess;
@@ -16,7 +16,14 @@ hipError_t launch_stream(const Params& p, dim3 grid, hipStream_t st)
     attr_rc = hipFuncSetAttribute((const void*)alcop_stream<C, Gfx950>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
   });
-  if (attr_rc != hipSuccess) return attr_rc;
+  return attr_rc;
+}
+
+template <class C>
+hipError_t launch_stream(const Params& p, dim3 grid, hipStream_t st)
+{
+  const hipError_t rc = prepare_stream<C>();
+  if (rc != hipSuccess) return rc;
   alcop_stream<C, Gfx950><<<grid, dim3(C::NT), C::LDS_BYTES, st>>>(p);
   return hipGetLastError();
 }
@@ -38,7 +45,7 @@ void add_stream(std::vector<KernelEntry>& t)
   if constexpr (stream_feasible(BM, BN, BK, WM, WN, S)) {
     using C = SCfg<DT, BM, BN, BK, WM, WN, S, BL, AM, AL, FU>;
     t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, 2, FU, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT,
-                            C::L, 0, &launch_stream<C>});
+                            C::L, 0, &launch_stream<C>, &prepare_stream<C>});
   }
 }
 

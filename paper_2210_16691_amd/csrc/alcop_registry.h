@@ -17,6 +17,9 @@ struct KernelEntry {
   int lds_bytes, threads, loads_per_stage;
   int patch_off;   // am == 3: LDS offset of the input patch (its size is per call)
   hipError_t (*launch)(const Params&, dim3, hipStream_t);
+  // what the first launch would do besides launching (the opt-in to the kernel's LDS size), so
+  // that alcop_init can do it ahead of time; may be null
+  hipError_t (*prepare)() = nullptr;
 };
 
 // Sub-tables, one per source shard (compiled in parallel).

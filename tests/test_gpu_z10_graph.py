@@ -54,3 +54,30 @@ def test_captured_launches_replay_bit_identically():
         torch.cuda.synchronize()
         for got, ref, what in zip((C1, C2, C3), want, ("gemm", "split-K static", "persistent bmm")):
             assert torch.equal(got.view(torch.int16), ref.view(torch.int16)), (what, rep)
+
+
+def test_capture_without_an_eager_call_after_alcop_init():
+    al.alcop_init()
+    M, N, K = 512, 384, 256
+    A = wl.uniform((M, K), "bf16", 9501).to(DEV)
+    B = wl.uniform((K, N), "bf16", 9502).to(DEV)
+    C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+    s = al.sched(256, 192, 64, 64, 96, 2, 2, 1)      # a kernel no other call of this file launches
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            al.alcop_gemm(A, B, C, s, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        got = C.clone()
+        C.fill_(float("nan"))
+        al.alcop_gemm(A, B, C, s)
+        torch.cuda.synchronize()
+        assert torch.equal(got.view(torch.int16), C.view(torch.int16)), rep
+        A.copy_(wl.uniform((M, K), "bf16", 9600 + rep).to(DEV))
+        C.fill_(float("nan"))

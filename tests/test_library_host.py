@@ -34,6 +34,11 @@ def test_version_and_strerror():
     assert al.strerror(-99) == "unknown status"
 
 
+def test_init_reports_a_missing_device_as_an_error():
+    # on a machine without a GPU the kernels cannot be opted in to their LDS size; with one it succeeds
+    assert al.lib().alcop_init() in (al.OK, al.ERR_LAUNCH)
+
+
 def test_null_and_bad_arguments_are_rejected_without_a_launch():
     L = al.lib()
     s = al.sched(128, 128, 64, 64, 64, 1, 1, 0)
