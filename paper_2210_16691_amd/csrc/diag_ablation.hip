@@ -6,6 +6,7 @@
 
 #include "../../include/alcop_diag.h"
 #include "alcop_gfx950.hip.h"
+#include "alcop_stream.hip.h"
 
 namespace alcop {
 namespace {
@@ -68,6 +69,7 @@ struct Config {
   const char* name;
   int dt, bm, bn, bk;
   hipError_t (*launch)(int drop, const Params& p, dim3 grid);
+  int persistent;   // 1: producer / consumer kernel, launched with one block per compute unit at most
 };
 
 template <class C, int DROP>
@@ -82,6 +84,39 @@ hipError_t launch_one(const Params& p, dim3 grid)
   }
   alcop_mainloop<C, Ablated<DROP>><<<grid, dim3(C::NT), C::LDS_BYTES, 0>>>(p);
   return hipGetLastError();
+}
+
+template <class C, int DROP>
+hipError_t launch_one_stream(const Params& p, dim3 grid)
+{
+  static bool attr = false;   // single-threaded measurement tool
+  if (!attr) {
+    hipError_t e = hipFuncSetAttribute((const void*)alcop_stream<C, Ablated<DROP>>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr = true;
+  }
+  alcop_stream<C, Ablated<DROP>><<<grid, dim3(C::NT), C::LDS_BYTES, 0>>>(p);
+  return hipGetLastError();
+}
+
+template <class C>
+hipError_t launch_cfg_stream(int drop, const Params& p, dim3 grid)
+{
+  switch (drop) {
+    case 0: return launch_one_stream<C, 0>(p, grid);
+    case 1: return launch_one_stream<C, 1>(p, grid);
+    case 2: return launch_one_stream<C, 2>(p, grid);
+    case 4: return launch_one_stream<C, 4>(p, grid);
+    case 8: return launch_one_stream<C, 8>(p, grid);
+    case 3: return launch_one_stream<C, 3>(p, grid);
+    case 6: return launch_one_stream<C, 6>(p, grid);
+    case 7: return launch_one_stream<C, 7>(p, grid);
+    case 16: return launch_one_stream<C, 16>(p, grid);
+    case 23: return launch_one_stream<C, 23>(p, grid);
+    case 32: return launch_one_stream<C, 32>(p, grid);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 template <class C>
@@ -112,6 +147,10 @@ const Config kConfigs[] = {
     {"f16 128x128x64 w64x64 S1 R1 F0", 0, 128, 128, 64, &launch_cfg<KCfg<0, 128, 128, 64, 64, 64, 1, 1, 0, 0, 0>>},
     {"bf16 256x256x32 w128x64 S3 R2 F1", 1, 256, 256, 32, &launch_cfg<KCfg<1, 256, 256, 32, 128, 64, 3, 2, 1, 0, 0>>},
     {"bf16 256x256x32 w128x64 S1 R1 F0", 1, 256, 256, 32, &launch_cfg<KCfg<1, 256, 256, 32, 128, 64, 1, 1, 0, 0, 0>>},
+    {"f16 128x128x64 w64x64 S3 persistent F0", 0, 128, 128, 64,
+     &launch_cfg_stream<SCfg<0, 128, 128, 64, 64, 64, 3, 0, 0, 0, 0>>, 1},
+    {"f16 128x128x64 w64x64 S3 persistent F1", 0, 128, 128, 64,
+     &launch_cfg_stream<SCfg<0, 128, 128, 64, 64, 64, 3, 0, 0, 0, 1>>, 1},
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 
@@ -157,7 +196,16 @@ int alcop_diag_time(int config, int drop, const void* A, const void* B, void* C,
   p.group_m = p.ntm < 8 ? p.ntm : 8;
   p.alpha = 1.0f;
   p.pf_pa = p.pf_pb = 1;
-  const dim3 grid((unsigned)(p.ntm * p.ntn), 1, 1);
+  dim3 grid((unsigned)(p.ntm * p.ntn), 1, 1);
+  if (cf.persistent) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      return -2;
+    p.sbatch = 1;
+    p.sgrid = p.ntm * p.ntn < cus ? p.ntm * p.ntn : cus;
+    grid = dim3((unsigned)p.sgrid, 1, 1);
+  }
   for (int i = 0; i < 20; i++)
     if (cf.launch(drop, p, grid) != hipSuccess) return -2;
   if (hipDeviceSynchronize() != hipSuccess) return -2;
