@@ -90,7 +90,9 @@ typedef struct {
                       /* while four consumer waves multiply and store, so the loads of the    */
                       /* next tile overlap the epilogue of this one (the paper's load / use   */
                       /* overlap, Sec. 1, carried across tiles; for short reduction axes,     */
-                      /* Sec. 6.1).  Needs stages >= 2, reg_stages = 2 (fuse_inner 0 or 1),   */
+                      /* Sec. 6.1).  Needs stages >= 2, reg_stages = 2 (fuse_inner 0 or 1)    */
+                      /* or reg_stages = 4 with fuse_inner = 1 and bk >= 64 (three fragments   */
+                      /* in flight, the barrier early in the k-tile),                           */
                       /* l2_prefetch = 0, four waves' worth of wave tiles per block tile, and */
                       /* for a convolution a k-tile that divides the channel count.  Results  */
                       /* are bit-identical to the default kernels of the same tile.  The      */
@@ -373,12 +375,14 @@ int alcop_sched_space(const alcop_problem* prob /* host */, alcop_sched* out /* 
  * The kernels outside the default space built for the problem.  They run when a caller names
  * them or asks the tuner for them (alcop_tune with variants = 1); a NULL / zero schedule never
  * resolves to one unless the tuner chose it.  They are
- *   - the schedule variants (alcop_sched.variant != 0), whose feasibility depends on more than the
+ *   - the schedule variant 1, whose feasibility depends on more than the
  *     problem description: for a convolution the variant with the input patch resident in LDS,
  *     which also needs stride 1 and a patch that fits the LDS (alcop_sched_supported only checks
  *     that such a kernel exists; the launch or the tuner checks the rest);
  *   - the kernels with bk = 128: half as many block-wide synchronisations per unit of work, but
- *     two stages of a 128 x 128 tile already fill 128 KB of LDS.
+ *     two stages of a 128 x 128 tile already fill 128 KB of LDS;
+ *   - the persistent kernels whose consumers run the deep register pipeline (variant 2 with
+ *     reg_stages = 4): measured no faster than reg_stages = 2 on any shape tried.
  */
 int alcop_sched_variants(const alcop_problem* prob /* host */, alcop_sched* out /* host */, int cap);
 

@@ -139,9 +139,9 @@ int check_sched(const alcop_problem& p, const alcop_sched& s, const KernelEntry*
       !(s.variant == 1 && p.op == ALCOP_OP_CONV2D && !p.transB && p.conv_C == s.bk && sk == 0))
     return ALCOP_ERR_SCHED;
   // variant 2, the persistent producer / consumer kernels: two register stages (fused across
-  // k-tiles and tiles, or restarted per k-tile), no L2 touches, no split-K; convolutions with one
-  // tap per k-tile
-  if (s.variant == 2 && (s.reg_stages != 2 || s.l2_prefetch != 0 || sk != 0 ||
+  // k-tiles and tiles, or restarted per k-tile) or four (three fragments in flight, fused, k-tiles
+  // of 64 and more); no L2 touches, no split-K; convolutions with one tap per k-tile
+  if (s.variant == 2 && ((s.reg_stages != 2 && !(s.reg_stages == 4 && s.fuse_inner)) || s.l2_prefetch != 0 || sk != 0 ||
                          s.stages < 2 || (p.op == ALCOP_OP_CONV2D && p.conv_C % s.bk != 0)))
     return ALCOP_ERR_SCHED;
   const KernelEntry* e = find_entry(p, s, sk);
@@ -164,8 +164,9 @@ int default_l2_prefetch(int bk) { return 256 / bk; }
 // Kernels outside the default schedule space: offered to a caller who names them or asks the
 // tuner for them, never picked by the model on its own.  These are the patch convolution (its
 // feasibility depends on the call, not only on the problem description) and the kernels with a
-// k-tile of 128 (two stages of a 128 x 128 tile fill the LDS: a trade the tuner should measure).
-bool opt_in(const KernelEntry& e) { return e.am == 3 || e.bk == 128; }
+// k-tile of 128 (two stages of a 128 x 128 tile fill the LDS: a trade the tuner should measure),
+// and the persistent kernels with the consumers' deep register pipeline (no faster where measured).
+bool opt_in(const KernelEntry& e) { return e.am == 3 || e.bk == 128 || (e.st && e.reg_stages == 4); }
 
 // variants: 0 = the default kernels; 1 = also the opt-in kernels; 2 = only those.
 std::vector<alcop_sched> space_of(const alcop_problem& p, int sk = 0, int variants = 0)

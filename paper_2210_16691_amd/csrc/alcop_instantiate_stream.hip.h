@@ -42,9 +42,10 @@ constexpr bool stream_feasible(int bm, int bn, int bk, int wm, int wn, int s)
 template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int BL, int AM, int AL = 0, int FU = 1>
 void add_stream(std::vector<KernelEntry>& t)
 {
-  if constexpr (stream_feasible(BM, BN, BK, WM, WN, S)) {
+  if constexpr (stream_feasible(BM, BN, BK, WM, WN, S) && (FU != 2 || BK >= 64)) {
     using C = SCfg<DT, BM, BN, BK, WM, WN, S, BL, AM, AL, FU>;
-    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, 2, FU, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT,
+    // FU = 2, the deep register pipeline of the consumers, is named reg_stages = 4 (fused) by the schedules
+    t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, FU == 2 ? 4 : 2, FU ? 1 : 0, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT,
                             C::L, 0, &launch_stream<C>, &prepare_stream<C>});
   }
 }

@@ -38,6 +38,8 @@
 // The k order per accumulator is the tile-at-a-time kernel's (ko ascending, ki ascending), so
 // results are bit-identical to every schedule of that kernel with the same tile.
 #pragma once
+#include <type_traits>
+
 #include "alcop_kernel.hip.h"
 
 namespace alcop {
@@ -45,7 +47,9 @@ namespace alcop {
 // DT, tile, wave tile, stages, layouts as in KCfg; AM: 0 = A is a matrix, 1 = convolution gather
 // with one filter tap per k-tile (bk divides the channel count).
 // FU: 1 = the consumers' register pipeline is fused across k-tiles and tiles (the barrier sits inside
-// the last register step); 0 = it restarts after the barrier that opens each k-tile.
+// the last register step); 0 = it restarts after the barrier that opens each k-tile; 2 = deep:
+// three fragments in flight in four register slots, the barrier early in the k-tile (schedules
+// name it reg_stages = 4; k-tiles of 64 or 128 only).
 template <int DT_, int BM_, int BN_, int BK_, int WM_, int WN_, int S_, int BL_, int AM_, int AL_ = 0,
           int FU_ = 1>
 struct SCfg {
@@ -231,6 +235,68 @@ __global__ void __launch_bounds__(C::NT) alcop_stream(const Params p)
     constexpr int RPG = (NRI + NMM - 1) / NMM > 2 ? (NRI + NMM - 1) / NMM : 2;   // reads per gap
     const uint32_t ebase = lds0 + C::RING_BYTES + (uint32_t)wave * C::EPI_WAVE_BYTES;
     const bool fused = p.alpha != 1.0f || p.bias != nullptr || p.act != 0;
+    auto store_tile = [&](f32x16 (&acc)[TN][TM], int batch, int tm, int tn) __attribute__((always_inline)) {
+      // ---- epilogue of a tile (Table 1, epilogue term), overlapped with the producers' loads of
+      // the following tiles: convert, transpose one 32-row band at a time through this wave's own
+      // staging area, store whole 128-byte lines
+      auto epilogue = [&](auto zero) __attribute__((always_inline)) {
+        using OT = decltype(zero);
+        constexpr int OBY = sizeof(OT);
+        constexpr int RS = WN * OBY + 16;
+        constexpr int LPR = WN * OBY / 16;
+        constexpr int RPI = 64 / LPR;
+        typedef OT ot4 __attribute__((ext_vector_type(4)));
+        const int m0 = tm * BM + wm * WM, n0 = tn * BN + wn * WN;
+        char* Cb = (char*)p.C + (long)batch * p.strideC * OBY;
+#pragma unroll
+        for (int jj = 0; jj < TM; jj++) {
+#pragma unroll
+          for (int i = 0; i < TN; i++)
+#pragma unroll
+            for (int vq = 0; vq < 4; vq++) {
+              f32x4 v = {acc[i][jj][4 * vq + 0], acc[i][jj][4 * vq + 1], acc[i][jj][4 * vq + 2],
+                         acc[i][jj][4 * vq + 3]};
+              if (fused) {
+                const int n = n0 + i * 32 + 8 * vq + 4 * (lane >> 5);
+                f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+                if (p.bias != nullptr && n < p.N) bv = HW::global_load_f32x4(p.bias + n);
+#pragma unroll
+                for (int e = 0; e < 4; e++) {
+                  float t = v[e] * p.alpha + bv[e];
+                  v[e] = (p.act == 1 && t < 0.f) ? 0.f : t;
+                }
+              }
+              const ot4 h = {HW::template cvt<OT>(v[0]), HW::template cvt<OT>(v[1]),
+                             HW::template cvt<OT>(v[2]), HW::template cvt<OT>(v[3])};
+              HW::lds_write(ebase + (lane & 31) * RS + (i * 32 + 8 * vq + 4 * (lane >> 5)) * OBY, h);
+            }
+          // a row is LPR lanes long; when that does not divide 64 (a wave tile 96 wide) the last
+          // lanes of an instruction idle and the last instruction covers fewer rows
+          constexpr bool EVEN = 64 % LPR == 0 && 32 % RPI == 0;
+          constexpr int NIT = (32 + RPI - 1) / RPI;
+#pragma unroll
+          for (int t = 0; t < NIT; t++) {
+            int r = t * RPI + lane / LPR;
+            const int c16 = lane % LPR;
+            bool lane_ok = true;
+            if constexpr (!EVEN) {
+              lane_ok = lane < RPI * LPR && r < 32;
+              if (!lane_ok) r = 0;        // every lane takes part in the read; idle ones store nothing
+            }
+            const u32x4 v = HW::lds_read16(ebase + r * RS + c16 * 16);
+            const int m = m0 + jj * 32 + r;
+            const int n = n0 + c16 * (16 / OBY);
+            if (lane_ok && m < p.M && n < p.N) HW::global_store16(Cb + ((long)m * p.ldc + n) * OBY, v);
+          }
+        }
+      };
+      if (p.out_dtype == 2)
+        epilogue(0.0f);
+      else if (p.out_dtype == 0)
+        epilogue((_Float16)0);
+      else
+        epilogue((__bf16)0);
+    };
     int slot = 0;
     int i_stream = 0;                      // k-tile of the stream being consumed
     u32x4 fa[2][TM], fb[2][TN];
@@ -242,6 +308,77 @@ __global__ void __launch_bounds__(C::NT) alcop_stream(const Params p)
 #pragma unroll
       for (int i = 0; i < OB::NRD; i++) curB[i] = sbase + rdB[i];
     };
+    if constexpr (C::FU == 2) {
+      // Deep register pipeline: D = 3 fragments are in flight ahead of the one the matrix
+      // instructions consume, in R = 4 rotating register slots (a k-tile has 4 or 8 fragments, so
+      // fragment ki always lives in slot ki % 4 and every register index is a compile-time
+      // constant).  In step ki the fragment 3 steps ahead is read: (i, 3) in step 0, then
+      // (i+1, 0), (i+1, 1), ... of the NEXT k-tile.  The barrier B_{i+1} therefore stands between
+      // steps 0 and 1 of k-tile i; when a wave passes it, the fragments of the next three steps
+      // are already in registers, so no matrix instruction behind the barrier waits for LDS.
+      constexpr int R = 4, D = 3;
+      static_assert(NKI % R == 0, "the deep consumer needs a k-tile of 64 or 128");
+      u32x4 ga[R][TM], gb[R][TN];
+      int j = 0, ko = 0, batch, tm, tn;
+      decode(first, batch, tm, tn);
+      f32x16 acc[TN][TM];
+#pragma unroll
+      for (int a = 0; a < TN; a++)
+#pragma unroll
+        for (int b = 0; b < TM; b++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) acc[a][b][v] = 0.f;
+      HW::wait_lds();
+      HW::block_barrier();                 // B_0: k-tile 0 has landed for every producer wave
+      open_slot();
+#pragma unroll
+      for (int ki = 0; ki < D; ki++)
+#pragma unroll
+        for (int r = 0; r < NRI; r++) read_one(ki, r, ga[ki], gb[ki]);
+      HW::sched_fence();
+      constexpr int RPM = (NRI + NMM - 1) / NMM > 2 ? (NRI + NMM - 1) / NMM : 2;   // reads per matrix instruction
+      for (int i = 0; i < T; i++) {
+        const bool more = i + 1 < T;       // another k-tile follows in the stream (uniform)
+#pragma unroll
+        for (int ki = 0; ki < NKI; ki++) {
+          // the fragment read during this step: (i, ki + D) while that is inside this k-tile,
+          // else (i + 1, ki + D - NKI), for which B_{i+1} must have been passed
+          const bool next_tile = ki + D >= NKI;
+          if (ki + D == NKI && more) {
+            // every fragment of k-tile i has been read (the last one during the step before)
+            HW::wait_lds();                // consumer_release: my reads of k-tile i are done
+            HW::block_barrier();           // B_{i+1}: k-tile i+1 has landed, slot i may be refilled
+            open_slot();
+            HW::sched_fence();
+          }
+          const int kr = next_tile ? ki + D - NKI : ki + D;     // fragment index within its k-tile
+#pragma unroll
+          for (int m = 0; m < NMM; m++) {
+            const int a = m / TM, b = m % TM;
+            acc[a][b] = HW::template mma<C::DT>(gb[ki % R][a], ga[ki % R][b], acc[a][b]);
+            if (!next_tile || more) {
+#pragma unroll
+              for (int r = m * RPM; r < (m + 1) * RPM && r < NRI; r++)
+                read_one(kr, r, ga[(ki + D) % R], gb[(ki + D) % R]);
+            }
+            HW::sched_fence();
+          }
+        }
+        if (++ko == nko) {
+          store_tile(acc, batch, tm, tn);
+          ko = 0;
+          if (++j < my_tiles) decode(first + j * p.sgrid, batch, tm, tn);
+#pragma unroll
+          for (int a = 0; a < TN; a++)
+#pragma unroll
+            for (int b = 0; b < TM; b++)
+#pragma unroll
+              for (int v = 0; v < 16; v++) acc[a][b][v] = 0.f;
+        }
+      }
+      HW::wait_lds();
+      return;
+    }
     // The register-level pipeline runs across k-tiles and across output tiles (Fig. 3(d)): the
     // barrier B_{i+1} sits after the first matrix instructions of the LAST step of k-tile i, when
     // every fragment of k-tile i is already in registers, and the rest of that step's matrix
@@ -307,66 +444,7 @@ __global__ void __launch_bounds__(C::NT) alcop_stream(const Params p)
           }
         }
       }
-      // ---- epilogue of tile j (Table 1, epilogue term), overlapped with the producers' loads of
-      // the following tiles: convert, transpose one 32-row band at a time through this wave's own
-      // staging area, store whole 128-byte lines
-      auto epilogue = [&](auto zero) __attribute__((always_inline)) {
-        using OT = decltype(zero);
-        constexpr int OBY = sizeof(OT);
-        constexpr int RS = WN * OBY + 16;
-        constexpr int LPR = WN * OBY / 16;
-        constexpr int RPI = 64 / LPR;
-        typedef OT ot4 __attribute__((ext_vector_type(4)));
-        const int m0 = tm * BM + wm * WM, n0 = tn * BN + wn * WN;
-        char* Cb = (char*)p.C + (long)batch * p.strideC * OBY;
-#pragma unroll
-        for (int jj = 0; jj < TM; jj++) {
-#pragma unroll
-          for (int i = 0; i < TN; i++)
-#pragma unroll
-            for (int vq = 0; vq < 4; vq++) {
-              f32x4 v = {acc[i][jj][4 * vq + 0], acc[i][jj][4 * vq + 1], acc[i][jj][4 * vq + 2],
-                         acc[i][jj][4 * vq + 3]};
-              if (fused) {
-                const int n = n0 + i * 32 + 8 * vq + 4 * (lane >> 5);
-                f32x4 bv = {0.f, 0.f, 0.f, 0.f};
-                if (p.bias != nullptr && n < p.N) bv = HW::global_load_f32x4(p.bias + n);
-#pragma unroll
-                for (int e = 0; e < 4; e++) {
-                  float t = v[e] * p.alpha + bv[e];
-                  v[e] = (p.act == 1 && t < 0.f) ? 0.f : t;
-                }
-              }
-              const ot4 h = {HW::template cvt<OT>(v[0]), HW::template cvt<OT>(v[1]),
-                             HW::template cvt<OT>(v[2]), HW::template cvt<OT>(v[3])};
-              HW::lds_write(ebase + (lane & 31) * RS + (i * 32 + 8 * vq + 4 * (lane >> 5)) * OBY, h);
-            }
-          // a row is LPR lanes long; when that does not divide 64 (a wave tile 96 wide) the last
-          // lanes of an instruction idle and the last instruction covers fewer rows
-          constexpr bool EVEN = 64 % LPR == 0 && 32 % RPI == 0;
-          constexpr int NIT = (32 + RPI - 1) / RPI;
-#pragma unroll
-          for (int t = 0; t < NIT; t++) {
-            int r = t * RPI + lane / LPR;
-            const int c16 = lane % LPR;
-            bool lane_ok = true;
-            if constexpr (!EVEN) {
-              lane_ok = lane < RPI * LPR && r < 32;
-              if (!lane_ok) r = 0;        // every lane takes part in the read; idle ones store nothing
-            }
-            const u32x4 v = HW::lds_read16(ebase + r * RS + c16 * 16);
-            const int m = m0 + jj * 32 + r;
-            const int n = n0 + c16 * (16 / OBY);
-            if (lane_ok && m < p.M && n < p.N) HW::global_store16(Cb + ((long)m * p.ldc + n) * OBY, v);
-          }
-        }
-      };
-      if (p.out_dtype == 2)
-        epilogue(0.0f);
-      else if (p.out_dtype == 0)
-        epilogue((_Float16)0);
-      else
-        epilogue((__bf16)0);
+      store_tile(acc, batch, tm, tn);
     }
     HW::wait_lds();
   }

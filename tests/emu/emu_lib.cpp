@@ -38,7 +38,7 @@ template <int DT, int BM, int BN, int BK, int WM, int WN, int S, int BL, int AM,
 void add_stream(std::vector<KernelEntry>& t)
 {
   using C = SCfg<DT, BM, BN, BK, WM, WN, S, BL, AM, AL, FU>;
-  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, 2, FU, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT, C::L, 0,
+  t.push_back(KernelEntry{DT, BM, BN, BK, WM, WN, S, FU == 2 ? 4 : 2, FU ? 1 : 0, BL, AM, AL, 0, 0, 1, C::LDS_BYTES, C::NT, C::L, 0,
                           &launch_emulated_stream<C>});
 }
 
@@ -148,6 +148,12 @@ void emu_part_6(std::vector<KernelEntry>& t)
   add_stream<0, 128, 64, 64, 64, 32, 3, 0, 1>(t);      // convolution gather
   add_stream<0, 64, 64, 32, 32, 32, 4, 0, 1>(t);
   add_stream<0, 256, 64, 64, 64, 64, 2, 0, 1>(t);
+  // ... with the deep register pipeline (three fragments in flight, the barrier early in the k-tile)
+  add_stream<0, 128, 128, 64, 64, 64, 3, 0, 0, 0, 2>(t);
+  add_stream<0, 128, 128, 64, 64, 64, 2, 1, 0, 0, 2>(t);
+  add_stream<1, 64, 64, 64, 32, 32, 2, 0, 0, 0, 2>(t);
+  add_stream<0, 128, 64, 64, 64, 32, 3, 0, 1, 0, 2>(t);
+  add_stream<0, 64, 64, 128, 32, 32, 2, 0, 0, 0, 2>(t);      // eight fragments per k-tile
   // ... with the register pipeline restarted in every k-tile
   add_stream<0, 128, 128, 64, 64, 64, 3, 0, 0, 0, 0>(t);
   add_stream<0, 64, 64, 64, 32, 32, 3, 1, 0, 0, 0>(t);

@@ -652,9 +652,10 @@ def test_stream_kernels_convolution_gemm_and_fused_epilogue(monkeypatch):
     assert _exact(C, ref)
 
 
-def test_stream_kernel_planted_mistakes_are_noticed(monkeypatch):
+@pytest.mark.parametrize("reg_stages", [2, 4])
+def test_stream_kernel_planted_mistakes_are_noticed(reg_stages, monkeypatch):
     monkeypatch.setenv("ALCOP_STREAM_BLOCKS", "2")
-    s = al.sched(128, 128, 64, 64, 64, 3, 2, 1, 1, 0, 2)
+    s = al.sched(128, 128, 64, 64, 64, 3, reg_stages, 1, 1, 0, 2)   # 4: the consumers' deep register pipeline
     b, M, N, K = 2, 256, 128, 5 * 64
     A = wl.small_ints((b, M, K), "f16", 1)
     B = wl.small_ints((b, K, N), "f16", 2)

@@ -15,7 +15,9 @@ pytestmark = pytest.mark.gpu
 
 
 def _stream(prob):
-    return [s for s in al.alcop_sched_space(prob) if s.variant == 2 and al.alcop_sched_supported(prob, s) == al.OK]
+    # the default persistent kernels and the opt-in ones with the consumers' deep register pipeline
+    both = al.alcop_sched_space(prob) + al.alcop_sched_variants(prob)
+    return [s for s in both if s.variant == 2 and al.alcop_sched_supported(prob, s) == al.OK]
 
 
 @pytest.mark.parametrize("dt,transB", [("f16", False), ("f16", True), ("bf16", False)])
