@@ -51,3 +51,17 @@ void add_stream(std::vector<KernelEntry>& t)
 }
 
 }  // namespace alcop
+
+// every ring depth, the consumers' register pipeline fused across k-tiles and not
+#define ALCOP_STREAM_STAGES(T, DT, BM, BN, BK, WM, WN, BL, AM)   \
+  add_stream<DT, BM, BN, BK, WM, WN, 2, BL, AM, 0, 1>(T);        \
+  add_stream<DT, BM, BN, BK, WM, WN, 3, BL, AM, 0, 1>(T);        \
+  add_stream<DT, BM, BN, BK, WM, WN, 4, BL, AM, 0, 1>(T);        \
+  add_stream<DT, BM, BN, BK, WM, WN, 2, BL, AM, 0, 0>(T);        \
+  add_stream<DT, BM, BN, BK, WM, WN, 3, BL, AM, 0, 0>(T);        \
+  add_stream<DT, BM, BN, BK, WM, WN, 4, BL, AM, 0, 0>(T);
+// the consumers' deep register pipeline (k-tile 64): measured no faster than the two above on any
+// configuration, so these stay outside the default schedule space (alcop_sched_variants)
+#define ALCOP_STREAM_DEEP(T, DT, BM, BN, WM, WN, BL, AM)         \
+  add_stream<DT, BM, BN, 64, WM, WN, 2, BL, AM, 0, 2>(T);        \
+  add_stream<DT, BM, BN, 64, WM, WN, 3, BL, AM, 0, 2>(T);
