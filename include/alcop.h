@@ -73,8 +73,9 @@ typedef struct {
   int bm, bn, bk;     /* block tile of C (bm x bn) and reduction step bk                    */
   int wm, wn;         /* per-wavefront tile; the block runs (bm/wm)*(bn/wn) wavefronts      */
   int stages;         /* S: LDS ring depth, 1..4; 1 = load and use strictly alternate       */
-  int reg_stages;     /* R: 1 = fragment loaded then used; 2 = next fragment prefetched     */
-  int fuse_inner;     /* 1 = register pipeline runs across ko (needs R=2 and S>=2)          */
+  int reg_stages;     /* R: 1 = fragment loaded then used; 2 = next fragment prefetched;    */
+                      /* 3, 4 = R-1 fragments in flight (fused only, (R-1)*16 <= bk)        */
+  int fuse_inner;     /* 1 = register pipeline runs across ko (needs R>=2 and S>=2)         */
   int raster;         /* block -> tile order: 0 row-major, 1 XCD-grouped panels             */
   int l2_prefetch;    /* third buffer level (HBM -> L2): lines of k-tile kt+l2_prefetch are  */
                       /* touched when k-tile kt is issued; 0 = off; needs raster = 1         */
