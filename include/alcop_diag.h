@@ -27,8 +27,11 @@ enum {
   ALCOP_DIAG_NO_MFMA = 4,     /* no matrix instructions                                          */
   ALCOP_DIAG_NO_BARRIER = 8,  /* no block-wide barrier (waits on the counters stay)              */
   ALCOP_DIAG_NO_STORE = 16,   /* no global stores of C (conversion and LDS staging stay)         */
-  ALCOP_DIAG_NO_SWIZZLE = 32  /* LDS tile images not permuted: every operation stays and the    */
+  ALCOP_DIAG_NO_SWIZZLE = 32, /* LDS tile images not permuted: every operation stays and the    */
                               /* result is right, but the fragment reads meet bank conflicts    */
+  ALCOP_DIAG_COPY = 64        /* nothing dropped: a second, separately named copy of the full   */
+                              /* kernel, so that a profiler keeps runs on other operands (all   */
+                              /* zeros, say) apart from the runs of variant 0                   */
 };
 
 /* Number of kernel configurations built in, and a description of configuration i
@@ -42,7 +45,7 @@ const char* alcop_diag_config_name(int i);
  * pointers owned by the caller, 16-byte aligned, M, N multiples of the tile and K of the k-tile.
  * `iters` back-to-back launches after 20 warm-up launches, 3 repeats; writes the best mean
  * microseconds per launch.  Only the combinations 0, 1, 2, 4, 8, 16, 1|2, 2|4, 1|2|4 (what is
- * left is launch, prologue, barriers and epilogue), 1|2|4|16 and 32 are built.
+ * left is launch, prologue, barriers and epilogue), 1|2|4|16, 32 and 64 are built.
  * Returns 0, or -1 (bad argument / combination not built), -2 (HIP error).
  */
 int alcop_diag_time(int config, int drop, const void* A, const void* B, void* C, int M, int N,

@@ -115,6 +115,7 @@ hipError_t launch_cfg_stream(int drop, const Params& p, dim3 grid)
     case 16: return launch_one_stream<C, 16>(p, grid);
     case 23: return launch_one_stream<C, 23>(p, grid);
     case 32: return launch_one_stream<C, 32>(p, grid);
+    case 64: return launch_one_stream<C, 64>(p, grid);
     default: return hipErrorInvalidValue;
   }
 }
@@ -134,6 +135,7 @@ hipError_t launch_cfg(int drop, const Params& p, dim3 grid)
     case 16: return launch_one<C, 16>(p, grid);
     case 23: return launch_one<C, 23>(p, grid);
     case 32: return launch_one<C, 32>(p, grid);
+    case 64: return launch_one<C, 64>(p, grid);
     default: return hipErrorInvalidValue;
   }
 }
@@ -176,7 +178,7 @@ int alcop_diag_time(int config, int drop, const void* A, const void* B, void* C,
   if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) & 15) return -1;
   if ((double)M * K * 2 >= 2147483648.0 || (double)K * N * 2 >= 2147483648.0) return -1;
   if (drop != 0 && drop != 1 && drop != 2 && drop != 4 && drop != 8 && drop != 3 && drop != 6 && drop != 7 &&
-      drop != 16 && drop != 23 && drop != 32)
+      drop != 16 && drop != 23 && drop != 32 && drop != 64)
     return -1;
   Params p;
   std::memset(&p, 0, sizeof(p));

@@ -6,7 +6,7 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-FULL, NO_DMA, NO_LDS_READ, NO_MFMA, NO_BARRIER, NO_STORE, NO_SWIZZLE = 0, 1, 2, 4, 8, 16, 32
+FULL, NO_DMA, NO_LDS_READ, NO_MFMA, NO_BARRIER, NO_STORE, NO_SWIZZLE, COPY = 0, 1, 2, 4, 8, 16, 32, 64
 EXPORTS = ("alcop_diag_configs", "alcop_diag_config_name", "alcop_diag_time", "alcop_diag_launch_floor")
 _lib = None
 
