@@ -664,6 +664,11 @@ void spread_over_tiles(std::vector<Cand>& ranked, int top_k)
       if (std::any_of(head.begin(), head.end(), of_family)) continue;
       auto it = std::find_if(tail.begin(), tail.end(), of_family);
       if (it == tail.end()) continue;
+      // the model does not tell the one-stage schedules of a tile apart: take the one that still
+      // prefetches its fragments (R = 2), which costs nothing and is never slower
+      auto r2 = std::find_if(tail.begin(), tail.end(),
+                             [&](const Cand& cd) { return of_family(cd) && cd.s.reg_stages == 2; });
+      if (r2 != tail.end()) it = r2;
       ins.push_back(*it);
       tail.erase(it);
     }
